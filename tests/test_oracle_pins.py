@@ -1,0 +1,403 @@
+"""Pins for the fp64 CPU checker: each test fixes a part of oracle/stage_oracle.py
+to something other than itself (finite differences, an independent scalar-loop
+evaluation, closed forms, invariants, a library routine, textbook re-assembly of
+a tensor-parallel split).  None of these needs a GPU."""
+import math
+
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import loop_twin
+from oracle import stage_oracle as so
+
+RNG = np.random.default_rng(7)
+
+TINY_GPT = si.StageConfig(1, 16, 2, 2, 4, 24, 6, 2, dtype=si.DTYPE_FP32)
+TINY_GPT_ERF = TINY_GPT.replace(act=si.ACT_GELU_ERF)
+TINY_LLAMA = si.StageConfig(1, 16, 4, 2, 4, 24, 6, 2, dtype=si.DTYPE_FP32, norm=si.NORM_RMSNORM,
+                            act=si.ACT_SWIGLU, pos=si.POS_ROTARY, has_bias=0)
+TINY_CFGS = [TINY_GPT, TINY_GPT_ERF, TINY_LLAMA]
+
+
+def _params(cfg, scale=0.3):
+    # larger than the training recipe's 0.02 so that every non-linearity is well away from its linear regime
+    p = {}
+    for name, shape in si.layer_inventory(cfg):
+        a = RNG.standard_normal(shape) * scale
+        if name.endswith("_gain"):
+            a = a + 1.0
+        p[name] = a
+    return p
+
+
+# ------------------------------------------------------------------ backward vs finite differences
+@pytest.mark.parametrize("cfg", TINY_CFGS)
+def test_layer_backward_matches_central_differences(cfg):
+    p = _params(cfg)
+    x = RNG.standard_normal((cfg.seq, cfg.micro_batch, cfg.hidden))
+    dy = RNG.standard_normal(x.shape)
+    y, st = so.layer_fwd(cfg, p, x)
+    dx, gr = so.layer_bwd(cfg, p, st, dy)
+    assert set(gr) == set(p)
+
+    def loss(pp, xx):
+        return float((so.layer_fwd(cfg, pp, xx)[0] * dy).sum())
+
+    eps = 1e-6
+
+    def fd(arr, setter):
+        out = np.zeros_like(arr)
+        it = np.nditer(arr, flags=["multi_index"])
+        for _ in it:
+            idx = it.multi_index
+            old = arr[idx]
+            arr[idx] = old + eps
+            lp = setter()
+            arr[idx] = old - eps
+            lm = setter()
+            arr[idx] = old
+            out[idx] = (lp - lm) / (2 * eps)
+        return out
+
+    xv = x.copy()
+    num_dx = fd(xv, lambda: loss(p, xv))
+    assert np.abs(num_dx - dx).max() <= 1e-6 * max(1.0, np.abs(dx).max())
+    for name in p:
+        arr = p[name]
+        num = fd(arr, lambda: loss(p, x))
+        scale = max(1.0, np.abs(gr[name]).max())
+        assert np.abs(num - gr[name]).max() <= 1e-6 * scale, name
+
+
+def test_two_layer_stage_backward_matches_directional_derivative():
+    cfg = TINY_LLAMA.replace(n_layers=2)
+    layers = [_params(cfg), _params(cfg)]
+    x = RNG.standard_normal((cfg.seq, cfg.micro_batch, cfg.hidden))
+    dy = RNG.standard_normal(x.shape)
+    y, st = so.stage_fwd(cfg, layers, x)
+    dx, grads = so.stage_bwd(cfg, layers, st, dy)
+    direction = [{k: RNG.standard_normal(v.shape) for k, v in l.items()} for l in layers]
+    dirx = RNG.standard_normal(x.shape)
+    analytic = float((dx * dirx).sum()) + sum(float((grads[i][k] * direction[i][k]).sum())
+                                              for i in range(2) for k in layers[i])
+    eps = 1e-6
+
+    def at(t):
+        ls = [{k: v + t * direction[i][k] for k, v in l.items()} for i, l in enumerate(layers)]
+        return float((so.stage_fwd(cfg, ls, x + t * dirx)[0] * dy).sum())
+
+    numeric = (at(eps) - at(-eps)) / (2 * eps)
+    assert abs(numeric - analytic) <= 1e-6 * max(1.0, abs(analytic))
+
+
+# ------------------------------------------------------------------ forward vs scalar loops
+@pytest.mark.parametrize("cfg", TINY_CFGS)
+def test_forward_matches_scalar_loop_evaluation(cfg):
+    p = _params(cfg)
+    x = RNG.standard_normal((cfg.seq, cfg.micro_batch, cfg.hidden))
+    y, _ = so.layer_fwd(cfg, p, x)
+    y_loop = np.array(loop_twin.layer_forward(cfg, {k: v.tolist() for k, v in p.items()}, x.tolist()))
+    assert np.abs(y - y_loop).max() <= 1e-12 * max(1.0, np.abs(y).max())
+
+
+# ------------------------------------------------------------------ softmax / attention
+def test_softmax_rows_sum_to_one_and_future_is_exactly_zero():
+    q, k = RNG.standard_normal((9, 4)) * 3, RNG.standard_normal((9, 4)) * 3
+    p = so.causal_probs(q, k)
+    assert np.abs(p.sum(axis=1) - 1.0).max() <= 1e-14
+    assert (p[np.triu_indices(9, 1)] == 0.0).all()
+    assert p[0, 0] == 1.0
+
+
+def test_attention_first_row_returns_first_value_exactly():
+    q, k, v = (RNG.standard_normal((5, 2, 3, 4)) for _ in range(3))
+    ctx = so.attention_fwd(q, k, v)
+    assert (ctx[0] == v[0]).all()
+
+
+def test_attention_zero_queries_give_prefix_means():
+    s, b, n, d = 7, 2, 2, 4
+    k, v = RNG.standard_normal((s, b, n, d)), RNG.standard_normal((s, b, n, d))
+    ctx = so.attention_fwd(np.zeros((s, b, n, d)), k, v)
+    prefix = np.cumsum(v, axis=0) / np.arange(1, s + 1)[:, None, None, None]
+    assert np.abs(ctx - prefix).max() <= 1e-14
+
+
+def test_attention_single_position_is_identity_on_v():
+    q, k, v = (RNG.standard_normal((1, 3, 2, 4)) for _ in range(3))
+    assert (so.attention_fwd(q, k, v) == v).all()
+
+
+def test_attention_two_positions_closed_form():
+    # s = 2: row 1 mixes v0, v1 with a logistic weight of the score gap
+    d = 4
+    q, k, v = (RNG.standard_normal((2, 1, 1, d)) for _ in range(3))
+    ctx = so.attention_fwd(q, k, v)
+    gap = (q[1, 0, 0] @ (k[1, 0, 0] - k[0, 0, 0])) / math.sqrt(d)
+    w1 = 1.0 / (1.0 + math.exp(-gap))
+    assert np.abs(ctx[1, 0, 0] - ((1 - w1) * v[0, 0, 0] + w1 * v[1, 0, 0])).max() <= 1e-14
+
+
+def test_gqa_equals_mha_with_replicated_kv_heads_and_summed_kv_grads():
+    s, b, nq, nkv, d = 6, 2, 4, 2, 4
+    q = RNG.standard_normal((s, b, nq, d))
+    k, v = RNG.standard_normal((s, b, nkv, d)), RNG.standard_normal((s, b, nkv, d))
+    dctx = RNG.standard_normal(q.shape)
+    rep = lambda t: np.repeat(t, nq // nkv, axis=2)
+    ctx = so.attention_fwd(q, k, v)
+    ctx_m = so.attention_fwd(q, rep(k), rep(v))
+    assert np.abs(ctx - ctx_m).max() <= 1e-14
+    dq, dk, dv = so.attention_bwd(dctx, q, k, v)
+    dq_m, dk_m, dv_m = so.attention_bwd(dctx, q, rep(k), rep(v))
+    fold = lambda t: t.reshape(s, b, nkv, nq // nkv, d).sum(axis=3)
+    assert np.abs(dq - dq_m).max() <= 1e-13
+    assert np.abs(dk - fold(dk_m)).max() <= 1e-13
+    assert np.abs(dv - fold(dv_m)).max() <= 1e-13
+
+
+@pytest.mark.parametrize("cfg", [TINY_GPT, TINY_LLAMA])
+def test_causality_of_forward_and_backward(cfg):
+    p = _params(cfg)
+    x = RNG.standard_normal((cfg.seq, cfg.micro_batch, cfg.hidden))
+    i0 = 3
+    y, st = so.layer_fwd(cfg, p, x)
+    x2 = x.copy()
+    x2[i0] += 1.0
+    y2, _ = so.layer_fwd(cfg, p, x2)
+    assert (y2[:i0] == y[:i0]).all() and np.abs(y2[i0:] - y[i0:]).max() > 1e-3
+    dy = RNG.standard_normal(x.shape)
+    dx, _ = so.layer_bwd(cfg, p, st, dy)
+    dy2 = dy.copy()
+    dy2[:i0] += 1.0                   # changing dy at earlier positions must not reach dx at later ones
+    dx2, _ = so.layer_bwd(cfg, p, st, dy2)
+    assert np.abs(dx2[i0:] - dx[i0:]).max() <= 1e-13
+
+
+def test_batch_entries_are_independent():
+    cfg = TINY_GPT
+    p = _params(cfg)
+    x = RNG.standard_normal((cfg.seq, cfg.micro_batch, cfg.hidden))
+    y, _ = so.layer_fwd(cfg, p, x)
+    x2 = x.copy()
+    x2[:, 1] += 1.0
+    y2, _ = so.layer_fwd(cfg, p, x2)
+    assert (y2[:, 0] == y[:, 0]).all()
+
+
+# ------------------------------------------------------------------ norms
+def test_layernorm_invariants():
+    h = 32
+    x = RNG.standard_normal((5, h)) * 3 + 2
+    gain, off = RNG.standard_normal(h), RNG.standard_normal(h)
+    eps = 1e-5
+    out, xhat, rstd = so.norm_fwd(x, gain, off, so.NORM_LAYERNORM, eps)
+    assert np.abs(xhat.mean(axis=1)).max() <= 1e-14
+    var = x.var(axis=1)
+    assert np.abs((xhat ** 2).mean(axis=1) - var / (var + eps)).max() <= 1e-13
+    out_shift, _, _ = so.norm_fwd(x + 7.0, gain, off, so.NORM_LAYERNORM, eps)
+    assert np.abs(out_shift - out).max() <= 1e-12
+    # matches the textbook formula evaluated row by row with numpy's own mean/var
+    for r in range(5):
+        ref = (x[r] - np.mean(x[r])) / np.sqrt(np.var(x[r]) + eps) * gain + off
+        assert np.abs(ref - out[r]).max() <= 1e-14
+    dout = RNG.standard_normal(x.shape)
+    dx, dgain, doff = so.norm_bwd(dout, xhat, rstd, gain, so.NORM_LAYERNORM)
+    assert np.abs(dx.sum(axis=1)).max() <= 1e-13
+    # sum_h dx*xhat vanishes up to the eps term: rstd * sum(w*xhat) * eps / (var + eps)
+    w = dout * gain
+    expect = rstd[:, 0] * (w * xhat).sum(axis=1) * eps / (var + eps)
+    assert np.abs((dx * xhat).sum(axis=1) - expect).max() <= 1e-13
+    dx0 = so.norm_bwd(dout, *so.norm_fwd(x, gain, off, so.NORM_LAYERNORM, 0.0)[1:], gain, so.NORM_LAYERNORM)[0]
+    xhat0 = so.norm_fwd(x, gain, off, so.NORM_LAYERNORM, 0.0)[1]
+    assert np.abs((dx0 * xhat0).sum(axis=1)).max() <= 1e-12
+    assert np.abs(doff - dout.sum(axis=0)).max() <= 1e-14
+
+
+def test_rmsnorm_invariants():
+    h = 32
+    x = RNG.standard_normal((5, h)) * 3 + 1
+    gain = RNG.standard_normal(h)
+    eps = 1e-5
+    out, xhat, rstd = so.norm_fwd(x, gain, None, so.NORM_RMSNORM, eps)
+    ms = (x ** 2).mean(axis=1)
+    assert np.abs((xhat ** 2).mean(axis=1) - ms / (ms + eps)).max() <= 1e-14
+    dout = RNG.standard_normal(x.shape)
+    dx, _, doff = so.norm_bwd(dout, xhat, rstd, gain, so.NORM_RMSNORM)
+    assert doff is None
+    # the norm's gradient is orthogonal to x up to the eps term (exactly at eps = 0)
+    expect = ((dout * gain) * xhat).sum(axis=1) * eps / (ms + eps)
+    assert np.abs((dx * xhat).sum(axis=1) - rstd[:, 0] * expect).max() <= 1e-12
+    _, xh0, rs0 = so.norm_fwd(x, gain, None, so.NORM_RMSNORM, 0.0)
+    dx0, _, _ = so.norm_bwd(dout, xh0, rs0, gain, so.NORM_RMSNORM)
+    assert np.abs((dx0 * x).sum(axis=1)).max() <= 1e-12
+    out0, _, _ = so.norm_fwd(x, gain, None, so.NORM_RMSNORM, 0.0)
+    out0s, _, _ = so.norm_fwd(5.0 * x, gain, None, so.NORM_RMSNORM, 0.0)
+    assert np.abs(out0 - out0s).max() <= 1e-13              # scale invariance at eps = 0
+
+
+# ------------------------------------------------------------------ activations
+def test_gelu_and_silu_special_values():
+    z = np.array([0.0])
+    for kind in (so.ACT_GELU_TANH, so.ACT_GELU_ERF):
+        assert so.gelu_fwd(z, kind)[0] == 0.0
+        assert so.gelu_bwd(np.ones(1), z, kind)[0] == 0.5
+        big = np.array([12.0])
+        assert abs(so.gelu_fwd(big, kind)[0] - 12.0) <= 1e-12
+        assert abs(so.gelu_fwd(-big, kind)[0]) <= 1e-12
+    u = np.linspace(-6, 6, 2001)
+    erf_ref = np.array([0.5 * t * (1.0 + math.erf(t / math.sqrt(2.0))) for t in u])
+    assert np.abs(so.gelu_fwd(u, so.ACT_GELU_ERF) - erf_ref).max() <= 1e-15
+    assert np.abs(so.gelu_fwd(u, so.ACT_GELU_TANH) - erf_ref).max() < 1e-3     # the known gap of the tanh form
+    assert np.abs(so.gelu_fwd(u, so.ACT_GELU_TANH) - erf_ref).max() > 1e-4
+    assert so.swiglu_fwd(z, np.ones(1))[0] == 0.0
+    dgate, dup = so.swiglu_bwd(np.ones(1), z, np.ones(1))
+    assert dgate[0] == 0.5 and dup[0] == 0.0
+    t = np.array([1.7])
+    assert abs(so.swiglu_fwd(t, np.array([2.0]))[0] - 2.0 * 1.7 / (1.0 + math.exp(-1.7))) <= 1e-15
+
+
+# ------------------------------------------------------------------ rotary
+def test_rotary_properties():
+    s, d = 9, 8
+    ang = so.rotary_angles(s, d, 10000.0)
+    assert (ang[0] == 0).all() and ang[1, 0] == 1.0
+    assert abs(ang[3, 2] - 3 * 10000.0 ** (-4 / 8)) <= 1e-15
+    z = RNG.standard_normal((s, 2, 3, d))
+    r = so.rotary_apply(z, ang)
+    assert (r[0] == z[0]).all()
+    pair_norm = lambda t: t[..., : d // 2] ** 2 + t[..., d // 2:] ** 2
+    assert np.abs(pair_norm(r) - pair_norm(z)).max() <= 1e-13
+    w = RNG.standard_normal(z.shape)
+    assert abs((r * w).sum() - (z * so.rotary_apply(w, ang, -1.0)).sum()) <= 1e-12   # backward = transpose
+    # explicit 2x2 rotation on one pair
+    i, j = 5, 1
+    c, sn = math.cos(ang[i, j]), math.sin(ang[i, j])
+    assert abs(r[i, 0, 0, j] - (z[i, 0, 0, j] * c - z[i, 0, 0, j + d // 2] * sn)) <= 1e-15
+    assert abs(r[i, 0, 0, j + d // 2] - (z[i, 0, 0, j + d // 2] * c + z[i, 0, 0, j] * sn)) <= 1e-15
+    # scores depend on relative position only
+    q, k = RNG.standard_normal((1, d)), RNG.standard_normal((1, d))
+    big = so.rotary_angles(40, d, 10000.0)
+    sc = lambda iq, ik: (so.rotary_apply(q, big[iq:iq + 1]) @ so.rotary_apply(k, big[ik:ik + 1]).T).item()
+    assert abs(sc(7, 3) - sc(27, 23)) <= 1e-12
+
+
+# ------------------------------------------------------------------ collectives as identities
+def test_tensor_parallel_shards_reassemble_the_unsharded_layer():
+    """Column-split Wqkv/W1 (by heads / ffn columns) and row-split Wout/W2 over 2 ranks: the sum of the
+    ranks' partial products is the unsharded layer's (what the all-reduce would deliver)."""
+    full = si.StageConfig(1, 16, 4, 4, 4, 24, 6, 2, dtype=si.DTYPE_FP32)
+    shard = full.replace(n_q_heads=2, n_kv_heads=2, ffn=12)
+    p = _params(full)
+    x = RNG.standard_normal((full.seq, full.micro_batch, full.hidden))
+    y_full, st_full = so.layer_fwd(full, p, x)
+    d, A, h = full.head_dim, full.attn_width, full.hidden
+    attn_sum = np.zeros_like(x)
+    x1_full = st_full["x1"]
+    mlp_sum = np.zeros_like(x)
+    for r in range(2):
+        heads = slice(r * 2 * d, (r + 1) * 2 * d)
+        rows = np.r_[np.arange(A)[heads], A + np.arange(A)[heads], 2 * A + np.arange(A)[heads]]
+        cols = slice(r * 12, (r + 1) * 12)
+        ps = dict(p)
+        ps["w_qkv"], ps["b_qkv"] = p["w_qkv"][rows], p["b_qkv"][rows]
+        ps["w_out"] = p["w_out"][:, heads]
+        ps["w_fc1"], ps["b_fc1"] = p["w_fc1"][cols], p["b_fc1"][cols]
+        ps["w_fc2"] = p["w_fc2"][:, cols]
+        ps["b_out"] = np.zeros(h)
+        ps["b_fc2"] = np.zeros(h)
+        _, st = so.layer_fwd(shard, ps, x)
+        attn_sum += st["x1"] - x                       # this rank's partial ctx Wout^T
+        # MLP partial, evaluated on the full layer's x1 (what every rank holds after the first all-reduce)
+        c = st_full["c"]
+        g = so.gelu_fwd(c @ ps["w_fc1"].T + ps["b_fc1"], full.act)
+        mlp_sum += g @ ps["w_fc2"].T
+    assert np.abs(x + attn_sum + p["b_out"] - x1_full).max() <= 1e-13
+    assert np.abs(x1_full + mlp_sum + p["b_fc2"] - y_full).max() <= 1e-13
+
+
+def test_zero_matrices_leave_only_the_residual_path():
+    cfg = TINY_GPT
+    p = {k: np.zeros(shape) for k, shape in si.layer_inventory(cfg)}
+    p["norm1_gain"] += 1.0
+    p["norm2_gain"] += 1.0
+    x = RNG.standard_normal((cfg.seq, cfg.micro_batch, cfg.hidden))
+    dy = RNG.standard_normal(x.shape)
+    y, st = so.layer_fwd(cfg, p, x)
+    assert (y == x).all()
+    dx, gr = so.layer_bwd(cfg, p, st, dy)
+    assert (dx == dy).all()
+    col = dy.reshape(-1, cfg.hidden).sum(axis=0)
+    assert np.abs(gr["b_fc2"] - col).max() <= 1e-14 and np.abs(gr["b_out"] - col).max() <= 1e-14
+    for k in ("w_qkv", "w_out", "w_fc1", "w_fc2", "b_qkv", "b_fc1", "norm1_gain", "norm2_gain"):
+        assert (gr[k] == 0).all(), k
+
+
+# ------------------------------------------------------------------ Adam and bf16 rounding
+def test_adam_closed_forms():
+    lr, b1, b2, eps = 1e-3, 0.9, 0.999, 1e-8
+    p0 = RNG.standard_normal(50)
+    g = RNG.standard_normal(50) * 1e-3
+    z = np.zeros(50)
+    p1, m1, v1 = so.adam_step(p0, g, z, z, 1, lr, b1, b2, eps)
+    assert np.abs(p1 - (p0 - lr * g / (np.abs(g) + eps))).max() <= 1e-15
+    # constant gradient: the bias-corrected moments stay at g and g^2, so t steps move t times as far
+    p, m, v = p0, z, z
+    for t in range(1, 6):
+        p, m, v = so.adam_step(p, g, m, v, t, lr, b1, b2, eps)
+    assert np.abs(p - (p0 - 5 * lr * g / (np.abs(g) + eps))).max() <= 1e-14
+    # zero gradient, zero decay: nothing moves
+    pz, mz, vz = so.adam_step(p0, z, z, z, 3, lr, b1, b2, eps)
+    assert (pz == p0).all() and (mz == 0).all() and (vz == 0).all()
+    # decoupled weight decay
+    pw, _, _ = so.adam_step(p0, g, z, z, 1, lr, b1, b2, eps, weight_decay=0.1)
+    assert np.abs(pw - (p0 * (1 - lr * 0.1) - lr * g / (np.abs(g) + eps))).max() <= 1e-15
+    # gradient scale multiplies g before anything else
+    ps, ms, vs = so.adam_step(p0, g, z, z, 1, lr, b1, b2, eps, grad_scale=4.0)
+    assert np.abs(ms - 0.1 * 4 * g).max() <= 1e-18 and np.abs(vs - 0.001 * 16 * g * g).max() <= 1e-20
+    # scalar twin with non-zero state
+    m0, v0 = RNG.standard_normal(50) * 1e-4, RNG.random(50) * 1e-6
+    pa, ma, va = so.adam_step(p0, g, m0, v0, 7, lr, b1, b2, eps, 0.01, 2.0)
+    for i in range(50):
+        ref = loop_twin.adam_scalar(p0[i], g[i], m0[i], v0[i], 7, lr, b1, b2, eps, 0.01, 2.0)
+        assert abs(pa[i] - ref[0]) <= 1e-15 and abs(ma[i] - ref[1]) <= 1e-18 and abs(va[i] - ref[2]) <= 1e-20
+
+
+def test_bf16_round_to_nearest_even_on_hand_picked_patterns():
+    # (fp32 pattern, expected bf16 pattern)
+    cases = [
+        (0x3F800000, 0x3F80),   # 1.0 exact
+        (0x3F808000, 0x3F80),   # exactly half way, lower neighbour even -> stays
+        (0x3F818000, 0x3F82),   # exactly half way, lower neighbour odd -> up to even
+        (0x3F808001, 0x3F81),   # just above half way -> up
+        (0x3F807FFF, 0x3F80),   # just below half way -> down
+        (0xBF818000, 0xBF82),   # sign is carried
+        (0x3FFF8000, 0x4000),   # carry into the exponent: 1.9960938 + half ulp -> 2.0
+        (0x00000000, 0x0000),
+        (0x80000000, 0x8000),
+    ]
+    pat = np.array([c[0] for c in cases], dtype=np.uint32).view(np.float32)
+    got = so.bf16_round_nearest_even(pat)
+    assert got.tolist() == [c[1] for c in cases]
+    a = (RNG.standard_normal(10000) * 0.02).astype(np.float32)
+    back = so.bf16_to_f64(so.bf16_round_nearest_even(a))
+    assert (np.abs(back - a) <= 2.0 ** -8 * np.abs(a)).all()   # half an ulp of an 8-bit significand
+
+
+# ------------------------------------------------------------------ input recipe
+def test_input_recipe_is_seeded_and_matches_inventory():
+    cfg = si.PRESETS["tiny"]
+    a, b = si.make_layer_params(cfg, 1), si.make_layer_params(cfg, 1)
+    assert all((a[k] == b[k]).all() for k in a)
+    c = si.make_layer_params(cfg, 0)
+    assert not (a["w_qkv"] == c["w_qkv"]).all()
+    assert si.stage_param_count(cfg) == 1579520
+    assert si.stage_param_count(si.PRESETS["gpt175b"]) == 2718922752
+    flat = si.make_flat_params(cfg)
+    views = si.split_flat(cfg, flat)
+    assert (views[1]["w_fc2"] == a["w_fc2"]).all()
+    bf = si.make_layer_params(si.PRESETS["tiny"].replace(dtype=si.DTYPE_BF16), 0)
+    assert (bf["w_qkv"].view(np.uint32) & 0xFFFF == 0).all()
+    assert (si.from_bf16_bits(si.bf16_bits(bf["w_qkv"])) == bf["w_qkv"]).all()
+    x = si.make_x(cfg)
+    assert x.shape == (128, 2, 256) and abs(float(x.std()) - 1.0) < 0.01
