@@ -1,0 +1,228 @@
+"""Python binding of libtm_stage.so: argument marshalling only.
+
+Every function has the name and argument order of its C counterpart in
+include/tm_stage.h and include/tm_ops.h.  Device tensors are passed either as
+integer addresses or as objects with a ``data_ptr()`` method (torch tensors);
+this module itself does not import torch.  A non-zero status raises TmError
+with the library's message.  There is no fallback: if the shared library is
+missing, importing any entry point fails with instructions to build it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Any, List, Optional, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtm_stage.so")
+
+TM_OK, TM_EINVAL, TM_EALIGN, TM_ESIZE, TM_EARCH, TM_ELAUNCH, TM_ESTATE = 0, -1, -2, -3, -4, -5, -6
+TM_DTYPE_FP32, TM_DTYPE_BF16 = 0, 1
+TM_NORM_LAYERNORM, TM_NORM_RMSNORM = 0, 1
+TM_ACT_GELU_TANH, TM_ACT_GELU_ERF, TM_ACT_SWIGLU = 0, 1, 2
+TM_POS_NONE, TM_POS_ROTARY = 0, 1
+
+
+class TmError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"tm status {code}: {message}")
+        self.code = code
+        self.message = message
+
+
+class tm_stage_config_t(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "seq",
+                                         "micro_batch", "dtype", "norm", "act", "pos", "has_bias")] + \
+               [("norm_eps", C.c_double), ("rope_theta", C.c_double)]
+
+
+class tm_stage_buffers_t(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("params", "master", "grads", "exp_avg", "exp_avg_sq", "workspace")]
+
+
+class tm_adam_hparams_t(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("lr", "beta1", "beta2", "eps", "weight_decay", "grad_scale")] + \
+               [("zero_grads", C.c_int32)]
+
+
+EXPORTS = {
+    # name: (restype, argtypes)
+    "tm_stage_param_count": (C.c_int64, [C.POINTER(tm_stage_config_t)]),
+    "tm_stage_workspace_bytes": (C.c_int64, [C.POINTER(tm_stage_config_t)]),
+    "tm_stage_param_layout": (C.c_int, [C.POINTER(tm_stage_config_t), C.c_int, C.POINTER(C.c_char_p),
+                                        C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
+    "tm_stage_init": (C.c_int, [C.POINTER(tm_stage_config_t), C.POINTER(tm_stage_buffers_t), C.POINTER(C.c_void_p)]),
+    "tm_stage_fwd": (C.c_int, [C.c_void_p] * 4),
+    "tm_stage_bwd": (C.c_int, [C.c_void_p] * 4),
+    "tm_adam_step": (C.c_int, [C.c_void_p, C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
+    "tm_adam_step_flat": (C.c_int, [C.c_int64] + [C.c_void_p] * 5 + [C.POINTER(tm_adam_hparams_t), C.c_int64,
+                                                                       C.c_void_p]),
+    "tm_stage_destroy": (None, [C.c_void_p]),
+    "tm_last_error": (C.c_char_p, []),
+    "tm_op_linear_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 6),
+    "tm_op_linear_dgrad": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 4),
+    "tm_op_linear_wgrad": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 4),
+    "tm_op_reduce_scratch_bytes": (C.c_int64, [C.c_int64, C.c_int64]),
+    "tm_op_bias_grad": (C.c_int, [C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 4),
+    "tm_op_norm_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_double] + [C.c_void_p] * 7),
+    "tm_op_norm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 11),
+    "tm_op_act_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 3),
+    "tm_op_act_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 4),
+    "tm_op_rotary": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_double, C.c_int, C.c_void_p, C.c_void_p]),
+    "tm_op_attn_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 4),
+    "tm_op_attn_bwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 7),
+}
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the shared library on first use; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2412_12636_amd.build` "
+                              "(hipcc, gfx950); there is no fallback path")
+        handle = C.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(handle, name)
+            fn.restype = res
+            fn.argtypes = args
+        _lib = handle
+    return _lib
+
+
+def _ptr(t: Any) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _check(status: int) -> int:
+    if status < 0:
+        raise TmError(int(status), lib().tm_last_error().decode())
+    return int(status)
+
+
+def make_config(cfg: Any) -> tm_stage_config_t:
+    """Accepts a tm_stage_config_t or any object with the same attribute names."""
+    if isinstance(cfg, tm_stage_config_t):
+        return cfg
+    out = tm_stage_config_t()
+    for name, _ in tm_stage_config_t._fields_:
+        setattr(out, name, getattr(cfg, name))
+    return out
+
+
+def make_hparams(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, grad_scale=1.0,
+                 zero_grads=0) -> tm_adam_hparams_t:
+    return tm_adam_hparams_t(lr, beta1, beta2, eps, weight_decay, grad_scale, int(zero_grads))
+
+
+# ---- tm_stage.h ---------------------------------------------------------------------------------
+def tm_stage_param_count(cfg) -> int:
+    return _check(lib().tm_stage_param_count(C.byref(make_config(cfg))))
+
+
+def tm_stage_workspace_bytes(cfg) -> int:
+    return _check(lib().tm_stage_workspace_bytes(C.byref(make_config(cfg))))
+
+
+def tm_stage_param_layout(cfg) -> List[Tuple[str, int, Tuple[int, int]]]:
+    """All tensors as (name, element offset, (rows, cols))."""
+    c = make_config(cfg)
+    n = _check(lib().tm_stage_param_layout(C.byref(c), -1, None, None, None))
+    out = []
+    for i in range(n):
+        name = C.c_char_p()
+        off = C.c_int64()
+        shape = (C.c_int64 * 2)()
+        _check(lib().tm_stage_param_layout(C.byref(c), i, C.byref(name), C.byref(off), shape))
+        out.append((name.value.decode(), int(off.value), (int(shape[0]), int(shape[1]))))
+    return out
+
+
+def tm_stage_init(cfg, params, master, grads, exp_avg, exp_avg_sq, workspace) -> int:
+    """Returns the opaque handle (an integer address)."""
+    b = tm_stage_buffers_t(_ptr(params), _ptr(master), _ptr(grads), _ptr(exp_avg), _ptr(exp_avg_sq), _ptr(workspace))
+    h = C.c_void_p()
+    _check(lib().tm_stage_init(C.byref(make_config(cfg)), C.byref(b), C.byref(h)))
+    return h.value
+
+
+def tm_stage_fwd(handle: int, x_in, y_out, stream: int = 0) -> None:
+    _check(lib().tm_stage_fwd(handle, _ptr(x_in), _ptr(y_out), stream))
+
+
+def tm_stage_bwd(handle: int, dy_in, dx_out, stream: int = 0) -> None:
+    _check(lib().tm_stage_bwd(handle, _ptr(dy_in), _ptr(dx_out), stream))
+
+
+def tm_adam_step(handle: int, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:
+    _check(lib().tm_adam_step(handle, C.byref(hp), step, stream))
+
+
+def tm_adam_step_flat(n: int, p, g, m, v, p_bf16, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:
+    _check(lib().tm_adam_step_flat(n, _ptr(p), _ptr(g), _ptr(m), _ptr(v), _ptr(p_bf16), C.byref(hp), step, stream))
+
+
+def tm_stage_destroy(handle: int) -> None:
+    lib().tm_stage_destroy(handle)
+
+
+def tm_last_error() -> str:
+    return lib().tm_last_error().decode()
+
+
+# ---- tm_ops.h -----------------------------------------------------------------------------------
+def tm_op_linear_fwd(dtype, T, N, K, x, w, bias, residual, y, stream=0):
+    _check(lib().tm_op_linear_fwd(dtype, T, N, K, _ptr(x), _ptr(w), _ptr(bias), _ptr(residual), _ptr(y), stream))
+
+
+def tm_op_linear_dgrad(dtype, T, N, K, dy, w, dx, stream=0):
+    _check(lib().tm_op_linear_dgrad(dtype, T, N, K, _ptr(dy), _ptr(w), _ptr(dx), stream))
+
+
+def tm_op_linear_wgrad(dtype, T, N, K, dy, x, dw, stream=0):
+    _check(lib().tm_op_linear_wgrad(dtype, T, N, K, _ptr(dy), _ptr(x), _ptr(dw), stream))
+
+
+def tm_op_reduce_scratch_bytes(T, width) -> int:
+    return _check(lib().tm_op_reduce_scratch_bytes(T, width))
+
+
+def tm_op_bias_grad(dtype, T, N, dy, db, scratch, stream=0):
+    _check(lib().tm_op_bias_grad(dtype, T, N, _ptr(dy), _ptr(db), _ptr(scratch), stream))
+
+
+def tm_op_norm_fwd(dtype, kind, T, h, eps, x, gain, offset, out, mean, rstd, stream=0):
+    _check(lib().tm_op_norm_fwd(dtype, kind, T, h, eps, _ptr(x), _ptr(gain), _ptr(offset), _ptr(out), _ptr(mean),
+                                _ptr(rstd), stream))
+
+
+def tm_op_norm_bwd(dtype, kind, T, h, dout, x, mean, rstd, gain, dres, dx, dgain, doffset, scratch, stream=0):
+    _check(lib().tm_op_norm_bwd(dtype, kind, T, h, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gain),
+                                _ptr(dres), _ptr(dx), _ptr(dgain), _ptr(doffset), _ptr(scratch), stream))
+
+
+def tm_op_act_fwd(dtype, act, T, f, u, g, stream=0):
+    _check(lib().tm_op_act_fwd(dtype, act, T, f, _ptr(u), _ptr(g), stream))
+
+
+def tm_op_act_bwd(dtype, act, T, f, dg, u, du, stream=0):
+    _check(lib().tm_op_act_bwd(dtype, act, T, f, _ptr(dg), _ptr(u), _ptr(du), stream))
+
+
+def tm_op_rotary(dtype, seq, batch, n_heads, d, row_width, theta, inverse, buf, stream=0):
+    _check(lib().tm_op_rotary(dtype, seq, batch, n_heads, d, row_width, theta, int(inverse), _ptr(buf), stream))
+
+
+def tm_op_attn_fwd(dtype, seq, batch, nq, nkv, d, qkv, ctx, lse, stream=0):
+    _check(lib().tm_op_attn_fwd(dtype, seq, batch, nq, nkv, d, _ptr(qkv), _ptr(ctx), _ptr(lse), stream))
+
+
+def tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, qkv, ctx, dctx, lse, dvec, dqkv, stream=0):
+    _check(lib().tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, _ptr(qkv), _ptr(ctx), _ptr(dctx), _ptr(lse),
+                                _ptr(dvec), _ptr(dqkv), stream))

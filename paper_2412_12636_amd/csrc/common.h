@@ -1,0 +1,88 @@
+// Shared host/device helpers for the stage-shard kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/tm_stage.h"
+
+namespace tmk {
+
+// ---- error reporting (host) -------------------------------------------------
+int fail(int code, const char *fmt, ...);   // records the message for tm_last_error(), returns code
+int check_launch(const char *what);         // hipGetLastError() -> TM_ELAUNCH
+
+// ---- storage types -----------------------------------------------------------
+typedef __bf16 bf16;
+
+template <typename T> struct Vec;            // 16-byte vector of T
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  float v[4];
+};
+template <> struct Vec<bf16> {
+  static constexpr int N = 8;
+  bf16 v[8];
+};
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16 x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f32(float x);
+template <> __device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <> __device__ __forceinline__ bf16 from_f32<bf16>(float x) { return (bf16)x; }  // round to nearest even
+
+template <typename T> __device__ __forceinline__ void load_vec(const T *p, float (&out)[Vec<T>::N]) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  union { u32x4 raw; Vec<T> v; } u;
+  u.raw = *reinterpret_cast<const u32x4 *>(p);
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) out[i] = to_f32(u.v.v[i]);
+}
+template <typename T> __device__ __forceinline__ void store_vec(T *p, const float (&in)[Vec<T>::N]) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  union { u32x4 raw; Vec<T> v; } u;
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) u.v.v[i] = from_f32<T>(in[i]);
+  *reinterpret_cast<u32x4 *>(p) = u.raw;
+}
+
+// ---- reductions ---------------------------------------------------------------
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float wave_sum(float x) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, kWave);
+  return x;
+}
+__device__ __forceinline__ float wave_max(float x) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) x = fmaxf(x, __shfl_xor(x, off, kWave));
+  return x;
+}
+
+// Sum of two values over a block of NT threads (NT a multiple of 64).  Every thread gets the
+// result; the order of additions is fixed, so results are reproducible.  `red` holds 2*NT/64 floats.
+template <int NT> __device__ __forceinline__ void block_sum2(float &a, float &b, float *red) {
+  constexpr int NW = NT / kWave;
+  a = wave_sum(a);
+  b = wave_sum(b);
+  const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
+  __syncthreads();  // protects `red` against the previous use
+  if (l == 0) {
+    red[w] = a;
+    red[NW + w] = b;
+  }
+  __syncthreads();
+  float sa = 0.f, sb = 0.f;
+#pragma unroll
+  for (int i = 0; i < NW; ++i) {
+    sa += red[i];
+    sb += red[NW + i];
+  }
+  a = sa;
+  b = sb;
+}
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+}  // namespace tmk

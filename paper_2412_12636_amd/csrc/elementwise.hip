@@ -1,0 +1,309 @@
+// Activation (GeLU / SwiGLU) forward and backward, rotary positions, fused Adam.
+// All HBM-bound: 16-byte accesses, fp32 arithmetic.
+#include <math.h>
+
+#include "common.h"
+#include "../../include/tm_ops.h"
+
+namespace tmk {
+
+constexpr int kEwThreads = 256;
+
+__device__ __forceinline__ float gelu_tanh_f(float u) {
+  const float k = 0.7978845608028654f;  // sqrt(2/pi)
+  return 0.5f * u * (1.f + tanhf(k * (u + 0.044715f * u * u * u)));
+}
+__device__ __forceinline__ float gelu_tanh_grad_f(float u) {
+  const float k = 0.7978845608028654f;
+  const float th = tanhf(k * (u + 0.044715f * u * u * u));
+  return 0.5f * (1.f + th) + 0.5f * u * (1.f - th * th) * k * (1.f + 0.134145f * u * u);
+}
+__device__ __forceinline__ float gelu_erf_f(float u) { return 0.5f * u * (1.f + erff(u * 0.7071067811865476f)); }
+__device__ __forceinline__ float gelu_erf_grad_f(float u) {
+  const float pdf = 0.3989422804014327f * expf(-0.5f * u * u);
+  return 0.5f * (1.f + erff(u * 0.7071067811865476f)) + u * pdf;
+}
+__device__ __forceinline__ float sigmoid_f(float z) { return 1.f / (1.f + expf(-z)); }
+
+// g = gelu(u), chunked over the flat array
+template <typename T, int ACT>
+__global__ __launch_bounds__(kEwThreads) void gelu_fwd_kernel(const T *__restrict__ u, T *__restrict__ g,
+                                                             int64_t nchunk) {
+  constexpr int VN = Vec<T>::N;
+  for (int64_t ch = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; ch < nchunk;
+       ch += (int64_t)gridDim.x * kEwThreads) {
+    float a[VN];
+    load_vec<T>(u + ch * VN, a);
+#pragma unroll
+    for (int i = 0; i < VN; ++i) a[i] = (ACT == TM_ACT_GELU_TANH) ? gelu_tanh_f(a[i]) : gelu_erf_f(a[i]);
+    store_vec<T>(g + ch * VN, a);
+  }
+}
+
+// du = dg * gelu'(u); du may alias dg
+template <typename T, int ACT>
+__global__ __launch_bounds__(kEwThreads) void gelu_bwd_kernel(const T *dg, const T *__restrict__ u, T *du,
+                                                             int64_t nchunk) {
+  constexpr int VN = Vec<T>::N;
+  for (int64_t ch = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; ch < nchunk;
+       ch += (int64_t)gridDim.x * kEwThreads) {
+    float a[VN], d[VN];
+    load_vec<T>(u + ch * VN, a);
+    load_vec<T>(dg + ch * VN, d);
+#pragma unroll
+    for (int i = 0; i < VN; ++i)
+      d[i] *= (ACT == TM_ACT_GELU_TANH) ? gelu_tanh_grad_f(a[i]) : gelu_erf_grad_f(a[i]);
+    store_vec<T>(du + ch * VN, d);
+  }
+}
+
+// u[T,2f] = [gate | up]  ->  g[T,f] = silu(gate) * up ; chunks_per_row = f / VN
+template <typename T>
+__global__ __launch_bounds__(kEwThreads) void swiglu_fwd_kernel(const T *__restrict__ u, T *__restrict__ g,
+                                                               int64_t nchunk, int chunks_per_row, int f) {
+  constexpr int VN = Vec<T>::N;
+  for (int64_t ch = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; ch < nchunk;
+       ch += (int64_t)gridDim.x * kEwThreads) {
+    const int64_t row = ch / chunks_per_row;
+    const int col = (int)(ch % chunks_per_row) * VN;
+    float a[VN], b[VN];
+    load_vec<T>(u + row * 2 * f + col, a);
+    load_vec<T>(u + row * 2 * f + f + col, b);
+#pragma unroll
+    for (int i = 0; i < VN; ++i) a[i] = a[i] * sigmoid_f(a[i]) * b[i];
+    store_vec<T>(g + row * f + col, a);
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kEwThreads) void swiglu_bwd_kernel(const T *__restrict__ dg, const T *__restrict__ u,
+                                                               T *__restrict__ du, int64_t nchunk,
+                                                               int chunks_per_row, int f) {
+  constexpr int VN = Vec<T>::N;
+  for (int64_t ch = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; ch < nchunk;
+       ch += (int64_t)gridDim.x * kEwThreads) {
+    const int64_t row = ch / chunks_per_row;
+    const int col = (int)(ch % chunks_per_row) * VN;
+    float a[VN], b[VN], d[VN], dgate[VN], dup[VN];
+    load_vec<T>(u + row * 2 * f + col, a);
+    load_vec<T>(u + row * 2 * f + f + col, b);
+    load_vec<T>(dg + row * f + col, d);
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      const float sg = sigmoid_f(a[i]);
+      dup[i] = d[i] * a[i] * sg;
+      dgate[i] = d[i] * b[i] * sg * (1.f + a[i] * (1.f - sg));
+    }
+    store_vec<T>(du + row * 2 * f + col, dgate);
+    store_vec<T>(du + row * 2 * f + f + col, dup);
+  }
+}
+
+// One thread per (token row, pair index j): the angle is evaluated once in double precision
+// (positions reach 16384, where an fp32 product loses the low bits of the angle) and reused
+// for every head of the row.
+template <typename T>
+__global__ __launch_bounds__(kEwThreads) void rotary_kernel(T *buf, int64_t rows, int batch, int n_heads, int d,
+                                                           int row_width, double theta, double sign) {
+  const int half = d / 2;
+  const int64_t idx = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
+  if (idx >= rows * half) return;
+  const int64_t t = idx / half;
+  const int j = (int)(idx % half);
+  const double pos = (double)(t / batch);
+  const double ang = pos * pow(theta, -2.0 * j / d);
+  double sd, cd;
+  sincos(ang, &sd, &cd);
+  const float c = (float)cd, s = (float)(sign * sd);
+  T *row = buf + t * row_width;
+  for (int hd = 0; hd < n_heads; ++hd) {
+    const float lo = to_f32(row[hd * d + j]), hi = to_f32(row[hd * d + j + half]);
+    row[hd * d + j] = from_f32<T>(lo * c - hi * s);
+    row[hd * d + j + half] = from_f32<T>(hi * c + lo * s);
+  }
+}
+
+struct AdamScalars {
+  float lr, beta1, beta2, one_minus_beta1, one_minus_beta2, eps, weight_decay, grad_scale, inv_bc1, inv_bc2;
+};
+
+__device__ __forceinline__ void adam_one(float &p, float g, float &m, float &v, const AdamScalars &a) {
+  g *= a.grad_scale;
+  m = a.beta1 * m + a.one_minus_beta1 * g;
+  v = a.beta2 * v + a.one_minus_beta2 * g * g;
+  const float mhat = m * a.inv_bc1;
+  const float vhat = v * a.inv_bc2;
+  p = p - a.lr * (mhat / (sqrtf(vhat) + a.eps) + a.weight_decay * p);
+}
+
+// 4 elements per thread and iteration; reads g,p,m,v and writes p,m,v (+ bf16 p, + zeroed g)
+template <bool LOWP, bool ZERO>
+__global__ __launch_bounds__(kEwThreads) void adam_kernel(float *__restrict__ p, float *__restrict__ g,
+                                                         float *__restrict__ m, float *__restrict__ v,
+                                                         bf16 *__restrict__ p_lowp, int64_t n, AdamScalars a) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  const int64_t nvec = n / 4;
+  for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kEwThreads) {
+    f32x4 pv = reinterpret_cast<f32x4 *>(p)[i];
+    f32x4 gv = reinterpret_cast<const f32x4 *>(g)[i];
+    f32x4 mv = reinterpret_cast<f32x4 *>(m)[i];
+    f32x4 vv = reinterpret_cast<f32x4 *>(v)[i];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      float pk = pv[k], mk = mv[k], vk = vv[k];
+      adam_one(pk, gv[k], mk, vk, a);
+      pv[k] = pk;
+      mv[k] = mk;
+      vv[k] = vk;
+    }
+    reinterpret_cast<f32x4 *>(p)[i] = pv;
+    reinterpret_cast<f32x4 *>(m)[i] = mv;
+    reinterpret_cast<f32x4 *>(v)[i] = vv;
+    if (LOWP) {
+      bf16x4 lo;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) lo[k] = (bf16)pv[k];
+      reinterpret_cast<bf16x4 *>(p_lowp)[i] = lo;
+    }
+    if (ZERO) reinterpret_cast<f32x4 *>(g)[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // tail (n not a multiple of 4)
+  const int64_t tail = nvec * 4 + (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
+  if (tail < n) {
+    float pk = p[tail], mk = m[tail], vk = v[tail];
+    adam_one(pk, g[tail], mk, vk, a);
+    p[tail] = pk;
+    m[tail] = mk;
+    v[tail] = vk;
+    if (LOWP) p_lowp[tail] = (bf16)pk;
+    if (ZERO) g[tail] = 0.f;
+  }
+}
+
+static unsigned ew_grid(int64_t nchunk) {
+  const int64_t blocks = ceil_div(nchunk, kEwThreads);
+  const int64_t cap = 256 * 32;  // enough blocks to fill 256 compute units several times over
+  return (unsigned)(blocks < cap ? (blocks > 0 ? blocks : 1) : cap);
+}
+
+}  // namespace tmk
+
+using namespace tmk;
+
+static int check_ew(const char *what, int dtype, int64_t T, int64_t f) {
+  if (dtype != TM_DTYPE_FP32 && dtype != TM_DTYPE_BF16) return fail(TM_EINVAL, "%s: unknown dtype %d", what, dtype);
+  if (T <= 0 || f <= 0) return fail(TM_EINVAL, "%s: empty shape [%lld, %lld]", what, (long long)T, (long long)f);
+  if (f % 8) return fail(TM_ESIZE, "%s: row width %lld is not a multiple of 8", what, (long long)f);
+  return TM_OK;
+}
+
+extern "C" int tm_op_act_fwd(int dtype, int act, int64_t T, int64_t f, const void *u, void *g, void *stream) {
+  if (int e = check_ew("act_fwd", dtype, T, f)) return e;
+  if (!u || !g) return fail(TM_EINVAL, "act_fwd: NULL pointer");
+  hipStream_t s = (hipStream_t)stream;
+  const int vn = dtype == TM_DTYPE_BF16 ? 8 : 4;
+  const int64_t nchunk = T * f / vn;
+  const unsigned grid = ew_grid(nchunk);
+#define TM_LAUNCH(TT)                                                                                              \
+  if (act == TM_ACT_GELU_TANH)                                                                                     \
+    gelu_fwd_kernel<TT, TM_ACT_GELU_TANH><<<grid, kEwThreads, 0, s>>>((const TT *)u, (TT *)g, nchunk);             \
+  else if (act == TM_ACT_GELU_ERF)                                                                                 \
+    gelu_fwd_kernel<TT, TM_ACT_GELU_ERF><<<grid, kEwThreads, 0, s>>>((const TT *)u, (TT *)g, nchunk);              \
+  else if (act == TM_ACT_SWIGLU)                                                                                   \
+    swiglu_fwd_kernel<TT><<<grid, kEwThreads, 0, s>>>((const TT *)u, (TT *)g, nchunk, (int)(f / vn), (int)f);      \
+  else                                                                                                             \
+    return fail(TM_EINVAL, "act_fwd: unknown activation %d", act);
+  if (dtype == TM_DTYPE_BF16) {
+    TM_LAUNCH(bf16)
+  } else {
+    TM_LAUNCH(float)
+  }
+#undef TM_LAUNCH
+  return check_launch("act_fwd");
+}
+
+extern "C" int tm_op_act_bwd(int dtype, int act, int64_t T, int64_t f, const void *dg, const void *u, void *du,
+                             void *stream) {
+  if (int e = check_ew("act_bwd", dtype, T, f)) return e;
+  if (!u || !dg || !du) return fail(TM_EINVAL, "act_bwd: NULL pointer");
+  if (act == TM_ACT_SWIGLU && dg == du) return fail(TM_EINVAL, "act_bwd: du may not alias dg under SwiGLU");
+  hipStream_t s = (hipStream_t)stream;
+  const int vn = dtype == TM_DTYPE_BF16 ? 8 : 4;
+  const int64_t nchunk = T * f / vn;
+  const unsigned grid = ew_grid(nchunk);
+#define TM_LAUNCH(TT)                                                                                              \
+  if (act == TM_ACT_GELU_TANH)                                                                                     \
+    gelu_bwd_kernel<TT, TM_ACT_GELU_TANH><<<grid, kEwThreads, 0, s>>>((const TT *)dg, (const TT *)u, (TT *)du,     \
+                                                                      nchunk);                                    \
+  else if (act == TM_ACT_GELU_ERF)                                                                                 \
+    gelu_bwd_kernel<TT, TM_ACT_GELU_ERF><<<grid, kEwThreads, 0, s>>>((const TT *)dg, (const TT *)u, (TT *)du,      \
+                                                                     nchunk);                                     \
+  else if (act == TM_ACT_SWIGLU)                                                                                   \
+    swiglu_bwd_kernel<TT><<<grid, kEwThreads, 0, s>>>((const TT *)dg, (const TT *)u, (TT *)du, nchunk,             \
+                                                      (int)(f / vn), (int)f);                                     \
+  else                                                                                                             \
+    return fail(TM_EINVAL, "act_bwd: unknown activation %d", act);
+  if (dtype == TM_DTYPE_BF16) {
+    TM_LAUNCH(bf16)
+  } else {
+    TM_LAUNCH(float)
+  }
+#undef TM_LAUNCH
+  return check_launch("act_bwd");
+}
+
+extern "C" int tm_op_rotary(int dtype, int64_t seq, int64_t batch, int64_t n_heads, int64_t d, int64_t row_width,
+                            double theta, int inverse, void *buf, void *stream) {
+  if (dtype != TM_DTYPE_FP32 && dtype != TM_DTYPE_BF16) return fail(TM_EINVAL, "rotary: unknown dtype %d", dtype);
+  if (seq <= 0 || batch <= 0 || n_heads <= 0 || d <= 0 || !buf) return fail(TM_EINVAL, "rotary: bad argument");
+  if (d % 2 || n_heads * d > row_width) return fail(TM_ESIZE, "rotary: heads do not fit the row");
+  if (!(theta > 0.0)) return fail(TM_EINVAL, "rotary: theta must be positive");
+  hipStream_t s = (hipStream_t)stream;
+  const int64_t rows = seq * batch;
+  const int64_t n = rows * (d / 2);
+  const unsigned grid = (unsigned)ceil_div(n, kEwThreads);
+  const double sign = inverse ? -1.0 : 1.0;
+  if (dtype == TM_DTYPE_BF16)
+    rotary_kernel<bf16><<<grid, kEwThreads, 0, s>>>((bf16 *)buf, rows, (int)batch, (int)n_heads, (int)d,
+                                                    (int)row_width, theta, sign);
+  else
+    rotary_kernel<float><<<grid, kEwThreads, 0, s>>>((float *)buf, rows, (int)batch, (int)n_heads, (int)d,
+                                                     (int)row_width, theta, sign);
+  return check_launch("rotary");
+}
+
+extern "C" int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float *v, void *p_bf16,
+                                 const tm_adam_hparams_t *hp, int64_t step, void *stream) {
+  if (!hp || !p || !g || !m || !v) return fail(TM_EINVAL, "adam: NULL pointer");
+  if (n < 0) return fail(TM_EINVAL, "adam: negative length");
+  if (step < 1) return fail(TM_EINVAL, "adam: step must be >= 1 (got %lld)", (long long)step);
+  if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0))
+    return fail(TM_EINVAL, "adam: betas must lie in [0, 1)");
+  if (((uintptr_t)p | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v) & 15 || ((uintptr_t)p_bf16 & 7))
+    return fail(TM_EALIGN, "adam: arrays must be 16-byte aligned");
+  if (n == 0) return TM_OK;
+  AdamScalars a;
+  a.lr = (float)hp->lr;
+  a.beta1 = (float)hp->beta1;
+  a.beta2 = (float)hp->beta2;
+  a.one_minus_beta1 = (float)(1.0 - hp->beta1);  // differences taken in double: 1 - 0.999 in fp32 is off by 6e-5
+  a.one_minus_beta2 = (float)(1.0 - hp->beta2);
+  a.eps = (float)hp->eps;
+  a.weight_decay = (float)hp->weight_decay;
+  a.grad_scale = (float)hp->grad_scale;
+  a.inv_bc1 = (float)(1.0 / (1.0 - pow(hp->beta1, (double)step)));
+  a.inv_bc2 = (float)(1.0 / (1.0 - pow(hp->beta2, (double)step)));
+  hipStream_t s = (hipStream_t)stream;
+  const unsigned grid = ew_grid(n / 4 > 0 ? n / 4 : 1);
+  const bool lowp = p_bf16 != nullptr, zero = hp->zero_grads != 0;
+  if (lowp && zero)
+    adam_kernel<true, true><<<grid, kEwThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, n, a);
+  else if (lowp)
+    adam_kernel<true, false><<<grid, kEwThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, n, a);
+  else if (zero)
+    adam_kernel<false, true><<<grid, kEwThreads, 0, s>>>(p, g, m, v, nullptr, n, a);
+  else
+    adam_kernel<false, false><<<grid, kEwThreads, 0, s>>>(p, g, m, v, nullptr, n, a);
+  return check_launch("adam");
+}

@@ -1,0 +1,333 @@
+// LayerNorm / RMSNorm forward and backward, column reductions (bias and gain gradients).
+// HBM-bound kernels: 16-byte accesses, fp32 arithmetic, wavefront shuffles for row sums.
+#include "common.h"
+#include "../../include/tm_ops.h"
+
+namespace tmk {
+
+constexpr int kNormThreads = 256;
+constexpr int kNormMaxChunks = 8;  // 16-byte chunks per thread: hidden <= 256 * 8 * Vec::N
+
+// ---------------------------------------------------------------------------------------
+// forward: one block per token row; the row stays in registers between the passes
+// ---------------------------------------------------------------------------------------
+template <typename T, int KIND, int NCH>
+__global__ __launch_bounds__(kNormThreads) void norm_fwd_kernel(
+    const T *__restrict__ x, const T *__restrict__ gain, const T *__restrict__ offset, T *__restrict__ out,
+    float *__restrict__ mean_out, float *__restrict__ rstd_out, int h, float eps) {
+  constexpr int VN = Vec<T>::N;
+  __shared__ float red[2 * kNormThreads / kWave];
+  const int64_t row = blockIdx.x;
+  const T *xr = x + row * h;
+  T *orow = out + row * h;
+  const int nchunk = h / VN;
+
+  float vals[NCH][VN];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int ch = threadIdx.x + c * kNormThreads;
+    if (ch < nchunk) {
+      load_vec<T>(xr + ch * VN, vals[c]);
+#pragma unroll
+      for (int i = 0; i < VN; ++i) {
+        s1 += vals[c][i];
+        s2 += vals[c][i] * vals[c][i];
+      }
+    }
+  }
+  block_sum2<kNormThreads>(s1, s2, red);
+  float mu = 0.f, rstd;
+  if (KIND == TM_NORM_LAYERNORM) {
+    mu = s1 / h;
+    float q = 0.f, dummy = 0.f;  // second pass over registers: sum of squared deviations
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int ch = threadIdx.x + c * kNormThreads;
+      if (ch < nchunk) {
+#pragma unroll
+        for (int i = 0; i < VN; ++i) {
+          const float dlt = vals[c][i] - mu;
+          q += dlt * dlt;
+        }
+      }
+    }
+    block_sum2<kNormThreads>(q, dummy, red);
+    rstd = 1.0f / sqrtf(q / h + eps);
+  } else {
+    rstd = 1.0f / sqrtf(s2 / h + eps);
+  }
+  if (threadIdx.x == 0) {
+    if (mean_out) mean_out[row] = mu;
+    rstd_out[row] = rstd;
+  }
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int ch = threadIdx.x + c * kNormThreads;
+    if (ch < nchunk) {
+      float g[VN], o[VN], r[VN];
+      load_vec<T>(gain + ch * VN, g);
+      if (KIND == TM_NORM_LAYERNORM) load_vec<T>(offset + ch * VN, o);
+#pragma unroll
+      for (int i = 0; i < VN; ++i) {
+        const float xh = (vals[c][i] - mu) * rstd;
+        r[i] = (KIND == TM_NORM_LAYERNORM) ? xh * g[i] + o[i] : xh * g[i];
+      }
+      store_vec<T>(orow + ch * VN, r);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// backward: block b handles rows b, b+G, ...; each thread keeps the gain/offset gradient of
+// its own columns in registers and writes one partial row per block at the end.
+// partial layout: [G][2][h] fp32 (gain partials, then offset partials)
+// ---------------------------------------------------------------------------------------
+template <typename T, int KIND, int NCH>
+__global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
+    const T *__restrict__ dout, const T *__restrict__ x, const float *__restrict__ mean,
+    const float *__restrict__ rstd, const T *__restrict__ gain, const T *dres, T *dx,
+    float *__restrict__ partial, int64_t rows, int h) {
+  constexpr int VN = Vec<T>::N;
+  __shared__ float red[2 * kNormThreads / kWave];
+  const int nchunk = h / VN;
+  float gacc[NCH][VN], oacc[NCH][VN];
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int ch = threadIdx.x + c * kNormThreads;
+#pragma unroll
+    for (int i = 0; i < VN; ++i) gacc[c][i] = oacc[c][i] = 0.f;
+    (void)ch;
+  }
+  for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+    const float mu = (KIND == TM_NORM_LAYERNORM) ? mean[row] : 0.f;
+    const float rs = rstd[row];
+    float w[NCH][VN], xh[NCH][VN];
+    float sw = 0.f, swx = 0.f;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int ch = threadIdx.x + c * kNormThreads;
+      if (ch < nchunk) {
+        float d[VN], xv[VN], gn[VN];
+        load_vec<T>(gain + ch * VN, gn);  // cache-resident after the first row
+        load_vec<T>(dout + row * h + ch * VN, d);
+        load_vec<T>(x + row * h + ch * VN, xv);
+#pragma unroll
+        for (int i = 0; i < VN; ++i) {
+          xh[c][i] = (xv[i] - mu) * rs;
+          w[c][i] = d[i] * gn[i];
+          gacc[c][i] += d[i] * xh[c][i];
+          oacc[c][i] += d[i];
+          sw += w[c][i];
+          swx += w[c][i] * xh[c][i];
+        }
+      }
+    }
+    block_sum2<kNormThreads>(sw, swx, red);
+    const float mw = (KIND == TM_NORM_LAYERNORM) ? sw / h : 0.f;
+    const float mwx = swx / h;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const int ch = threadIdx.x + c * kNormThreads;
+      if (ch < nchunk) {
+        float r[VN];
+        if (dres) {
+          load_vec<T>(dres + row * h + ch * VN, r);
+        } else {
+#pragma unroll
+          for (int i = 0; i < VN; ++i) r[i] = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < VN; ++i) r[i] += (w[c][i] - mw - xh[c][i] * mwx) * rs;
+        store_vec<T>(dx + row * h + ch * VN, r);
+      }
+    }
+  }
+  float *pg = partial + (int64_t)blockIdx.x * 2 * h;
+#pragma unroll
+  for (int c = 0; c < NCH; ++c) {
+    const int ch = threadIdx.x + c * kNormThreads;
+    if (ch < nchunk) {
+#pragma unroll
+      for (int i = 0; i < VN; ++i) {
+        pg[ch * VN + i] = gacc[c][i];
+        pg[h + ch * VN + i] = oacc[c][i];
+      }
+    }
+  }
+}
+
+// out[c] += sum_{r<R} partial[r*ld + c], r ascending (fixed order)
+__global__ void reduce_partials_kernel(const float *__restrict__ partial, int R, int64_t ld, int n,
+                                       float *__restrict__ out) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  float s = 0.f;
+  for (int r = 0; r < R; ++r) s += partial[r * ld + c];
+  out[c] += s;
+}
+
+// ---------------------------------------------------------------------------------------
+// column sums of dy[T,N] (bias gradients): grid (column groups, row groups) -> partial[R][N]
+// ---------------------------------------------------------------------------------------
+constexpr int kColLanes = 64, kColRowsPerBlock = 4;
+
+template <typename T>
+__global__ __launch_bounds__(kColLanes *kColRowsPerBlock) void colsum_partial_kernel(
+    const T *__restrict__ dy, float *__restrict__ partial, int64_t rows, int n, int rows_per_group) {
+  constexpr int VN = Vec<T>::N;
+  __shared__ float sm[kColRowsPerBlock][kColLanes * VN];
+  const int lane = threadIdx.x % kColLanes, ry = threadIdx.x / kColLanes;
+  const int col = (blockIdx.x * kColLanes + lane) * VN;
+  const int64_t r0 = (int64_t)blockIdx.y * rows_per_group;
+  const int64_t r1 = (r0 + rows_per_group < rows) ? r0 + rows_per_group : rows;
+  float acc[VN];
+#pragma unroll
+  for (int i = 0; i < VN; ++i) acc[i] = 0.f;
+  if (col < n) {
+    for (int64_t r = r0 + ry; r < r1; r += kColRowsPerBlock) {
+      float v[VN];
+      load_vec<T>(dy + r * n + col, v);
+#pragma unroll
+      for (int i = 0; i < VN; ++i) acc[i] += v[i];
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < VN; ++i) sm[ry][lane * VN + i] = acc[i];
+  __syncthreads();
+  if (ry == 0 && col < n) {
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      float s = 0.f;
+#pragma unroll
+      for (int k = 0; k < kColRowsPerBlock; ++k) s += sm[k][lane * VN + i];
+      partial[(int64_t)blockIdx.y * n + col + i] = s;
+    }
+  }
+}
+
+static int norm_bwd_blocks(int64_t T) { return (int)(T < 256 ? T : 256); }
+static int colsum_groups(int64_t T) { return (int)(T < 32 * kColRowsPerBlock ? ceil_div(T, kColRowsPerBlock) : 32); }
+
+// chunks per thread, rounded up to an instantiated count
+static int pick_nch(int h, int vn) {
+  const int need = (int)ceil_div(h / vn, kNormThreads);
+  const int opts[] = {1, 2, 3, 4, 6, 8};
+  for (int o : opts)
+    if (need <= o) return o;
+  return -1;
+}
+#define TM_NCH_SWITCH(nch, CALL)                    \
+  switch (nch) {                                    \
+    case 1: { constexpr int NCH = 1; CALL; } break; \
+    case 2: { constexpr int NCH = 2; CALL; } break; \
+    case 3: { constexpr int NCH = 3; CALL; } break; \
+    case 4: { constexpr int NCH = 4; CALL; } break; \
+    case 6: { constexpr int NCH = 6; CALL; } break; \
+    default: { constexpr int NCH = 8; CALL; } break; \
+  }
+
+template <typename T>
+static int norm_fwd_t(int kind, int64_t rows, int h, float eps, const void *x, const void *gain, const void *offset,
+                      void *out, float *mean, float *rstd, hipStream_t s) {
+  const int nch = pick_nch(h, Vec<T>::N);
+  if (kind == TM_NORM_LAYERNORM) {
+    TM_NCH_SWITCH(nch, (norm_fwd_kernel<T, TM_NORM_LAYERNORM, NCH><<<dim3((unsigned)rows), kNormThreads, 0, s>>>(
+                           (const T *)x, (const T *)gain, (const T *)offset, (T *)out, mean, rstd, h, eps)))
+  } else {
+    TM_NCH_SWITCH(nch, (norm_fwd_kernel<T, TM_NORM_RMSNORM, NCH><<<dim3((unsigned)rows), kNormThreads, 0, s>>>(
+                           (const T *)x, (const T *)gain, nullptr, (T *)out, mean, rstd, h, eps)))
+  }
+  return check_launch("norm_fwd");
+}
+
+template <typename T>
+static int norm_bwd_t(int kind, int64_t rows, int h, const void *dout, const void *x, const float *mean,
+                      const float *rstd, const void *gain, const void *dres, void *dx, float *partial, hipStream_t s) {
+  const int G = norm_bwd_blocks(rows);
+  const int nch = pick_nch(h, Vec<T>::N);
+  if (kind == TM_NORM_LAYERNORM) {
+    TM_NCH_SWITCH(nch, (norm_bwd_kernel<T, TM_NORM_LAYERNORM, NCH><<<G, kNormThreads, 0, s>>>(
+                           (const T *)dout, (const T *)x, mean, rstd, (const T *)gain, (const T *)dres, (T *)dx,
+                           partial, rows, h)))
+  } else {
+    TM_NCH_SWITCH(nch, (norm_bwd_kernel<T, TM_NORM_RMSNORM, NCH><<<G, kNormThreads, 0, s>>>(
+                           (const T *)dout, (const T *)x, mean, rstd, (const T *)gain, (const T *)dres, (T *)dx,
+                           partial, rows, h)))
+  }
+  return check_launch("norm_bwd");
+}
+
+}  // namespace tmk
+
+using namespace tmk;
+
+static int check_width(const char *what, int dtype, int64_t T, int64_t h) {
+  if (dtype != TM_DTYPE_FP32 && dtype != TM_DTYPE_BF16) return fail(TM_EINVAL, "%s: unknown dtype %d", what, dtype);
+  if (T <= 0 || h <= 0) return fail(TM_EINVAL, "%s: empty shape [%lld, %lld]", what, (long long)T, (long long)h);
+  if (h % 8) return fail(TM_ESIZE, "%s: row width %lld is not a multiple of 8", what, (long long)h);
+  if (T > 0x7fffffffLL / 8) return fail(TM_ESIZE, "%s: %lld rows exceed the supported range", what, (long long)T);
+  return TM_OK;
+}
+
+extern "C" int64_t tm_op_reduce_scratch_bytes(int64_t T, int64_t width) {
+  if (T <= 0 || width <= 0) return TM_EINVAL;
+  const int64_t g1 = norm_bwd_blocks(T), g2 = colsum_groups(T);
+  return (g1 > g2 ? g1 : g2) * width * (int64_t)sizeof(float);
+}
+
+extern "C" int tm_op_norm_fwd(int dtype, int kind, int64_t T, int64_t h, double eps, const void *x, const void *gain,
+                              const void *offset, void *out, float *mean, float *rstd, void *stream) {
+  if (int e = check_width("norm_fwd", dtype, T, h)) return e;
+  if (kind != TM_NORM_LAYERNORM && kind != TM_NORM_RMSNORM) return fail(TM_EINVAL, "norm_fwd: unknown kind %d", kind);
+  if (!x || !gain || !out || !rstd || (kind == TM_NORM_LAYERNORM && (!offset || !mean)))
+    return fail(TM_EINVAL, "norm_fwd: NULL pointer");
+  const int64_t hmax = (int64_t)kNormThreads * kNormMaxChunks * (dtype == TM_DTYPE_BF16 ? 8 : 4);
+  if (h > hmax) return fail(TM_ESIZE, "norm_fwd: width %lld above the limit %lld", (long long)h, (long long)hmax);
+  hipStream_t s = (hipStream_t)stream;
+  return dtype == TM_DTYPE_BF16
+             ? norm_fwd_t<bf16>(kind, T, (int)h, (float)eps, x, gain, offset, out, mean, rstd, s)
+             : norm_fwd_t<float>(kind, T, (int)h, (float)eps, x, gain, offset, out, mean, rstd, s);
+}
+
+extern "C" int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x,
+                              const float *mean, const float *rstd, const void *gain, const void *dres, void *dx,
+                              float *dgain, float *doffset, void *scratch, void *stream) {
+  if (int e = check_width("norm_bwd", dtype, T, h)) return e;
+  if (kind != TM_NORM_LAYERNORM && kind != TM_NORM_RMSNORM) return fail(TM_EINVAL, "norm_bwd: unknown kind %d", kind);
+  if (!dout || !x || !rstd || !gain || !dx || !dgain || !scratch || (kind == TM_NORM_LAYERNORM && (!mean || !doffset)))
+    return fail(TM_EINVAL, "norm_bwd: NULL pointer");
+  const int64_t hmax = (int64_t)kNormThreads * kNormMaxChunks * (dtype == TM_DTYPE_BF16 ? 8 : 4);
+  if (h > hmax) return fail(TM_ESIZE, "norm_bwd: width %lld above the limit %lld", (long long)h, (long long)hmax);
+  hipStream_t s = (hipStream_t)stream;
+  float *partial = (float *)scratch;
+  int e = dtype == TM_DTYPE_BF16
+              ? norm_bwd_t<bf16>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s)
+              : norm_bwd_t<float>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s);
+  if (e) return e;
+  const int G = norm_bwd_blocks(T);
+  const int nb = (int)ceil_div(h, 256);
+  reduce_partials_kernel<<<nb, 256, 0, s>>>(partial, G, 2 * h, (int)h, dgain);
+  if (kind == TM_NORM_LAYERNORM) reduce_partials_kernel<<<nb, 256, 0, s>>>(partial + h, G, 2 * h, (int)h, doffset);
+  return check_launch("norm_bwd reduce");
+}
+
+extern "C" int tm_op_bias_grad(int dtype, int64_t T, int64_t N, const void *dy, float *db, void *scratch,
+                               void *stream) {
+  if (int e = check_width("bias_grad", dtype, T, N)) return e;
+  if (!dy || !db || !scratch) return fail(TM_EINVAL, "bias_grad: NULL pointer");
+  hipStream_t s = (hipStream_t)stream;
+  const int R = colsum_groups(T);
+  const int rows_per_group = (int)ceil_div(T, R);
+  float *partial = (float *)scratch;
+  const int vn = dtype == TM_DTYPE_BF16 ? 8 : 4;
+  dim3 grid((unsigned)ceil_div(N, (int64_t)kColLanes * vn), (unsigned)R);
+  if (dtype == TM_DTYPE_BF16)
+    colsum_partial_kernel<bf16><<<grid, kColLanes * kColRowsPerBlock, 0, s>>>((const bf16 *)dy, partial, T, (int)N,
+                                                                              rows_per_group);
+  else
+    colsum_partial_kernel<float><<<grid, kColLanes * kColRowsPerBlock, 0, s>>>((const float *)dy, partial, T, (int)N,
+                                                                               rows_per_group);
+  reduce_partials_kernel<<<(int)ceil_div(N, 256), 256, 0, s>>>(partial, R, N, (int)N, db);
+  return check_launch("bias_grad");
+}

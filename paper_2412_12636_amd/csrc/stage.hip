@@ -1,0 +1,421 @@
+// Host side of the library: configuration checks, flat parameter layout, workspace plan, and the
+// sequencing of one pipeline stage's forward pass, backward pass and Adam step.  No kernels here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <deque>
+#include <string>
+#include <vector>
+
+#include "common.h"
+#include "../../include/tm_ops.h"
+
+namespace tmk {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+int check_launch(const char *what) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(TM_ELAUNCH, "%s: %s", what, hipGetErrorString(e));
+  return TM_OK;
+}
+
+// ---- parameter layout ------------------------------------------------------------------------------
+struct TensorInfo {
+  std::string name;
+  int64_t offset, rows, cols;
+};
+
+struct LayerOffsets {  // element offsets inside one layer's block; -1 = absent
+  int64_t norm1_gain, norm1_offset, w_qkv, b_qkv, w_out, b_out, norm2_gain, norm2_offset, w_fc1, b_fc1, w_fc2, b_fc2;
+  int64_t total;
+};
+
+static int validate(const tm_stage_config_t *c) {
+  if (!c) return fail(TM_EINVAL, "config is NULL");
+  if (c->n_layers <= 0 || c->hidden <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 ||
+      c->ffn <= 0 || c->seq <= 0 || c->micro_batch <= 0)
+    return fail(TM_EINVAL, "config: every size must be positive");
+  if (c->dtype != TM_DTYPE_FP32 && c->dtype != TM_DTYPE_BF16) return fail(TM_EINVAL, "config: unknown dtype %d", c->dtype);
+  if (c->norm != TM_NORM_LAYERNORM && c->norm != TM_NORM_RMSNORM) return fail(TM_EINVAL, "config: unknown norm %d", c->norm);
+  if (c->act < TM_ACT_GELU_TANH || c->act > TM_ACT_SWIGLU) return fail(TM_EINVAL, "config: unknown activation %d", c->act);
+  if (c->pos != TM_POS_NONE && c->pos != TM_POS_ROTARY) return fail(TM_EINVAL, "config: unknown position code %d", c->pos);
+  if (!(c->norm_eps >= 0.0)) return fail(TM_EINVAL, "config: norm_eps must be >= 0");
+  if (c->pos == TM_POS_ROTARY && !(c->rope_theta > 0.0)) return fail(TM_EINVAL, "config: rope_theta must be positive");
+  if (c->hidden % 8 || c->head_dim % 8 || c->ffn % 8)
+    return fail(TM_ESIZE, "config: hidden, head_dim and ffn must be multiples of 8");
+  const int hmax = c->dtype == TM_DTYPE_BF16 ? 16384 : 8192;
+  if (c->hidden > hmax) return fail(TM_ESIZE, "config: hidden %d above the limit %d", c->hidden, hmax);
+  if (c->head_dim > 256) return fail(TM_ESIZE, "config: head_dim %d above 256", c->head_dim);
+  if (c->n_q_heads % c->n_kv_heads) return fail(TM_ESIZE, "config: n_q_heads must be a multiple of n_kv_heads");
+  const int64_t T = (int64_t)c->seq * c->micro_batch;
+  const int64_t widest = std::max<int64_t>(std::max<int64_t>(c->hidden, 2LL * c->ffn),
+                                           (int64_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim);
+  if (T * widest >= (1LL << 31) * 8) return fail(TM_ESIZE, "config: seq * micro_batch * width too large");
+  if (T > 0x7fffffffLL / 8) return fail(TM_ESIZE, "config: too many tokens");
+  const bool flash = c->dtype == TM_DTYPE_BF16 && (c->head_dim == 64 || c->head_dim == 128);
+  if (!flash && c->seq > 8192) return fail(TM_ESIZE, "config: seq above 8192 needs bf16 with head_dim 64 or 128");
+  return TM_OK;
+}
+
+static LayerOffsets layer_offsets(const tm_stage_config_t *c) {
+  const int64_t h = c->hidden, A = (int64_t)c->n_q_heads * c->head_dim;
+  const int64_t nqkv = (int64_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
+  const int64_t f = c->ffn, f1 = c->act == TM_ACT_SWIGLU ? 2 * f : f;
+  const bool ln = c->norm == TM_NORM_LAYERNORM, bias = c->has_bias != 0;
+  LayerOffsets o;
+  int64_t at = 0;
+  auto take = [&](bool present, int64_t n) {
+    if (!present) return (int64_t)-1;
+    const int64_t r = at;
+    at += n;
+    return r;
+  };
+  o.norm1_gain = take(true, h);
+  o.norm1_offset = take(ln, h);
+  o.w_qkv = take(true, nqkv * h);
+  o.b_qkv = take(bias, nqkv);
+  o.w_out = take(true, h * A);
+  o.b_out = take(bias, h);
+  o.norm2_gain = take(true, h);
+  o.norm2_offset = take(ln, h);
+  o.w_fc1 = take(true, f1 * h);
+  o.b_fc1 = take(bias, f1);
+  o.w_fc2 = take(true, h * f);
+  o.b_fc2 = take(bias, h);
+  o.total = at;
+  return o;
+}
+
+static std::vector<TensorInfo> tensor_list(const tm_stage_config_t *c) {
+  const LayerOffsets o = layer_offsets(c);
+  const int64_t h = c->hidden, A = (int64_t)c->n_q_heads * c->head_dim;
+  const int64_t nqkv = (int64_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
+  const int64_t f = c->ffn, f1 = c->act == TM_ACT_SWIGLU ? 2 * f : f;
+  std::vector<TensorInfo> out;
+  for (int l = 0; l < c->n_layers; ++l) {
+    const int64_t b = (int64_t)l * o.total;
+    auto add = [&](const char *nm, int64_t off, int64_t r, int64_t cc) {
+      if (off < 0) return;
+      out.push_back({"layer" + std::to_string(l) + "." + nm, b + off, r, cc});
+    };
+    add("norm1_gain", o.norm1_gain, h, 1);
+    add("norm1_offset", o.norm1_offset, h, 1);
+    add("w_qkv", o.w_qkv, nqkv, h);
+    add("b_qkv", o.b_qkv, nqkv, 1);
+    add("w_out", o.w_out, h, A);
+    add("b_out", o.b_out, h, 1);
+    add("norm2_gain", o.norm2_gain, h, 1);
+    add("norm2_offset", o.norm2_offset, h, 1);
+    add("w_fc1", o.w_fc1, f1, h);
+    add("b_fc1", o.b_fc1, f1, 1);
+    add("w_fc2", o.w_fc2, h, f);
+    add("b_fc2", o.b_fc2, h, 1);
+  }
+  return out;
+}
+
+// ---- workspace plan --------------------------------------------------------------------------------
+struct LayerStash {  // byte offsets into the workspace
+  int64_t x, mean1, rstd1, a, qkv, lse, ctx, x1, mean2, rstd2, c, u, g;
+};
+struct Plan {
+  std::vector<LayerStash> layer;
+  int64_t dstream[2];  // ping-pong buffers for the gradient of the residual stream, [T,h]
+  int64_t dwide;       // [T, max(f1, h)] : dg -> du, later da
+  int64_t dmid;        // [T, f]  : dg under SwiGLU (du needs its own buffer)
+  int64_t dx1;         // [T, h]
+  int64_t dnorm;       // [T, h]  : gradient w.r.t. a norm's output (dc, da)
+  int64_t dctx;        // [T, A]
+  int64_t dqkv;        // [T, Nqkv]
+  int64_t dvec;        // [b, nq, s] fp32
+  int64_t reduce;      // scratch of the column reductions
+  int64_t total;
+};
+
+static Plan make_plan(const tm_stage_config_t *c) {
+  const int64_t es = c->dtype == TM_DTYPE_BF16 ? 2 : 4;
+  const int64_t T = (int64_t)c->seq * c->micro_batch, h = c->hidden, A = (int64_t)c->n_q_heads * c->head_dim;
+  const int64_t nqkv = (int64_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
+  const int64_t f = c->ffn, f1 = c->act == TM_ACT_SWIGLU ? 2 * f : f;
+  Plan p;
+  int64_t at = 0;
+  auto take = [&](int64_t bytes) {
+    const int64_t r = at;
+    at += (bytes + 255) / 256 * 256;
+    return r;
+  };
+  const int64_t stat = (int64_t)c->micro_batch * c->n_q_heads * c->seq * 4;
+  p.layer.resize(c->n_layers);
+  for (auto &s : p.layer) {
+    s.x = take(T * h * es);
+    s.mean1 = take(T * 4);
+    s.rstd1 = take(T * 4);
+    s.a = take(T * h * es);
+    s.qkv = take(T * nqkv * es);
+    s.lse = take(stat);
+    s.ctx = take(T * A * es);
+    s.x1 = take(T * h * es);
+    s.mean2 = take(T * 4);
+    s.rstd2 = take(T * 4);
+    s.c = take(T * h * es);
+    s.u = take(T * f1 * es);
+    s.g = take(T * f * es);
+  }
+  p.dstream[0] = take(T * h * es);
+  p.dstream[1] = take(T * h * es);
+  p.dwide = take(T * std::max(f1, h) * es);
+  p.dmid = take(T * f * es);
+  p.dx1 = take(T * h * es);
+  p.dnorm = take(T * h * es);
+  p.dctx = take(T * A * es);
+  p.dqkv = take(T * nqkv * es);
+  p.dvec = take(stat);
+  const int64_t widest = std::max(std::max(2 * h, f1), std::max(nqkv, h));
+  p.reduce = take(tm_op_reduce_scratch_bytes(T, widest));
+  p.total = at;
+  return p;
+}
+
+}  // namespace tmk
+
+using namespace tmk;
+
+struct tm_stage {
+  tm_stage_config_t cfg;
+  tm_stage_buffers_t buf;
+  LayerOffsets lo;
+  Plan plan;
+  int64_t n_params;
+  bool have_fwd;
+  std::vector<TensorInfo> tensors;
+};
+
+static std::deque<std::string> &name_pool() {  // deque: growing it never moves the strings
+  static thread_local std::deque<std::string> pool;
+  return pool;
+}
+
+extern "C" const char *tm_last_error(void) { return g_err; }
+
+extern "C" int64_t tm_stage_param_count(const tm_stage_config_t *cfg) {
+  if (int e = validate(cfg)) return e;
+  return layer_offsets(cfg).total * cfg->n_layers;
+}
+
+extern "C" int64_t tm_stage_workspace_bytes(const tm_stage_config_t *cfg) {
+  if (int e = validate(cfg)) return e;
+  return make_plan(cfg).total;
+}
+
+extern "C" int tm_stage_param_layout(const tm_stage_config_t *cfg, int index, const char **name, int64_t *offset_elems,
+                                     int64_t shape[2]) {
+  if (int e = validate(cfg)) return e;
+  const std::vector<TensorInfo> t = tensor_list(cfg);
+  if (index == -1) return (int)t.size();
+  if (index < 0 || index >= (int)t.size()) return fail(TM_EINVAL, "param_layout: index %d out of range", index);
+  if (name) {
+    // names stay valid for the life of the calling thread
+    auto &pool = name_pool();
+    for (auto &s : pool)
+      if (s == t[index].name) {
+        *name = s.c_str();
+        goto named;
+      }
+    pool.push_back(t[index].name);
+    *name = pool.back().c_str();
+  }
+named:
+  if (offset_elems) *offset_elems = t[index].offset;
+  if (shape) {
+    shape[0] = t[index].rows;
+    shape[1] = t[index].cols;
+  }
+  return TM_OK;
+}
+
+extern "C" int tm_stage_init(const tm_stage_config_t *cfg, const tm_stage_buffers_t *b, tm_stage_t **out) {
+  if (!out) return fail(TM_EINVAL, "stage_init: out is NULL");
+  *out = nullptr;
+  if (int e = validate(cfg)) return e;
+  if (!b) return fail(TM_EINVAL, "stage_init: buffers is NULL");
+  if (!b->params || !b->grads || !b->exp_avg || !b->exp_avg_sq || !b->workspace)
+    return fail(TM_EINVAL, "stage_init: a required buffer is NULL");
+  if (cfg->dtype == TM_DTYPE_BF16 && !b->master) return fail(TM_EINVAL, "stage_init: bf16 stages need master weights");
+  const void *ptrs[] = {b->params, b->master, b->grads, b->exp_avg, b->exp_avg_sq, b->workspace};
+  for (const void *q : ptrs)
+    if (((uintptr_t)q) & 255) return fail(TM_EALIGN, "stage_init: buffers must be 256-byte aligned");
+  int dev = 0;
+  hipDeviceProp_t prop;
+  if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) {
+    (void)hipGetLastError();
+    return fail(TM_EARCH, "stage_init: no usable HIP device");
+  }
+  if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
+    return fail(TM_EARCH, "stage_init: device is %s, this library is built for gfx950", prop.gcnArchName);
+  tm_stage *st = new tm_stage();
+  st->cfg = *cfg;
+  st->buf = *b;
+  st->lo = layer_offsets(cfg);
+  st->plan = make_plan(cfg);
+  st->n_params = st->lo.total * cfg->n_layers;
+  st->have_fwd = false;
+  *out = st;
+  return TM_OK;
+}
+
+extern "C" void tm_stage_destroy(tm_stage_t *st) { delete st; }
+
+namespace {
+struct Dims {
+  int64_t T, h, A, nqkv, f, f1, es;
+};
+Dims dims_of(const tm_stage_config_t &c) {
+  Dims d;
+  d.T = (int64_t)c.seq * c.micro_batch;
+  d.h = c.hidden;
+  d.A = (int64_t)c.n_q_heads * c.head_dim;
+  d.nqkv = (int64_t)(c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim;
+  d.f = c.ffn;
+  d.f1 = c.act == TM_ACT_SWIGLU ? 2 * d.f : d.f;
+  d.es = c.dtype == TM_DTYPE_BF16 ? 2 : 4;
+  return d;
+}
+}  // namespace
+
+#define TM_TRY(expr)          \
+  do {                        \
+    const int _e = (expr);    \
+    if (_e) return _e;        \
+  } while (0)
+
+extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void *stream) {
+  if (!st || !x_in || !y_out) return fail(TM_EINVAL, "stage_fwd: NULL argument");
+  if ((((uintptr_t)x_in) | ((uintptr_t)y_out)) & 255) return fail(TM_EALIGN, "stage_fwd: tensors must be 256-byte aligned");
+  const tm_stage_config_t &c = st->cfg;
+  const Dims d = dims_of(c);
+  const int dt = c.dtype;
+  char *ws = (char *)st->buf.workspace;
+  const char *par = (const char *)st->buf.params;
+  hipStream_t s = (hipStream_t)stream;
+  st->have_fwd = false;
+
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerStash &k = st->plan.layer[l];
+    const LayerOffsets &o = st->lo;
+    const int64_t pb = (int64_t)l * o.total;
+    auto P = [&](int64_t off) -> const void * { return off < 0 ? nullptr : par + (pb + off) * d.es; };
+    void *x = ws + k.x;
+    if (l == 0) {
+      if (hipMemcpyAsync(x, x_in, d.T * d.h * d.es, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return fail(TM_ELAUNCH, "stage_fwd: copy of the stage input failed");
+    }
+    void *y = (l + 1 < c.n_layers) ? (void *)(ws + st->plan.layer[l + 1].x) : y_out;
+    // a = Norm(x)
+    TM_TRY(tm_op_norm_fwd(dt, c.norm, d.T, d.h, c.norm_eps, x, P(o.norm1_gain), P(o.norm1_offset), ws + k.a,
+                          (float *)(ws + k.mean1), (float *)(ws + k.rstd1), s));
+    // qkv = a Wqkv^T + b
+    TM_TRY(tm_op_linear_fwd(dt, d.T, d.nqkv, d.h, ws + k.a, P(o.w_qkv), P(o.b_qkv), nullptr, ws + k.qkv, s));
+    if (c.pos == TM_POS_ROTARY)
+      TM_TRY(tm_op_rotary(dt, c.seq, c.micro_batch, c.n_q_heads + c.n_kv_heads, c.head_dim, d.nqkv, c.rope_theta, 0,
+                          ws + k.qkv, s));
+    TM_TRY(tm_op_attn_fwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
+                          (float *)(ws + k.lse), s));
+    // x1 = x + ctx Wout^T + b   (row-parallel projection; its all-reduce is the identity here)
+    TM_TRY(tm_op_linear_fwd(dt, d.T, d.h, d.A, ws + k.ctx, P(o.w_out), P(o.b_out), x, ws + k.x1, s));
+    // c = Norm(x1)
+    TM_TRY(tm_op_norm_fwd(dt, c.norm, d.T, d.h, c.norm_eps, ws + k.x1, P(o.norm2_gain), P(o.norm2_offset), ws + k.c,
+                          (float *)(ws + k.mean2), (float *)(ws + k.rstd2), s));
+    // u = c W1^T + b ; g = act(u)
+    TM_TRY(tm_op_linear_fwd(dt, d.T, d.f1, d.h, ws + k.c, P(o.w_fc1), P(o.b_fc1), nullptr, ws + k.u, s));
+    TM_TRY(tm_op_act_fwd(dt, c.act, d.T, d.f, ws + k.u, ws + k.g, s));
+    // y = x1 + g W2^T + b
+    TM_TRY(tm_op_linear_fwd(dt, d.T, d.h, d.f, ws + k.g, P(o.w_fc2), P(o.b_fc2), ws + k.x1, y, s));
+  }
+  st->have_fwd = true;
+  return TM_OK;
+}
+
+extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stream) {
+  if (!st || !dy_in || !dx_out) return fail(TM_EINVAL, "stage_bwd: NULL argument");
+  if ((((uintptr_t)dy_in) | ((uintptr_t)dx_out)) & 255) return fail(TM_EALIGN, "stage_bwd: tensors must be 256-byte aligned");
+  if (!st->have_fwd) return fail(TM_ESTATE, "stage_bwd: no forward pass to differentiate");
+  const tm_stage_config_t &c = st->cfg;
+  const Dims d = dims_of(c);
+  const int dt = c.dtype;
+  char *ws = (char *)st->buf.workspace;
+  const char *par = (const char *)st->buf.params;
+  float *grads = st->buf.grads;
+  hipStream_t s = (hipStream_t)stream;
+  const Plan &pl = st->plan;
+  void *red = ws + pl.reduce;
+  const bool bias = c.has_bias != 0;
+
+  const void *dy = dy_in;
+  for (int l = c.n_layers - 1; l >= 0; --l) {
+    const LayerStash &k = pl.layer[l];
+    const LayerOffsets &o = st->lo;
+    const int64_t pb = (int64_t)l * o.total;
+    auto P = [&](int64_t off) -> const void * { return off < 0 ? nullptr : par + (pb + off) * d.es; };
+    auto G = [&](int64_t off) -> float * { return off < 0 ? nullptr : grads + pb + off; };
+    void *dx = (l == 0) ? dx_out : (void *)(ws + pl.dstream[l & 1]);
+
+    // y = x1 + g W2^T + b2
+    void *dg = (c.act == TM_ACT_SWIGLU) ? (void *)(ws + pl.dmid) : (void *)(ws + pl.dwide);
+    TM_TRY(tm_op_linear_dgrad(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, s));
+    TM_TRY(tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), s));
+    if (bias) TM_TRY(tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, s));
+    // activation
+    void *du = ws + pl.dwide;
+    TM_TRY(tm_op_act_bwd(dt, c.act, d.T, d.f, dg, ws + k.u, du, s));
+    // u = c W1^T + b1
+    void *dc = ws + pl.dnorm;
+    TM_TRY(tm_op_linear_dgrad(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, s));
+    TM_TRY(tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), s));
+    if (bias) TM_TRY(tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, s));
+    // c = Norm(x1): dx1 = dy + norm gradient
+    void *dx1 = ws + pl.dx1;
+    TM_TRY(tm_op_norm_bwd(dt, c.norm, d.T, d.h, dc, ws + k.x1, (const float *)(ws + k.mean2),
+                          (const float *)(ws + k.rstd2), P(o.norm2_gain), dy, dx1, G(o.norm2_gain),
+                          G(o.norm2_offset), red, s));
+    // x1 = x + ctx Wout^T + bout
+    TM_TRY(tm_op_linear_dgrad(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, s));
+    TM_TRY(tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), s));
+    if (bias) TM_TRY(tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, s));
+    // attention, rotary
+    TM_TRY(tm_op_attn_bwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
+                          ws + pl.dctx, (const float *)(ws + k.lse), (float *)(ws + pl.dvec), ws + pl.dqkv, s));
+    if (c.pos == TM_POS_ROTARY)
+      TM_TRY(tm_op_rotary(dt, c.seq, c.micro_batch, c.n_q_heads + c.n_kv_heads, c.head_dim, d.nqkv, c.rope_theta, 1,
+                          ws + pl.dqkv, s));
+    // qkv = a Wqkv^T + b
+    void *da = ws + pl.dnorm;
+    TM_TRY(tm_op_linear_dgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, s));
+    TM_TRY(tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), s));
+    if (bias) TM_TRY(tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, s));
+    // a = Norm(x): dx = dx1 + norm gradient
+    TM_TRY(tm_op_norm_bwd(dt, c.norm, d.T, d.h, da, ws + k.x, (const float *)(ws + k.mean1),
+                          (const float *)(ws + k.rstd1), P(o.norm1_gain), dx1, dx, G(o.norm1_gain),
+                          G(o.norm1_offset), red, s));
+    dy = dx;
+  }
+  return TM_OK;
+}
+
+extern "C" int tm_adam_step(tm_stage_t *st, const tm_adam_hparams_t *hp, int64_t step, void *stream) {
+  if (!st || !hp) return fail(TM_EINVAL, "adam_step: NULL argument");
+  const bool lowp = st->cfg.dtype == TM_DTYPE_BF16;
+  float *p = lowp ? st->buf.master : (float *)st->buf.params;
+  return tm_adam_step_flat(st->n_params, p, st->buf.grads, st->buf.exp_avg, st->buf.exp_avg_sq,
+                           lowp ? st->buf.params : nullptr, hp, step, stream);
+}

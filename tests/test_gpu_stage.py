@@ -1,0 +1,163 @@
+"""End-to-end parity of tm_stage_fwd / tm_stage_bwd / tm_adam_step against the fp64 CPU checker,
+plus the properties the sandboxed warm-up relies on (overwritable state, reproducible results)."""
+import numpy as np
+import pytest
+
+import synth_inputs as si
+from oracle import stage_oracle as so
+from tests.gpu_util import TOL_ADAM, TOL_BF16, TOL_FP32, rel_err, require_gpu, to_dev, to_host
+from tests.stage_runner import GpuStage, flatten_grads, oracle_iteration
+
+pytestmark = pytest.mark.gpu
+
+SMALL_GPT = si.StageConfig(2, 256, 2, 2, 128, 512, 200, 2)                     # bf16, ragged sequence, batch 2
+SMALL_LLAMA = si.StageConfig(2, 256, 4, 1, 64, 328, 130, 1, norm=si.NORM_RMSNORM, act=si.ACT_SWIGLU,
+                             pos=si.POS_ROTARY, has_bias=0)
+SMALL_ERF = si.StageConfig(1, 128, 2, 2, 32, 256, 40, 1, act=si.ACT_GELU_ERF)   # plain-ALU attention in bf16
+TINY = si.PRESETS["tiny"]
+TINY_LLAMA_FP32 = si.StageConfig(1, 64, 4, 2, 16, 96, 33, 2, dtype=si.DTYPE_FP32, norm=si.NORM_RMSNORM,
+                                 act=si.ACT_SWIGLU, pos=si.POS_ROTARY, has_bias=0)
+
+
+@pytest.fixture(scope="module")
+def env():
+    torch = require_gpu()
+    import paper_2412_12636_amd as tm
+    return torch, tm
+
+
+def run_and_compare(torch, tm, cfg, progress=False):
+    tol = TOL_BF16 if cfg.dtype == si.DTYPE_BF16 else TOL_FP32
+    flat = si.make_flat_params(cfg)
+    x, dy = si.make_x(cfg), si.make_dy(cfg)
+    st = GpuStage(torch, tm, cfg, flat)
+    y = to_host(st.fwd(to_dev(torch, x, cfg.dtype)))
+    dx = to_host(st.bwd(to_dev(torch, dy, cfg.dtype)))
+    torch.cuda.synchronize()
+    gpu_grads = st.grads.cpu().numpy().astype(np.float64)
+    layers = si.split_flat(cfg, flat)
+    ry, rdx, rgrads = oracle_iteration(cfg, layers, x, dy, progress)
+    errs = {"y": rel_err(y, ry), "dx": rel_err(dx, rdx)}
+    off = 0
+    for l in range(cfg.n_layers):
+        for name, shape in si.layer_inventory(cfg):
+            n = int(np.prod(shape))
+            errs[f"layer{l}.{name}"] = rel_err(gpu_grads[off:off + n], rgrads[l][name].reshape(-1))
+            off += n
+    worst = max(errs, key=errs.get)
+    print(f"worst {worst}: {errs[worst]:.3e}  y {errs['y']:.3e}  dx {errs['dx']:.3e}", flush=True)
+    for k, e in errs.items():
+        assert e <= tol, (k, e)
+
+    # Adam: fed the GPU's own fp32 gradients on both sides, the master weights must agree to 1e-5
+    p0 = flat.astype(np.float64)
+    z = np.zeros_like(p0)
+    st.adam(step=1)
+    torch.cuda.synchronize()
+    rp, rm, rv = so.adam_step(p0, gpu_grads, z, z, 1, **{k: si.ADAM_DEFAULTS[k] for k in
+                                                         ("lr", "beta1", "beta2", "eps", "weight_decay", "grad_scale")})
+    assert rel_err(to_host(st.master_weights()), rp) <= TOL_ADAM
+    assert rel_err(to_host(st.m), rm) <= TOL_ADAM and rel_err(to_host(st.v), rv) <= TOL_ADAM
+    if cfg.dtype == si.DTYPE_BF16:
+        want = so.bf16_round_nearest_even(st.master.cpu().numpy())
+        got = st.params.view(torch.int16).cpu().numpy().view(np.uint16)
+        assert (got == want).all()
+    # chained end to end (checker gradients -> checker Adam): at step 1 the update is lr*g/(|g|+eps),
+    # insensitive to small gradient errors except where g is near zero
+    cp, _, _ = so.adam_step(p0, flatten_grads(cfg, rgrads), z, z, 1, 1e-3, 0.9, 0.999, 1e-8)
+    chained = np.abs(to_host(st.master_weights()) - cp)
+    print(f"chained Adam: max |dp| {chained.max():.3e} (lr = 1e-3), mean {chained.mean():.3e}", flush=True)
+    assert chained.max() <= 2.0e-3 + 1e-6      # never more than the two updates pointing opposite ways
+    st.close()
+    return errs
+
+
+@pytest.mark.parametrize("cfg", [TINY, TINY_LLAMA_FP32, SMALL_GPT, SMALL_LLAMA, SMALL_ERF],
+                         ids=["tiny", "tiny_llama_fp32", "small_gpt", "small_llama", "small_erf"])
+def test_stage_iteration_matches_checker(env, cfg):
+    torch, tm = env
+    print(f"stage parity {cfg}", flush=True)
+    run_and_compare(torch, tm, cfg)
+
+
+def test_gpt6p7b_shard_full_depth(env):
+    torch, tm = env
+    print("stage parity gpt6p7b (4 layers, full size)", flush=True)
+    run_and_compare(torch, tm, si.PRESETS["gpt6p7b"], progress=True)
+
+
+def test_backward_needs_forward_and_gradients_accumulate(env):
+    torch, tm = env
+    cfg = SMALL_GPT
+    flat = si.make_flat_params(cfg)
+    st = GpuStage(torch, tm, cfg, flat)
+    x, dy = to_dev(torch, si.make_x(cfg), cfg.dtype), to_dev(torch, si.make_dy(cfg), cfg.dtype)
+    with pytest.raises(tm.TmError) as e:
+        st.bwd(dy)
+    assert e.value.code == tm.TM_ESTATE
+    st.fwd(x)
+    st.bwd(dy)
+    g1 = st.grads.clone()
+    st.bwd(dy)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(st.grads), 2.0 * to_host(g1)) <= 1e-6
+    # zero_grads clears the buffer inside the Adam kernel
+    st.adam(step=1, zero_grads=1)
+    torch.cuda.synchronize()
+    assert float(st.grads.abs().max()) == 0.0
+    st.close()
+
+
+def test_two_runs_are_bit_identical(env):
+    torch, tm = env
+    cfg = SMALL_LLAMA
+    flat = si.make_flat_params(cfg)
+    x, dy = to_dev(torch, si.make_x(cfg), cfg.dtype), to_dev(torch, si.make_dy(cfg), cfg.dtype)
+    outs = []
+    for _ in range(2):
+        st = GpuStage(torch, tm, cfg, flat)
+        st.fwd(x)
+        st.bwd(dy)
+        st.adam(step=1)
+        torch.cuda.synchronize()
+        outs.append((st.y.clone(), st.dx.clone(), st.grads.clone(), st.master.clone(), st.params.clone()))
+        st.close()
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_state_overwritten_between_calls_is_used(env):
+    """After the warm-up all local state is overwritten by the leaver's: the library must read the
+    buffers at launch time and keep no copies."""
+    torch, tm = env
+    cfg = SMALL_GPT
+    flat_a, flat_b = si.make_flat_params(cfg, seed=1), si.make_flat_params(cfg, seed=2)
+    x = to_dev(torch, si.make_x(cfg), cfg.dtype)
+    st = GpuStage(torch, tm, cfg, flat_a)
+    ya = st.fwd(x).clone()
+    st.params.copy_(to_dev(torch, flat_b, cfg.dtype))       # the "leaver's" parameters arrive
+    yb = st.fwd(x).clone()
+    ref = GpuStage(torch, tm, cfg, flat_b)
+    yref = ref.fwd(x).clone()
+    torch.cuda.synchronize()
+    assert not torch.equal(ya, yb)
+    assert torch.equal(yb, yref)
+    st.close()
+    ref.close()
+
+
+def test_init_rejects_bad_buffers_and_shapes(env):
+    torch, tm = env
+    cfg = SMALL_GPT
+    n = tm.tm_stage_param_count(cfg)
+    buf = torch.zeros(n + 64, dtype=torch.float32, device="cuda")
+    ws = torch.empty(tm.tm_stage_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    with pytest.raises(tm.TmError) as e:
+        tm.tm_stage_init(cfg, buf, None, buf, buf, buf, ws)            # bf16 stage without master weights
+    assert e.value.code == tm.TM_EINVAL
+    with pytest.raises(tm.TmError) as e:
+        tm.tm_stage_init(cfg, buf.data_ptr() + 4, buf, buf, buf, buf, ws)
+    assert e.value.code == tm.TM_EALIGN
+    with pytest.raises(tm.TmError) as e:
+        tm.tm_stage_init(cfg.replace(n_q_heads=3), buf, buf, buf, buf, buf, ws)
+    assert e.value.code == tm.TM_ESIZE

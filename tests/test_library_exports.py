@@ -1,0 +1,77 @@
+"""Host-only checks: the shared library loads, exports every symbol the headers declare, and its
+layout / workspace queries are pure functions of the configuration that agree with the input
+recipe's inventory.  No kernel is launched."""
+import os
+import re
+
+import pytest
+
+import synth_inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def tm():
+    import paper_2412_12636_amd as tm
+    if not os.path.exists(tm.LIB_PATH):
+        from paper_2412_12636_amd import build
+        build.build()
+    return tm
+
+
+def declared_symbols():
+    names = set()
+    for hdr in ("tm_stage.h", "tm_ops.h"):
+        text = open(os.path.join(ROOT, "include", hdr)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(tm_[a-z0-9_]+)\s*\(", text))
+    return names
+
+
+def test_every_declared_symbol_is_exported_and_bound(tm):
+    lib = tm.lib()
+    decl = declared_symbols()
+    assert decl, "no declarations found"
+    for name in decl:
+        assert hasattr(lib, name), name
+    assert decl == set(tm.EXPORTS), decl ^ set(tm.EXPORTS)
+    for name in decl:
+        assert callable(getattr(tm, name)), f"binding lacks {name}"
+
+
+@pytest.mark.parametrize("preset", list(si.PRESETS))
+def test_layout_matches_inventory(tm, preset):
+    cfg = si.PRESETS[preset]
+    assert tm.tm_stage_param_count(cfg) == si.stage_param_count(cfg)
+    layout = tm.tm_stage_param_layout(cfg)
+    inv = si.layer_inventory(cfg)
+    assert len(layout) == cfg.n_layers * len(inv)
+    off = 0
+    for l in range(cfg.n_layers):
+        for (name, shape) in inv:
+            lname, loff, lshape = layout[l * len(inv) + inv.index((name, shape))]
+            assert lname == f"layer{l}.{name}"
+            assert loff == off and off % 8 == 0
+            assert lshape == (shape[0], shape[1] if len(shape) == 2 else 1)
+            off += shape[0] * (shape[1] if len(shape) == 2 else 1)
+    # queries are pure: asking twice gives the same answers
+    assert tm.tm_stage_param_layout(cfg) == layout
+    assert tm.tm_stage_workspace_bytes(cfg) == tm.tm_stage_workspace_bytes(cfg) > 0
+
+
+def test_config_errors(tm):
+    cfg = si.PRESETS["tiny"]
+    for bad, code in ((cfg.replace(hidden=100), tm.TM_ESIZE), (cfg.replace(n_layers=0), tm.TM_EINVAL),
+                      (cfg.replace(n_q_heads=3, n_kv_heads=2), tm.TM_ESIZE), (cfg.replace(dtype=7), tm.TM_EINVAL),
+                      (cfg.replace(hidden=32768, dtype=si.DTYPE_BF16), tm.TM_ESIZE),
+                      (cfg.replace(seq=10000), tm.TM_ESIZE)):
+        with pytest.raises(tm.TmError) as e:
+            tm.tm_stage_param_count(bad)
+        assert e.value.code == code
+        assert tm.tm_last_error()
+
+
+def test_reduce_scratch_query(tm):
+    assert tm.tm_op_reduce_scratch_bytes(2048, 12288) == 256 * 12288 * 4
+    assert tm.tm_op_reduce_scratch_bytes(5, 8) == 5 * 8 * 4
