@@ -1,0 +1,244 @@
+#!/usr/bin/env python3
+"""Throughput of the stage-shard iteration (forward + backward + Adam) on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic micro-batch of the chosen shard
+preset: tm_stage_fwd, tm_stage_bwd, tm_adam_step (gradients cleared inside the Adam kernel).
+Inputs and all state are resident in HBM before the timed region.  One JSON line is printed.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--preset gpt175b] [--cpu-seconds 20]
+
+Timing: W untimed steps, then K steps bracketed by device synchronisation and HIP events on the
+stream the kernels are launched on.  A second pass of K steps runs with the library's per-kernel
+event profiling switched on; the kernel with the largest total time gives the `roofline` object
+(algorithmic flops or bytes of its launches / their summed duration).  The CPU checker is timed on
+a bounded sample of the same workload for `cpu_baseline`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def model_flops(cfg) -> float:
+    """Model flops of one iteration: 3 x forward; attention counted causal (half the square), no
+    credit for recomputation."""
+    T = cfg.seq * cfg.micro_batch
+    gemm = 2.0 * T * (cfg.qkv_width * cfg.hidden + cfg.hidden * cfg.attn_width + cfg.fc1_width * cfg.hidden
+                      + cfg.hidden * cfg.ffn)
+    attn = 2.0 * cfg.micro_batch * cfg.n_q_heads * cfg.seq * cfg.seq * cfg.head_dim
+    return 3.0 * cfg.n_layers * (gemm + attn)
+
+
+def cpu_baseline(si, cfg, budget_s: float):
+    """Times the fp64 CPU checker on one layer at a reduced token count and scales to the whole
+    stage: forward/backward time is linear in tokens (attention is a small share), Adam is per
+    parameter.  Returns the dict for the JSON line."""
+    import numpy as np
+    from oracle import stage_oracle as so
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    seq_s = min(cfg.seq, 256)
+    sample = cfg.replace(n_layers=1, seq=seq_s)
+    p = si.make_layer_params(sample, 0)
+    x, dy = si.make_x(sample), si.make_dy(sample)
+    t0 = time.time()
+    y, st = so.layer_fwd(sample, p, x)
+    dx, gr = so.layer_bwd(sample, p, st, dy)
+    t_fb = time.time() - t0
+    # Adam on the layer's largest matrix, scaled to the layer's parameter count
+    name = max(gr, key=lambda k: gr[k].size)
+    w = p[name].astype(np.float64)
+    z = np.zeros_like(w)
+    t0 = time.time()
+    w2, m2, v2 = so.adam_step(w, gr[name], z, z, 1, 1e-3, 0.9, 0.999, 1e-8)
+    so.bf16_round_nearest_even(w2.astype(np.float32))
+    t_adam = (time.time() - t0) * si.layer_param_count(sample) / w.size
+    step_s = cfg.n_layers * (t_fb * (cfg.seq / seq_s) + t_adam)
+    return {
+        "value": cfg.seq * cfg.micro_batch / step_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+        "sample": (f"fp64 numpy checker, 1 of {cfg.n_layers} layers at full width, first {seq_s} of {cfg.seq} positions: "
+                   f"fwd+bwd {t_fb:.2f} s, Adam {t_adam:.2f} s; scaled x{cfg.seq // seq_s} in tokens (Adam not) "
+                   f"and x{cfg.n_layers} in layers"),
+        "measured_s": round(t_fb + t_adam, 2), "host_cpus": len(os.sched_getaffinity(0)),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--preset", default="gpt175b")
+    ap.add_argument("--layers", type=int, default=0, help="override the preset's layer count (0 = preset)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU's stage shard; this build has no multi-GPU path "
+              "(collectives are identities by design). Run with --gpus 1.", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_2412_12636_amd as tm
+    import synth_inputs as si
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    cfg = si.PRESETS[args.preset]
+    if args.layers:
+        cfg = cfg.replace(n_layers=args.layers)
+    bf16 = cfg.dtype == si.DTYPE_BF16
+    td = torch.bfloat16 if bf16 else torch.float32
+    n = tm.tm_stage_param_count(cfg)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(si.BASE_SEED)
+
+    # state, resident in HBM: N(0, 0.02^2) everywhere, norm gains shifted to 1
+    master = torch.empty(n, dtype=torch.float32, device="cuda")
+    chunk = 1 << 28
+    for lo in range(0, n, chunk):
+        master[lo:lo + chunk].normal_(0.0, 0.02, generator=gen)
+    for name, off, shape in tm.tm_stage_param_layout(cfg):
+        if name.endswith("_gain"):
+            master[off:off + shape[0]] += 1.0
+    params = master.to(td) if bf16 else master
+    if bf16:
+        master.copy_(params)          # master starts from the bf16-representable values
+    grads = torch.zeros(n, dtype=torch.float32, device="cuda")
+    m = torch.zeros(n, dtype=torch.float32, device="cuda")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda")
+    ws = torch.empty(tm.tm_stage_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    shape = (cfg.seq, cfg.micro_batch, cfg.hidden)
+    x = torch.empty(shape, dtype=torch.float32, device="cuda").normal_(0, 1, generator=gen).to(td)
+    dy = torch.empty(shape, dtype=torch.float32, device="cuda").normal_(0, 1e-2, generator=gen).to(td)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    h = tm.tm_stage_init(cfg, params, master if bf16 else None, grads, m, v, ws)
+    hp = tm.make_hparams(**{**si.ADAM_DEFAULTS, "zero_grads": 1})
+    stream = int(torch.cuda.current_stream().cuda_stream)
+    step_no = [0]
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def one_step(marks=None):
+        step_no[0] += 1
+        if marks is not None:
+            marks[0].record()
+        tm.tm_stage_fwd(h, x, y, stream)
+        if marks is not None:
+            marks[1].record()
+        tm.tm_stage_bwd(h, dy, dx, stream)
+        if marks is not None:
+            marks[2].record()
+        tm.tm_adam_step(h, hp, step_no[0], stream)
+        if marks is not None:
+            marks[3].record()
+
+    # cold first call (the gap the sandboxed warm-up exists to hide)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    one_step()
+    torch.cuda.synchronize()
+    first_ms = (time.time() - t0) * 1e3
+    for _ in range(max(0, args.warmup - 1)):
+        one_step()
+    torch.cuda.synchronize()
+
+    marks = [[ev() for _ in range(4)] for _ in range(args.steps)]
+    start, stop = ev(), ev()
+    torch.cuda.synchronize()
+    t0 = time.time()
+    start.record()
+    for k in range(args.steps):
+        one_step(marks[k])
+    stop.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.time() - t0) * 1e3
+    total_ms = start.elapsed_time(stop)
+    ms_step = total_ms / args.steps
+    fwd_ms = sum(mk[0].elapsed_time(mk[1]) for mk in marks) / args.steps
+    bwd_ms = sum(mk[1].elapsed_time(mk[2]) for mk in marks) / args.steps
+    adam_ms = sum(mk[2].elapsed_time(mk[3]) for mk in marks) / args.steps
+
+    # second pass with per-kernel events
+    tm.tm_stage_profile_enable(h, True)
+    torch.cuda.synchronize()
+    pstart, pstop = ev(), ev()
+    pstart.record()
+    for k in range(args.steps):
+        one_step()
+    pstop.record()
+    torch.cuda.synchronize()
+    prof = tm.tm_stage_profile_collect(h, 64)
+    tm.tm_stage_profile_enable(h, False)
+    prof_ms_step = pstart.elapsed_time(pstop) / args.steps
+    prof.sort(key=lambda e: -e["ms"])
+    kernels = []
+    for e in prof:
+        avg_ms = e["ms"] / e["launches"]
+        row = {"kernel": e["kernel"], "launches_per_step": e["launches"] // args.steps,
+               "ms_per_step": round(e["ms"] / args.steps, 4), "avg_launch_ms": round(avg_ms, 5)}
+        if e["flops"] > 0:
+            row["tflops"] = round(e["flops"] / (e["ms"] * 1e-3) / 1e12, 1)
+        if e["bytes"] > 0:
+            row["gbps"] = round(e["bytes"] / (e["ms"] * 1e-3) / 1e9, 1)
+        kernels.append(row)
+    top = prof[0]
+    if top["flops"] > 0:
+        ach = top["flops"] / (top["ms"] * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / PEAK_BF16_TFLOPS, 4), "traffic": None}
+    else:
+        ach = top["bytes"] / (top["ms"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
+    roofline.update({"kernel": top["kernel"], "avg_launch_ms": round(top["ms"] / top["launches"], 5),
+                     "launches": top["launches"]})
+
+    tokens = cfg.seq * cfg.micro_batch
+    flops = model_flops(cfg)
+    tf = flops / ((fwd_ms + bwd_ms) * 1e-3) / 1e12
+    adam_bytes = (34.0 if bf16 else 32.0) * n
+    out = {
+        "metric": "stage-shard fwd+bwd+Adam tokens/s per GPU; MFMA util % of bf16 peak",
+        "value": round(tokens / (ms_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.preset}: {cfg.n_layers} layers, hidden {cfg.hidden}, {cfg.n_q_heads}q/"
+                               f"{cfg.n_kv_heads}kv heads x {cfg.head_dim}, ffn {cfg.ffn}, seq {cfg.seq}, "
+                               f"micro-batch {cfg.micro_batch}, {n} parameters (one rank's TP shard of one PP stage)",
+                   "preset": args.preset, "tokens_per_step": tokens},
+        "phases_ms": {"fwd": round(fwd_ms, 4), "bwd": round(bwd_ms, 4), "adam": round(adam_ms, 4)},
+        "tflops_fwd_bwd": round(tf, 2), "mfma_frac_fwd_bwd": round(tf / PEAK_BF16_TFLOPS, 4),
+        "model_tflop_per_step": round(flops / 1e12, 3),
+        "adam_gbps": round(adam_bytes / (adam_ms * 1e-3) / 1e9, 1), "adam_frac_hbm": round(adam_bytes / (adam_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+        "first_step_ms": round(first_ms, 2), "host_wall_ms_per_step": round(wall_ms / args.steps, 4),
+        "profiled_ms_per_step": round(prof_ms_step, 4),
+        "roofline": roofline, "kernels": kernels[:12],
+    }
+    tm.tm_stage_destroy(h)
+    if not args.no_cpu_baseline:
+        del master, params, grads, m, v, ws
+        out["cpu_baseline"] = cpu_baseline(si, cfg, args.cpu_seconds)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

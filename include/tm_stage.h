@@ -169,6 +169,27 @@ int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float *v, void *p
 
 void tm_stage_destroy(tm_stage_t *st);
 
+/*
+ * Optional per-kernel timing for measurement.  While enabled, every step that tm_stage_fwd,
+ * tm_stage_bwd and tm_adam_step enqueue is bracketed by two HIP events on the caller's stream.
+ * tm_stage_profile_collect waits for the recorded events (the only call here that blocks the
+ * host), sums elapsed time, launch count and algorithmic work per kernel name into entries[]
+ * (at most max_entries; `kernel` points at static storage), clears the record list and returns
+ * the number of entries filled.  flops counts 2*M*N*K per matrix product and 2*b*nq*s^2*d per
+ * causal attention forward (twice that backward); bytes counts the operands and results of the
+ * streaming kernels once.  Disabling frees the events.  Events are host objects: no device
+ * memory is allocated.
+ */
+typedef struct {
+  const char *kernel;
+  double ms;
+  double flops;
+  double bytes;
+  int64_t launches;
+} tm_profile_entry_t;
+int tm_stage_profile_enable(tm_stage_t *st, int enable);
+int tm_stage_profile_collect(tm_stage_t *st, tm_profile_entry_t *entries, int max_entries);
+
 /* Message of the last failure on the calling thread; never NULL. */
 const char *tm_last_error(void);
 

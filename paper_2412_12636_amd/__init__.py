@@ -40,6 +40,11 @@ class tm_stage_buffers_t(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("params", "master", "grads", "exp_avg", "exp_avg_sq", "workspace")]
 
 
+class tm_profile_entry_t(C.Structure):
+    _fields_ = [("kernel", C.c_char_p), ("ms", C.c_double), ("flops", C.c_double), ("bytes", C.c_double),
+                ("launches", C.c_int64)]
+
+
 class tm_adam_hparams_t(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("lr", "beta1", "beta2", "eps", "weight_decay", "grad_scale")] + \
                [("zero_grads", C.c_int32)]
@@ -58,6 +63,8 @@ EXPORTS = {
     "tm_adam_step_flat": (C.c_int, [C.c_int64] + [C.c_void_p] * 5 + [C.POINTER(tm_adam_hparams_t), C.c_int64,
                                                                        C.c_void_p]),
     "tm_stage_destroy": (None, [C.c_void_p]),
+    "tm_stage_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
+    "tm_stage_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(tm_profile_entry_t), C.c_int]),
     "tm_last_error": (C.c_char_p, []),
     "tm_op_linear_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 6),
     "tm_op_linear_dgrad": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 4),
@@ -170,6 +177,18 @@ def tm_adam_step_flat(n: int, p, g, m, v, p_bf16, hp: tm_adam_hparams_t, step: i
 
 def tm_stage_destroy(handle: int) -> None:
     lib().tm_stage_destroy(handle)
+
+
+def tm_stage_profile_enable(handle: int, enable: bool) -> None:
+    _check(lib().tm_stage_profile_enable(handle, int(enable)))
+
+
+def tm_stage_profile_collect(handle: int, max_entries: int = 64) -> List[dict]:
+    """Per-kernel totals since the last collect: kernel, ms, flops, bytes, launches."""
+    arr = (tm_profile_entry_t * max_entries)()
+    n = _check(lib().tm_stage_profile_collect(handle, arr, max_entries))
+    return [dict(kernel=arr[i].kernel.decode(), ms=arr[i].ms, flops=arr[i].flops, bytes=arr[i].bytes,
+                 launches=int(arr[i].launches)) for i in range(n)]
 
 
 def tm_last_error() -> str:

@@ -163,6 +163,7 @@ static AttnShape make_shape(int64_t seq, int64_t batch, int64_t nq, int64_t nkv,
 template <typename T>
 static int fwd_t(const AttnShape &a, const void *qkv, void *ctx, float *lse, hipStream_t s) {
   dim3 grid(a.seq, a.nq, a.batch);
+  g_last_kernel = "attn_fwd_generic";
   attn_fwd_generic<T><<<grid, 64, a.seq * sizeof(float), s>>>((const T *)qkv, (T *)ctx, lse, a);
   return check_launch("attn_fwd_generic");
 }
@@ -170,6 +171,7 @@ static int fwd_t(const AttnShape &a, const void *qkv, void *ctx, float *lse, hip
 template <typename T>
 static int bwd_t(const AttnShape &a, const void *qkv, const void *dctx, const float *lse, const float *dvec,
                  void *dqkv, hipStream_t s) {
+  g_last_kernel = "attn_bwd_generic";
   attn_bwd_dq_generic<T><<<dim3(a.seq, a.nq, a.batch), 64, a.seq * sizeof(float), s>>>(
       (const T *)qkv, (const T *)dctx, lse, dvec, (T *)dqkv, a);
   attn_bwd_dkv_generic<T><<<dim3(a.seq, a.nkv, a.batch), 64, 2 * a.seq * sizeof(float), s>>>(

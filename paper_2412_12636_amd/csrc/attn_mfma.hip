@@ -399,6 +399,7 @@ int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   p.ctx = (bf16 *)ctx;
   p.lse = lse;
   dim3 grid((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
+  g_last_kernel = "flash_fwd_kernel";
   if (d == 128)
     flash_fwd_kernel<128><<<grid, 256, 0, s>>>(p);
   else
@@ -426,6 +427,7 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
       return fail(TM_ELAUNCH, "flash_bwd: cannot reserve LDS");
     attr_set = true;
   }
+  g_last_kernel = "flash_bwd_dq_kernel+flash_bwd_dkv_kernel";
   if (d == 128) {
     flash_bwd_dq_kernel<128><<<gq, 256, 0, s>>>(p);
     flash_bwd_dkv_kernel<128><<<gk, 256, lds, s>>>(p);

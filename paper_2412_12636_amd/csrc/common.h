@@ -11,6 +11,9 @@ namespace tmk {
 // ---- error reporting (host) -------------------------------------------------
 int fail(int code, const char *fmt, ...);   // records the message for tm_last_error(), returns code
 int check_launch(const char *what);         // hipGetLastError() -> TM_ELAUNCH
+// Name of the (main) kernel the most recent launcher on this thread enqueued; read by the stage
+// profiler to attribute event timings.  Points at a string with static storage.
+extern thread_local const char *g_last_kernel;
 
 // ---- storage types -----------------------------------------------------------
 typedef __bf16 bf16;

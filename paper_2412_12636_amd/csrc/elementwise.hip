@@ -205,6 +205,7 @@ extern "C" int tm_op_act_fwd(int dtype, int act, int64_t T, int64_t f, const voi
   const int vn = dtype == TM_DTYPE_BF16 ? 8 : 4;
   const int64_t nchunk = T * f / vn;
   const unsigned grid = ew_grid(nchunk);
+  g_last_kernel = act == TM_ACT_SWIGLU ? "swiglu_fwd_kernel" : "gelu_fwd_kernel";
 #define TM_LAUNCH(TT)                                                                                              \
   if (act == TM_ACT_GELU_TANH)                                                                                     \
     gelu_fwd_kernel<TT, TM_ACT_GELU_TANH><<<grid, kEwThreads, 0, s>>>((const TT *)u, (TT *)g, nchunk);             \
@@ -232,6 +233,7 @@ extern "C" int tm_op_act_bwd(int dtype, int act, int64_t T, int64_t f, const voi
   const int vn = dtype == TM_DTYPE_BF16 ? 8 : 4;
   const int64_t nchunk = T * f / vn;
   const unsigned grid = ew_grid(nchunk);
+  g_last_kernel = act == TM_ACT_SWIGLU ? "swiglu_bwd_kernel" : "gelu_bwd_kernel";
 #define TM_LAUNCH(TT)                                                                                              \
   if (act == TM_ACT_GELU_TANH)                                                                                     \
     gelu_bwd_kernel<TT, TM_ACT_GELU_TANH><<<grid, kEwThreads, 0, s>>>((const TT *)dg, (const TT *)u, (TT *)du,     \
@@ -264,6 +266,7 @@ extern "C" int tm_op_rotary(int dtype, int64_t seq, int64_t batch, int64_t n_hea
   const int64_t n = rows * (d / 2);
   const unsigned grid = (unsigned)ceil_div(n, kEwThreads);
   const double sign = inverse ? -1.0 : 1.0;
+  g_last_kernel = "rotary_kernel";
   if (dtype == TM_DTYPE_BF16)
     rotary_kernel<bf16><<<grid, kEwThreads, 0, s>>>((bf16 *)buf, rows, (int)batch, (int)n_heads, (int)d,
                                                     (int)row_width, theta, sign);
@@ -297,6 +300,7 @@ extern "C" int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float 
   hipStream_t s = (hipStream_t)stream;
   const unsigned grid = ew_grid(n / 4 > 0 ? n / 4 : 1);
   const bool lowp = p_bf16 != nullptr, zero = hp->zero_grads != 0;
+  g_last_kernel = "adam_kernel";
   if (lowp && zero)
     adam_kernel<true, true><<<grid, kEwThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, n, a);
   else if (lowp)

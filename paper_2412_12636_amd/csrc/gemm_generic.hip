@@ -72,6 +72,7 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(int M, int N, int K, 
 template <typename T>
 static int launch_generic(const GemmArgs &g, hipStream_t s) {
   dim3 grid((unsigned)ceil_div(g.N, GT), (unsigned)ceil_div(g.M, GT));
+  g_last_kernel = "gemm_generic_kernel";
   if (g.accumulate_f32)
     gemm_generic_kernel<T, float, 1><<<grid, 256, 0, s>>>((int)g.M, (int)g.N, (int)g.K, (const T *)g.A, g.a_rs, g.a_cs,
                                                           (const T *)g.B, g.b_rs, g.b_cs, (float *)g.C, g.ldc, nullptr,

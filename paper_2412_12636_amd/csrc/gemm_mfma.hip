@@ -14,6 +14,8 @@
 // Block index -> tile mapping: consecutive hardware block ids land on different XCDs (8 per chip,
 // each with its own L2); ids are re-numbered so that every XCD works on a contiguous range of
 // tiles, with the M tiles of one weight column adjacent.
+#include <string>
+
 #include "gemm.h"
 
 namespace tmk {
@@ -255,6 +257,10 @@ static int launch_tile(const GemmArgs &g, hipStream_t s) {
   }
   const int64_t nblk = (int64_t)p.tiles_m * p.tiles_n;
   if (nblk > 0x7fffffff) return fail(TM_ESIZE, "gemm_mfma: too many tiles");
+  static const std::string name = "gemm_mfma_kernel<" + std::to_string(BM) + "," + std::to_string(BN) + "," +
+                                  (A_KC ? "true" : "false") + "," + (B_KC ? "true" : "false") + "," +
+                                  std::to_string(EPI) + ">";
+  g_last_kernel = name.c_str();
   kern<<<dim3((unsigned)nblk), 256, lds_bytes, s>>>(p);
   return check_launch("gemm_mfma");
 }

@@ -231,6 +231,7 @@ template <typename T>
 static int norm_fwd_t(int kind, int64_t rows, int h, float eps, const void *x, const void *gain, const void *offset,
                       void *out, float *mean, float *rstd, hipStream_t s) {
   const int nch = pick_nch(h, Vec<T>::N);
+  g_last_kernel = "norm_fwd_kernel";
   if (kind == TM_NORM_LAYERNORM) {
     TM_NCH_SWITCH(nch, (norm_fwd_kernel<T, TM_NORM_LAYERNORM, NCH><<<dim3((unsigned)rows), kNormThreads, 0, s>>>(
                            (const T *)x, (const T *)gain, (const T *)offset, (T *)out, mean, rstd, h, eps)))
@@ -246,6 +247,7 @@ static int norm_bwd_t(int kind, int64_t rows, int h, const void *dout, const voi
                       const float *rstd, const void *gain, const void *dres, void *dx, float *partial, hipStream_t s) {
   const int G = norm_bwd_blocks(rows);
   const int nch = pick_nch(h, Vec<T>::N);
+  g_last_kernel = "norm_bwd_kernel";
   if (kind == TM_NORM_LAYERNORM) {
     TM_NCH_SWITCH(nch, (norm_bwd_kernel<T, TM_NORM_LAYERNORM, NCH><<<G, kNormThreads, 0, s>>>(
                            (const T *)dout, (const T *)x, mean, rstd, (const T *)gain, (const T *)dres, (T *)dx,
@@ -321,6 +323,7 @@ extern "C" int tm_op_bias_grad(int dtype, int64_t T, int64_t N, const void *dy, 
   const int rows_per_group = (int)ceil_div(T, R);
   float *partial = (float *)scratch;
   const int vn = dtype == TM_DTYPE_BF16 ? 8 : 4;
+  g_last_kernel = "colsum_partial_kernel";
   dim3 grid((unsigned)ceil_div(N, (int64_t)kColLanes * vn), (unsigned)R);
   if (dtype == TM_DTYPE_BF16)
     colsum_partial_kernel<bf16><<<grid, kColLanes * kColRowsPerBlock, 0, s>>>((const bf16 *)dy, partial, T, (int)N,

@@ -15,6 +15,7 @@
 namespace tmk {
 
 static thread_local char g_err[512] = "";
+thread_local const char *g_last_kernel = "";
 
 int fail(int code, const char *fmt, ...) {
   va_list ap;
@@ -191,7 +192,35 @@ static Plan make_plan(const tm_stage_config_t *c) {
 
 using namespace tmk;
 
+// Event-based timing of every step a stage call enqueues (off by default).
+struct ProfRecord {
+  const char *kernel;
+  double flops, bytes;
+  hipEvent_t e0, e1;
+};
+struct Profiler {
+  bool on = false;
+  std::vector<hipEvent_t> pool;  // created on demand, reused after every collect
+  size_t used = 0;
+  std::vector<ProfRecord> recs;
+  hipEvent_t take() {
+    if (used == pool.size()) {
+      hipEvent_t e;
+      if (hipEventCreate(&e) != hipSuccess) return nullptr;
+      pool.push_back(e);
+    }
+    return pool[used++];
+  }
+  void release() {
+    for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+    pool.clear();
+    recs.clear();
+    used = 0;
+  }
+};
+
 struct tm_stage {
+  Profiler prof;
   tm_stage_config_t cfg;
   tm_stage_buffers_t buf;
   LayerOffsets lo;
@@ -274,7 +303,49 @@ extern "C" int tm_stage_init(const tm_stage_config_t *cfg, const tm_stage_buffer
   return TM_OK;
 }
 
-extern "C" void tm_stage_destroy(tm_stage_t *st) { delete st; }
+extern "C" void tm_stage_destroy(tm_stage_t *st) {
+  if (!st) return;
+  st->prof.release();
+  delete st;
+}
+
+extern "C" int tm_stage_profile_enable(tm_stage_t *st, int enable) {
+  if (!st) return fail(TM_EINVAL, "profile_enable: NULL handle");
+  st->prof.on = enable != 0;
+  if (!enable) st->prof.release();
+  return TM_OK;
+}
+
+extern "C" int tm_stage_profile_collect(tm_stage_t *st, tm_profile_entry_t *entries, int max_entries) {
+  if (!st || (!entries && max_entries > 0)) return fail(TM_EINVAL, "profile_collect: NULL argument");
+  Profiler &pr = st->prof;
+  int n = 0;
+  for (const ProfRecord &r : pr.recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(TM_ELAUNCH, "profile_collect: event query failed");
+    }
+    int k = 0;
+    for (; k < n; ++k)
+      if (!strcmp(entries[k].kernel, r.kernel)) break;
+    if (k == n) {
+      if (n == max_entries) continue;  // table full: the remaining kernels are dropped
+      entries[n].kernel = r.kernel;
+      entries[n].ms = 0.0;
+      entries[n].flops = entries[n].bytes = 0.0;
+      entries[n].launches = 0;
+      ++n;
+    }
+    entries[k].ms += ms;
+    entries[k].flops += r.flops;
+    entries[k].bytes += r.bytes;
+    entries[k].launches += 1;
+  }
+  pr.recs.clear();
+  pr.used = 0;
+  return n;
+}
 
 namespace {
 struct Dims {
@@ -299,6 +370,25 @@ Dims dims_of(const tm_stage_config_t &c) {
     if (_e) return _e;        \
   } while (0)
 
+// Runs one step; with profiling on, brackets it with events on the stream and notes its
+// algorithmic work (flops for the matrix-core steps, HBM bytes for the streaming ones).
+#define TM_STEP(FLOPS, BYTES, expr)                                             \
+  do {                                                                          \
+    hipEvent_t _e0 = nullptr, _e1 = nullptr;                                    \
+    if (st->prof.on) {                                                          \
+      _e0 = st->prof.take();                                                    \
+      _e1 = st->prof.take();                                                    \
+      if (!_e0 || !_e1) return fail(TM_ELAUNCH, "profiler: cannot create events"); \
+      (void)hipEventRecord(_e0, s);                                             \
+    }                                                                           \
+    const int _e = (expr);                                                      \
+    if (_e) return _e;                                                          \
+    if (st->prof.on) {                                                          \
+      (void)hipEventRecord(_e1, s);                                             \
+      st->prof.recs.push_back({g_last_kernel, (double)(FLOPS), (double)(BYTES), _e0, _e1}); \
+    }                                                                           \
+  } while (0)
+
 extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void *stream) {
   if (!st || !x_in || !y_out) return fail(TM_EINVAL, "stage_fwd: NULL argument");
   if ((((uintptr_t)x_in) | ((uintptr_t)y_out)) & 255) return fail(TM_EALIGN, "stage_fwd: tensors must be 256-byte aligned");
@@ -309,6 +399,8 @@ extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void 
   const char *par = (const char *)st->buf.params;
   hipStream_t s = (hipStream_t)stream;
   st->have_fwd = false;
+  const double es = (double)d.es, Th = (double)d.T * d.h;
+  const double attn_flops = 2.0 * c.micro_batch * c.n_q_heads * (double)c.seq * c.seq * c.head_dim;  // causal half
 
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerStash &k = st->plan.layer[l];
@@ -317,30 +409,41 @@ extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void 
     auto P = [&](int64_t off) -> const void * { return off < 0 ? nullptr : par + (pb + off) * d.es; };
     void *x = ws + k.x;
     if (l == 0) {
-      if (hipMemcpyAsync(x, x_in, d.T * d.h * d.es, hipMemcpyDeviceToDevice, s) != hipSuccess)
-        return fail(TM_ELAUNCH, "stage_fwd: copy of the stage input failed");
+      g_last_kernel = "copy_stage_input";
+      TM_STEP(0, 2 * es * Th,
+              hipMemcpyAsync(x, x_in, d.T * d.h * d.es, hipMemcpyDeviceToDevice, s) == hipSuccess
+                  ? TM_OK
+                  : fail(TM_ELAUNCH, "stage_fwd: copy of the stage input failed"));
     }
     void *y = (l + 1 < c.n_layers) ? (void *)(ws + st->plan.layer[l + 1].x) : y_out;
     // a = Norm(x)
-    TM_TRY(tm_op_norm_fwd(dt, c.norm, d.T, d.h, c.norm_eps, x, P(o.norm1_gain), P(o.norm1_offset), ws + k.a,
-                          (float *)(ws + k.mean1), (float *)(ws + k.rstd1), s));
+    TM_STEP(0, 2 * es * Th,
+            tm_op_norm_fwd(dt, c.norm, d.T, d.h, c.norm_eps, x, P(o.norm1_gain), P(o.norm1_offset), ws + k.a,
+                           (float *)(ws + k.mean1), (float *)(ws + k.rstd1), s));
     // qkv = a Wqkv^T + b
-    TM_TRY(tm_op_linear_fwd(dt, d.T, d.nqkv, d.h, ws + k.a, P(o.w_qkv), P(o.b_qkv), nullptr, ws + k.qkv, s));
+    TM_STEP(2.0 * d.T * d.nqkv * d.h, 0,
+            tm_op_linear_fwd(dt, d.T, d.nqkv, d.h, ws + k.a, P(o.w_qkv), P(o.b_qkv), nullptr, ws + k.qkv, s));
     if (c.pos == TM_POS_ROTARY)
-      TM_TRY(tm_op_rotary(dt, c.seq, c.micro_batch, c.n_q_heads + c.n_kv_heads, c.head_dim, d.nqkv, c.rope_theta, 0,
-                          ws + k.qkv, s));
-    TM_TRY(tm_op_attn_fwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
-                          (float *)(ws + k.lse), s));
+      TM_STEP(0, 2 * es * d.T * (c.n_q_heads + c.n_kv_heads) * c.head_dim,
+              tm_op_rotary(dt, c.seq, c.micro_batch, c.n_q_heads + c.n_kv_heads, c.head_dim, d.nqkv, c.rope_theta, 0,
+                           ws + k.qkv, s));
+    TM_STEP(attn_flops, 0,
+            tm_op_attn_fwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
+                           (float *)(ws + k.lse), s));
     // x1 = x + ctx Wout^T + b   (row-parallel projection; its all-reduce is the identity here)
-    TM_TRY(tm_op_linear_fwd(dt, d.T, d.h, d.A, ws + k.ctx, P(o.w_out), P(o.b_out), x, ws + k.x1, s));
+    TM_STEP(2.0 * d.T * d.h * d.A, 0,
+            tm_op_linear_fwd(dt, d.T, d.h, d.A, ws + k.ctx, P(o.w_out), P(o.b_out), x, ws + k.x1, s));
     // c = Norm(x1)
-    TM_TRY(tm_op_norm_fwd(dt, c.norm, d.T, d.h, c.norm_eps, ws + k.x1, P(o.norm2_gain), P(o.norm2_offset), ws + k.c,
-                          (float *)(ws + k.mean2), (float *)(ws + k.rstd2), s));
+    TM_STEP(0, 2 * es * Th,
+            tm_op_norm_fwd(dt, c.norm, d.T, d.h, c.norm_eps, ws + k.x1, P(o.norm2_gain), P(o.norm2_offset), ws + k.c,
+                           (float *)(ws + k.mean2), (float *)(ws + k.rstd2), s));
     // u = c W1^T + b ; g = act(u)
-    TM_TRY(tm_op_linear_fwd(dt, d.T, d.f1, d.h, ws + k.c, P(o.w_fc1), P(o.b_fc1), nullptr, ws + k.u, s));
-    TM_TRY(tm_op_act_fwd(dt, c.act, d.T, d.f, ws + k.u, ws + k.g, s));
+    TM_STEP(2.0 * d.T * d.f1 * d.h, 0,
+            tm_op_linear_fwd(dt, d.T, d.f1, d.h, ws + k.c, P(o.w_fc1), P(o.b_fc1), nullptr, ws + k.u, s));
+    TM_STEP(0, es * d.T * (d.f1 + d.f), tm_op_act_fwd(dt, c.act, d.T, d.f, ws + k.u, ws + k.g, s));
     // y = x1 + g W2^T + b
-    TM_TRY(tm_op_linear_fwd(dt, d.T, d.h, d.f, ws + k.g, P(o.w_fc2), P(o.b_fc2), ws + k.x1, y, s));
+    TM_STEP(2.0 * d.T * d.h * d.f, 0,
+            tm_op_linear_fwd(dt, d.T, d.h, d.f, ws + k.g, P(o.w_fc2), P(o.b_fc2), ws + k.x1, y, s));
   }
   st->have_fwd = true;
   return TM_OK;
@@ -360,6 +463,9 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
   const Plan &pl = st->plan;
   void *red = ws + pl.reduce;
   const bool bias = c.has_bias != 0;
+  const double es = (double)d.es, Th = (double)d.T * d.h;
+  const double attn_flops = 2.0 * c.micro_batch * c.n_q_heads * (double)c.seq * c.seq * c.head_dim;
+  auto mm = [&](int64_t n, int64_t kk) { return 2.0 * d.T * n * kk; };
 
   const void *dy = dy_in;
   for (int l = c.n_layers - 1; l >= 0; --l) {
@@ -372,41 +478,45 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
 
     // y = x1 + g W2^T + b2
     void *dg = (c.act == TM_ACT_SWIGLU) ? (void *)(ws + pl.dmid) : (void *)(ws + pl.dwide);
-    TM_TRY(tm_op_linear_dgrad(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, s));
-    TM_TRY(tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), s));
-    if (bias) TM_TRY(tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, s));
+    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_dgrad(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, s));
+    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), s));
+    if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, s));
     // activation
     void *du = ws + pl.dwide;
-    TM_TRY(tm_op_act_bwd(dt, c.act, d.T, d.f, dg, ws + k.u, du, s));
+    TM_STEP(0, es * d.T * (d.f + 2 * d.f1), tm_op_act_bwd(dt, c.act, d.T, d.f, dg, ws + k.u, du, s));
     // u = c W1^T + b1
     void *dc = ws + pl.dnorm;
-    TM_TRY(tm_op_linear_dgrad(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, s));
-    TM_TRY(tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), s));
-    if (bias) TM_TRY(tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, s));
+    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_dgrad(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, s));
+    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), s));
+    if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, s));
     // c = Norm(x1): dx1 = dy + norm gradient
     void *dx1 = ws + pl.dx1;
-    TM_TRY(tm_op_norm_bwd(dt, c.norm, d.T, d.h, dc, ws + k.x1, (const float *)(ws + k.mean2),
-                          (const float *)(ws + k.rstd2), P(o.norm2_gain), dy, dx1, G(o.norm2_gain),
-                          G(o.norm2_offset), red, s));
+    TM_STEP(0, 4 * es * Th,
+            tm_op_norm_bwd(dt, c.norm, d.T, d.h, dc, ws + k.x1, (const float *)(ws + k.mean2),
+                           (const float *)(ws + k.rstd2), P(o.norm2_gain), dy, dx1, G(o.norm2_gain),
+                           G(o.norm2_offset), red, s));
     // x1 = x + ctx Wout^T + bout
-    TM_TRY(tm_op_linear_dgrad(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, s));
-    TM_TRY(tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), s));
-    if (bias) TM_TRY(tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, s));
+    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_dgrad(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, s));
+    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), s));
+    if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, s));
     // attention, rotary
-    TM_TRY(tm_op_attn_bwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
-                          ws + pl.dctx, (const float *)(ws + k.lse), (float *)(ws + pl.dvec), ws + pl.dqkv, s));
+    TM_STEP(2 * attn_flops, 0,
+            tm_op_attn_bwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
+                           ws + pl.dctx, (const float *)(ws + k.lse), (float *)(ws + pl.dvec), ws + pl.dqkv, s));
     if (c.pos == TM_POS_ROTARY)
-      TM_TRY(tm_op_rotary(dt, c.seq, c.micro_batch, c.n_q_heads + c.n_kv_heads, c.head_dim, d.nqkv, c.rope_theta, 1,
-                          ws + pl.dqkv, s));
+      TM_STEP(0, 2 * es * d.T * (c.n_q_heads + c.n_kv_heads) * c.head_dim,
+              tm_op_rotary(dt, c.seq, c.micro_batch, c.n_q_heads + c.n_kv_heads, c.head_dim, d.nqkv, c.rope_theta, 1,
+                           ws + pl.dqkv, s));
     // qkv = a Wqkv^T + b
     void *da = ws + pl.dnorm;
-    TM_TRY(tm_op_linear_dgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, s));
-    TM_TRY(tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), s));
-    if (bias) TM_TRY(tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, s));
+    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_dgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, s));
+    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), s));
+    if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, s));
     // a = Norm(x): dx = dx1 + norm gradient
-    TM_TRY(tm_op_norm_bwd(dt, c.norm, d.T, d.h, da, ws + k.x, (const float *)(ws + k.mean1),
-                          (const float *)(ws + k.rstd1), P(o.norm1_gain), dx1, dx, G(o.norm1_gain),
-                          G(o.norm1_offset), red, s));
+    TM_STEP(0, 4 * es * Th,
+            tm_op_norm_bwd(dt, c.norm, d.T, d.h, da, ws + k.x, (const float *)(ws + k.mean1),
+                           (const float *)(ws + k.rstd1), P(o.norm1_gain), dx1, dx, G(o.norm1_gain),
+                           G(o.norm1_offset), red, s));
     dy = dx;
   }
   return TM_OK;
@@ -416,6 +526,10 @@ extern "C" int tm_adam_step(tm_stage_t *st, const tm_adam_hparams_t *hp, int64_t
   if (!st || !hp) return fail(TM_EINVAL, "adam_step: NULL argument");
   const bool lowp = st->cfg.dtype == TM_DTYPE_BF16;
   float *p = lowp ? st->buf.master : (float *)st->buf.params;
-  return tm_adam_step_flat(st->n_params, p, st->buf.grads, st->buf.exp_avg, st->buf.exp_avg_sq,
-                           lowp ? st->buf.params : nullptr, hp, step, stream);
+  hipStream_t s = (hipStream_t)stream;
+  const double per_param = 28.0 + (lowp ? 2.0 : 0.0) + (hp->zero_grads ? 4.0 : 0.0);
+  TM_STEP(0, per_param * (double)st->n_params,
+          tm_adam_step_flat(st->n_params, p, st->buf.grads, st->buf.exp_avg, st->buf.exp_avg_sq,
+                            lowp ? st->buf.params : nullptr, hp, step, stream));
+  return TM_OK;
 }
