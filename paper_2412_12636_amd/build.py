@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtm_stage.so")
 
-SOURCES = ["stage.hip", "norm.hip", "elementwise.hip", "gemm_generic.hip", "gemm_mfma.hip", "linear.hip",
+SOURCES = ["stage.hip", "norm.hip", "elementwise.hip", "gemm_generic.hip", "gemm_mfma.hip", "gemm_mfma_nt.hip", "gemm_mfma_nn.hip", "gemm_mfma_tn.hip", "linear.hip",
            "attn_generic.hip", "attn_mfma.hip", "attn.hip"]
 
 # packed fp32 VALU forms are switched off on purpose (build flags)
@@ -28,7 +28,8 @@ def _hipcc() -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [_hipcc(), *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    extra = os.environ.get("TM_EXTRA_HIPCC_FLAGS", "").split()   # tuning aid, e.g. -DTM_GEMM_BK=32
+    cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed on {src}:\n{r.stdout}\n{r.stderr}")

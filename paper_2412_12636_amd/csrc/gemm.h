@@ -27,5 +27,6 @@ int gemm_generic(int dtype, const GemmArgs &g, hipStream_t s);
 // 16-byte aligned base pointers.
 bool gemm_mfma_supported(const GemmArgs &g);
 int gemm_mfma(const GemmArgs &g, hipStream_t s);
+void gemm_pick_tile(int64_t M, int64_t N, int &bm, int &bn);
 
 }  // namespace tmk

@@ -1,0 +1,587 @@
+// bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+//
+// One 256-thread block (four wavefronts in a 2x2 grid) owns a BM x BN output tile and walks the
+// reduction axis BK elements at a time through a ring of NSTAGE LDS buffers.
+//
+// Main kernel (gemm_direct_kernel).  Operand tiles go from global memory STRAIGHT into LDS
+// (buffer_load ... lds, 16 bytes per lane): no staging registers, no LDS store instructions.  A
+// wave-wide load fills 1024 contiguous LDS bytes, so any layout permutation is applied on the
+// global side: each lane fetches the 16-byte chunk that belongs at its LDS position.
+//   * Operand with contiguous reduction axis (x and W in y = x W^T, dy in dx = dy W): LDS tile
+//     [row][BK], chunks XOR-swizzled by row; MFMA fragments are plain 16-byte LDS reads.
+//   * Operand with strided reduction axis (W in dx = dy W; dy and x in dW = dy^T x): LDS tile
+//     [k][rows], i.e. the global layout; MFMA fragments come from the transposing LDS read
+//     ds_read_b64_tr_b16, which hands each lane four consecutive k of one row.  No transposed copies
+//     in HBM, no register shuffles.
+// Loads run NSTAGE-1 steps ahead; one barrier per step; waits on the loads are explicit
+// (s_waitcnt vmcnt), since the compiler does not track the LDS side of these loads.
+// A reduction length that is not a multiple of BK on a contiguous-reduction operand cannot be
+// masked on this path; such shapes take the staged kernel below.
+//
+// Staged kernel (gemm_staged_kernel): 128x128 tile, global -> registers -> LDS with the reduction
+// tail masked on the way; strided operands are transposed in registers.  Any K that is a multiple of 8.
+//
+// Global accesses use buffer descriptors: reads past the end of a tensor return zero and writes
+// past the end are dropped, so ragged M / N edges need no branches.
+//
+// Epilogue: the MFMA operands are passed swapped, so an accumulator tile is C^T and every lane owns
+// four CONSECUTIVE output columns of one row: 8-byte bf16 / 16-byte fp32 stores.
+//
+// Block index -> tile mapping: consecutive hardware block ids land on different XCDs (8 per chip,
+// each with its own L2); ids are re-numbered so that every XCD works on a contiguous range of
+// tiles, with the M tiles of one weight column adjacent.
+#pragma once
+#include <string>
+
+#include "gemm.h"
+
+namespace tmk {
+
+typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int v4u32 __attribute__((__vector_size__(16)));  // the buffer builtins' own vector type
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+
+constexpr int NXCD = 8;
+
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buf_load16(rsrc_t r, uint32_t voff, uint32_t soff) {
+  return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+}
+
+struct MfmaGemmParams {
+  int M, N, K;
+  const bf16 *A;
+  int64_t lda;  // the non-unit stride of A
+  const bf16 *B;
+  int64_t ldb;
+  void *C;
+  int64_t ldc;
+  const bf16 *bias;
+  const bf16 *residual;
+  int tiles_m, tiles_n;
+  uint32_t a_bytes, b_bytes, c_bytes;  // extents of the tensors, for the buffer descriptors
+};
+
+// Block id -> output tile.  Hardware block ids go round-robin over the 8 XCDs; ids are first
+// re-numbered so that each XCD owns a contiguous range, then the range is walked in groups of
+// GROUP_M row-tiles by all column-tiles, row-tile fastest.  The blocks an XCD runs at the same time
+// then form a roughly square patch of tiles and share both operands' slices in that XCD's L2.
+constexpr int GROUP_M = 8;
+__device__ __forceinline__ void tile_of_block(const MfmaGemmParams &p, int BM, int BN, int &m0, int &n0) {
+  const int nblk = gridDim.x, pid = blockIdx.x;
+  const int xcd = pid % NXCD, local = pid / NXCD;
+  const int base = nblk / NXCD, rem = nblk % NXCD;
+  const int lid = xcd * base + (xcd < rem ? xcd : rem) + local;
+  const int per_group = GROUP_M * p.tiles_n;
+  const int group = lid / per_group, first_m = group * GROUP_M;
+  const int gsz = p.tiles_m - first_m < GROUP_M ? p.tiles_m - first_m : GROUP_M;
+  const int in_group = lid - group * per_group;
+  m0 = (first_m + in_group % gsz) * BM;
+  n0 = (in_group / gsz) * BN;
+}
+
+// ---- epilogue shared by both kernels -------------------------------------------------------------
+// acc[i][j] is the transposed 32x32 tile (rows = output columns): register 4q+e of lane l holds
+// C[row = .. + l%32][col = .. + 8q + 4*(l/32) + e].   EPI 0: bf16 C = acc (+bias) (+residual);
+// EPI 1: fp32 C += acc.
+template <int TM, int TN, int EPI>
+__device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (&acc)[TM][TN], int row_base,
+                                         int col_base, int l32, int hh) {
+  const uint32_t c_elem = EPI == 0 ? 2u : 4u;
+  const rsrc_t rc = make_rsrc(p.C, p.c_bytes);
+  const rsrc_t rres = make_rsrc(p.residual ? (const void *)p.residual : p.C, p.c_bytes);
+  const rsrc_t rbias = make_rsrc(p.bias ? (const void *)p.bias : p.C, (uint32_t)p.N * 2u);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int col = col_base + j * 32 + 8 * q + 4 * hh;
+      const bool col_ok = col < p.N;  // N is a multiple of 8: the four columns are in or out together
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (EPI == 0 && p.bias) {
+        const u32x2 braw = __builtin_bit_cast(
+            u32x2, __builtin_amdgcn_raw_buffer_load_b64(rbias, col_ok ? (uint32_t)col * 2u : 0xfffffff0u, 0, 0));
+        bv[0] = __builtin_bit_cast(float, braw[0] << 16);
+        bv[1] = __builtin_bit_cast(float, braw[0] & 0xffff0000u);
+        bv[2] = __builtin_bit_cast(float, braw[1] << 16);
+        bv[3] = __builtin_bit_cast(float, braw[1] & 0xffff0000u);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = row_base + i * 32 + l32;
+        const uint32_t off = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * c_elem) : 0xfffffff0u;
+        if (EPI == 0) {
+          float r[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) r[e] = acc[i][j][4 * q + e] + bv[e];
+          if (p.residual) {
+            const u32x2 rr = __builtin_bit_cast(u32x2, __builtin_amdgcn_raw_buffer_load_b64(rres, off, 0, 0));
+            r[0] += __builtin_bit_cast(float, rr[0] << 16);
+            r[1] += __builtin_bit_cast(float, rr[0] & 0xffff0000u);
+            r[2] += __builtin_bit_cast(float, rr[1] << 16);
+            r[3] += __builtin_bit_cast(float, rr[1] & 0xffff0000u);
+          }
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16)r[e];
+          __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rc, off, 0, 0);
+        } else {
+          const f32x4 old = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rc, off, 0, 0));
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = old[e] + acc[i][j][4 * q + e];
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u32, o), rc, off, 0, 0);
+        }
+      }
+    }
+  }
+}
+
+// =================================================================================================
+// direct-to-LDS kernel
+// =================================================================================================
+
+// ---- operand with contiguous reduction axis: element (r, k) at base[r*ld + k]; LDS [R][BK] --------
+template <int R, int BK> struct DirectKC {
+  static constexpr int ROWB = BK * 2;               // bytes per LDS row
+  static constexpr int CPR = BK / 8;                // 16-byte chunks per row
+  static constexpr int RPL = 64 / CPR;              // rows covered by one wave-wide load
+  static constexpr int NLOAD = R / (4 * RPL);       // loads per wave and step (R is a multiple of 64)
+  static constexpr int BYTES = R * ROWB;
+  // rows that are 8 apart in a fragment read must not share banks: XOR the chunk index with low row bits
+  static __device__ __forceinline__ int swz(int row) {
+    return BK == 64 ? ((row ^ (row >> 3)) & 7) : ((row >> 1) & 3);
+  }
+  uint32_t voff[NLOAD];
+  __device__ __forceinline__ void init(int64_t ld, int row0, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int row = (i * 4 + wave) * RPL + lane / CPR;
+      const int c = (lane % CPR) ^ swz(row);  // logical chunk that belongs at this lane's LDS position
+      voff[i] = (uint32_t)(((int64_t)(row0 + row) * ld + c * 8) * 2);
+    }
+  }
+  __device__ __forceinline__ void issue(rsrc_t rs, char *tile, int k0, int64_t /*ld*/, int wave) const {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * 4 + wave) * 1024), 16, voff[i],
+                                               (uint32_t)k0 * 2u, 0, 0);
+  }
+  // fragment of the 32-row block starting at r32: lane's row r32 + lane%32, reduction slots 16ks + 8hh + 0..7
+  static __device__ __forceinline__ bf16x8 frag(const char *tile, int r32, int ks, int lane) {
+    const int r = r32 + (lane & 31), hh = lane >> 5;
+    return *reinterpret_cast<const bf16x8 *>(tile + r * ROWB + (((2 * ks + hh) ^ swz(r)) << 4));
+  }
+};
+
+// ---- operand with strided reduction axis: element (r, k) at base[k*ld + r]; LDS [BK][R] ------------
+template <int R, int BK> struct DirectKS {
+  static constexpr int ROWB = R * 2;                // bytes per LDS k-row
+  static constexpr int CPR = R / 8;                 // chunks per k-row (32 or 16)
+  static constexpr int NLOAD = BK * CPR / 256;      // loads per wave and step
+  static constexpr int BYTES = BK * ROWB;
+  // The transposing read of a 16-lane group touches 4 k-rows x 32 contiguous bytes, a half-wave the
+  // neighbouring 32 bytes as well; k-rows alias in the banks (row pitch 256/512 bytes).  The position
+  // of chunk c in k-row kk spreads the four k-rows over distinct 32-byte windows and sends the
+  // neighbouring group to the other 128-byte half.
+  // (With 24 chunks per k-row the row pitch is 384 bytes, consecutive k-rows already differ by 128 bytes,
+  // and the XOR of bits 2:1 alone separates everything.)
+  static __device__ __forceinline__ int place(int c, int kk) {
+    return CPR % 16 == 0 ? c ^ (((kk & 3) << 1) | (((c >> 1) & 1) << 3)) : c ^ ((kk & 3) << 1);
+  }
+  static __device__ __forceinline__ int unplace(int pc, int kk) {
+    const int low = pc ^ ((kk & 3) << 1);           // bits 2:1 restored
+    return CPR % 16 == 0 ? low ^ (((low >> 1) & 1) << 3) : low;
+  }
+  uint32_t voff[NLOAD];
+  __device__ __forceinline__ void init(int64_t ld, int row0, int wave, int lane) {
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+      const int idx = (i * 4 + wave) * 64 + lane;
+      const int kk = idx / CPR, c = unplace(idx % CPR, kk);
+      voff[i] = (uint32_t)(((int64_t)kk * ld + row0 + c * 8) * 2);
+    }
+  }
+  __device__ __forceinline__ void issue(rsrc_t rs, char *tile, int k0, int64_t ld, int wave) const {
+    const uint32_t soff = (uint32_t)((int64_t)k0 * ld * 2);
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * 4 + wave) * 1024), 16, voff[i], soff, 0, 0);
+  }
+  // ds_read_b64_tr_b16: within 16 lanes, lane i receives element (i%4) of the 8-byte pieces addressed
+  // by lanes i/4, i/4+4, i/4+8, i/4+12.  With lane s addressing T[k0 + s/4][r0 + 4*(s%4) ..+3], lane i
+  // ends up with T[k0 .. k0+3][r0 + i]: four consecutive k of one row.
+  static __device__ __forceinline__ bf16x8 frag(const char *tile, int r32, int ks, int lane) {
+    const int g = lane >> 4, s = lane & 15;
+    const int r = r32 + 16 * (g & 1) + 4 * (s & 3);
+    const int c = r >> 3, half = (r >> 2) & 1;
+    union { s16x4 h[2]; bf16x8 v; } x;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int kk = 16 * ks + 8 * (g >> 1) + 4 * t + (s >> 2);
+      const char *a = tile + kk * ROWB + (place(c, kk) << 4) + (half << 3);
+      x.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(a));
+    }
+    return x.v;
+  }
+};
+
+template <int R, int BK, bool KC> struct DirectSel { typedef DirectKC<R, BK> type; };
+template <int R, int BK> struct DirectSel<R, BK, false> { typedef DirectKS<R, BK> type; };
+
+// Compile-time construction of the scheduler's issue order (the builtin wants literal constants).
+// Masks: 0x008 MFMA, 0x020 global/buffer load, 0x100 LDS read.
+template <int MASK, int N> __device__ __forceinline__ void sched_group() {
+  if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+template <int KS, int MF, int LOADS, int DSN, int ks, int i> __device__ __forceinline__ void sched_slices() {
+  if constexpr (ks < KS) {
+    sched_group<0x008, 1>();
+    if constexpr (ks == 0) sched_group<0x020, LOADS * (i + 1) / MF - LOADS * i / MF>();
+    if constexpr (ks + 1 < KS) sched_group<0x100, DSN * (i + 1) / MF - DSN * i / MF>();
+    if constexpr (i + 1 < MF)
+      sched_slices<KS, MF, LOADS, DSN, ks, i + 1>();
+    else
+      sched_slices<KS, MF, LOADS, DSN, ks + 1, 0>();
+  }
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+// Tiles of at most 256x128 keep their accumulators in 128 registers: two blocks fit on a compute unit
+// (two waves per SIMD), so one block's barrier and load waits are covered by the other's MFMAs.
+template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256, (BM * BN <= 256 * 128 ? 2 : 1)) void gemm_direct_kernel(const MfmaGemmParams p) {
+  extern __shared__ __align__(16) char lds[];
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  typedef typename DirectSel<BM, BK, A_KC>::type LA;
+  typedef typename DirectSel<BN, BK, B_KC>::type LB;
+  constexpr int STAGE = LA::BYTES + LB::BYTES;
+  constexpr int LOADS = LA::NLOAD + LB::NLOAD;
+  static_assert((NSTAGE - 2) * LOADS <= 63, "vmcnt field");
+
+  int m0, n0;
+  tile_of_block(p, BM, BN, m0, n0);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  LA la;
+  LB lb;
+  const rsrc_t ra = make_rsrc(p.A, p.a_bytes), rb = make_rsrc(p.B, p.b_bytes);
+  la.init(p.lda, m0, wave, lane);
+  lb.init(p.ldb, n0, wave, lane);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nk = (p.K + BK - 1) / BK;
+  // Loads are issued unconditionally (a step past K reads zeros or unused rows) so that the number
+  // of loads in flight at each wait is a compile-time constant.
+#pragma unroll
+  for (int s = 0; s < NSTAGE - 1; ++s) {
+    la.issue(ra, lds + s * STAGE, s * BK, p.lda, wave);
+    lb.issue(rb, lds + s * STAGE + LA::BYTES, s * BK, p.ldb, wave);
+  }
+  int cur = 0, nxt = NSTAGE - 1;  // ring positions of step kt and of step kt + NSTAGE - 1
+  for (int kt = 0; kt < nk; ++kt) {
+    wait_vmcnt<(NSTAGE - 2) * LOADS>();  // this wave's part of step kt has landed
+    __builtin_amdgcn_s_barrier();        // ... everyone's has; and everyone is done reading step kt-1
+    const char *As = lds + cur * STAGE;
+    const char *Bs = As + LA::BYTES;
+    // Fragments are double buffered in registers: the LDS reads of reduction slice ks+1 are issued
+    // before the MFMAs of slice ks.
+    constexpr int KS = BK / 16;
+    bf16x8 a[2][TM], b[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[0][i] = LA::frag(As, wm * WM + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[0][j] = LB::frag(Bs, wn * WN + j * 32, 0, lane);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[(ks + 1) & 1][i] = LA::frag(As, wm * WM + i * 32, ks + 1, lane);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[(ks + 1) & 1][j] = LB::frag(Bs, wn * WN + j * 32, ks + 1, lane);
+      }
+      if (ks == 0) {
+        // The look-ahead loads write LDS, so the compiler keeps them ordered against the LDS reads:
+        // placed here they can sink between the MFMAs of slice 0 instead of delaying the first reads.
+        la.issue(ra, lds + nxt * STAGE, (kt + NSTAGE - 1) * BK, p.lda, wave);
+        lb.issue(rb, lds + nxt * STAGE + LA::BYTES, (kt + NSTAGE - 1) * BK, p.ldb, wave);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
+    }
+    // Issue order for the scheduler (the step is one basic block): first the LDS reads of slice 0; then
+    // the MFMAs of slice ks, with this step's global->LDS loads (slice 0 only) and the LDS reads of
+    // slice ks+1 spread between them.  With one wave per SIMD nothing else can cover these latencies.
+    {
+      constexpr int MF = TM * TN;                                     // MFMAs per slice
+      constexpr int DSN = TM * (A_KC ? 1 : 2) + TN * (B_KC ? 1 : 2);  // LDS read instructions per slice
+      sched_group<0x100, DSN>();
+      sched_slices<KS, MF, LOADS, DSN, 0, 0>();
+    }
+    cur = cur + 1 == NSTAGE ? 0 : cur + 1;
+    nxt = nxt + 1 == NSTAGE ? 0 : nxt + 1;
+  }
+  wait_vmcnt<0>();  // drain the look-ahead loads before the block may exit
+  epilogue<TM, TN, EPI>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
+}
+
+// =================================================================================================
+// staged kernel (any K that is a multiple of 8): 128x128x64, registers in between
+// =================================================================================================
+constexpr int SBK = 64, SROWB = SBK * 2;
+__device__ __forceinline__ int sswz(int row) { return (row ^ (row >> 3)) & 7; }
+
+template <int R> struct StagedKC {
+  static constexpr int NCH = R / 32;
+  u32x4 reg[NCH];
+  uint32_t voff[NCH];
+  __device__ __forceinline__ void init(int64_t ld, int row0) {
+    const int c = threadIdx.x & 7, r0 = threadIdx.x >> 3;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) voff[i] = (uint32_t)(((int64_t)(row0 + r0 + 32 * i) * ld + c * 8) * 2);
+  }
+  __device__ __forceinline__ void g2r(rsrc_t rs, int k0) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) reg[i] = buf_load16(rs, voff[i], (uint32_t)k0 * 2);
+  }
+  // the mask is applied here, after the MFMAs that overlap the loads, so that it forces no early wait
+  __device__ __forceinline__ void r2s(char *lds, int k_left) const {
+    const int c = threadIdx.x & 7, r0 = threadIdx.x >> 3;
+    const bool drop = c * 8 >= k_left;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int r = r0 + 32 * i;
+      u32x4 v = reg[i];
+      if (drop) v = u32x4{0u, 0u, 0u, 0u};
+      *reinterpret_cast<u32x4 *>(lds + r * SROWB + ((c ^ sswz(r)) << 4)) = v;
+    }
+  }
+};
+
+template <int R> struct StagedKS {
+  static constexpr int RB = R / 8, KG_STEP = 256 / RB, NB = 16 / KG_STEP;
+  u32x4 reg[NB][4];
+  uint32_t voff[NB];
+  int64_t ldb2;
+  __device__ __forceinline__ void init(int64_t ld, int row0) {
+    const int rb = threadIdx.x % RB, kg0 = threadIdx.x / RB;
+    ldb2 = ld * 2;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) voff[i] = (uint32_t)(((int64_t)(kg0 + i * KG_STEP) * 4 * ld + row0 + rb * 8) * 2);
+  }
+  __device__ __forceinline__ void g2r(rsrc_t rs, int k0) {
+    const uint32_t base = (uint32_t)((int64_t)k0 * ldb2);
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) reg[i][j] = buf_load16(rs, voff[i] + (uint32_t)(j * ldb2), base);
+  }
+  // 4 k-rows x 8 columns per thread are transposed in registers into 8 pieces of 4 k-values
+  __device__ __forceinline__ void r2s(char *lds, int /*k_left*/) const {
+    const int rb = threadIdx.x % RB, kg0 = threadIdx.x / RB;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int kg = kg0 + i * KG_STEP;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int w = e >> 1;
+        u32x2 o;
+        if (e & 1) {
+          o[0] = (reg[i][0][w] >> 16) | (reg[i][1][w] & 0xffff0000u);
+          o[1] = (reg[i][2][w] >> 16) | (reg[i][3][w] & 0xffff0000u);
+        } else {
+          o[0] = (reg[i][0][w] & 0xffffu) | (reg[i][1][w] << 16);
+          o[1] = (reg[i][2][w] & 0xffffu) | (reg[i][3][w] << 16);
+        }
+        const int r = rb * 8 + e;
+        *reinterpret_cast<u32x2 *>(lds + r * SROWB + (((kg >> 1) ^ sswz(r)) << 4) + ((kg & 1) << 3)) = o;
+      }
+    }
+  }
+};
+template <int R, bool KC> struct StagedSel { typedef StagedKC<R> type; };
+template <int R> struct StagedSel<R, false> { typedef StagedKS<R> type; };
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256) void gemm_staged_kernel(const MfmaGemmParams p) {
+  constexpr int BM = 128, BN = 128, WM = 64, WN = 64, TM = 2, TN = 2;
+  constexpr int A_BYTES = BM * SROWB, STAGE = (BM + BN) * SROWB;
+  __shared__ __align__(16) char lds[2 * STAGE];
+  int m0, n0;
+  tile_of_block(p, BM, BN, m0, n0);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wm = wave >> 1, wn = wave & 1, l32 = lane & 31, hh = lane >> 5;
+  typename StagedSel<BM, A_KC>::type la;
+  typename StagedSel<BN, B_KC>::type lb;
+  const rsrc_t ra = make_rsrc(p.A, p.a_bytes), rb = make_rsrc(p.B, p.b_bytes);
+  la.init(p.lda, m0);
+  lb.init(p.ldb, n0);
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  const int nk = (p.K + SBK - 1) / SBK;
+  la.g2r(ra, 0);
+  lb.g2r(rb, 0);
+  la.r2s(lds, p.K);
+  lb.r2s(lds + A_BYTES, p.K);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {
+      la.g2r(ra, (kt + 1) * SBK);
+      lb.g2r(rb, (kt + 1) * SBK);
+    }
+    const char *As = lds + cur * STAGE, *Bs = As + A_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < SBK / 16; ++ks) {
+      bf16x8 a[TM], b[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int r = wm * WM + i * 32 + l32;
+        a[i] = *reinterpret_cast<const bf16x8 *>(As + r * SROWB + (((2 * ks + hh) ^ sswz(r)) << 4));
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int r = wn * WN + j * 32 + l32;
+        b[j] = *reinterpret_cast<const bf16x8 *>(Bs + r * SROWB + (((2 * ks + hh) ^ sswz(r)) << 4));
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) {
+      char *nx = lds + (cur ^ 1) * STAGE;
+      la.r2s(nx, p.K - (kt + 1) * SBK);
+      lb.r2s(nx + A_BYTES, p.K - (kt + 1) * SBK);
+    }
+    __syncthreads();
+  }
+  epilogue<TM, TN, EPI>(p, acc, m0 + wm * WM, n0 + wn * WN, l32, hh);
+}
+
+// =================================================================================================
+// host side: one layout (A_KC, B_KC, EPI) per translation unit, so that the variants compile in parallel
+// =================================================================================================
+template <bool A_KC, bool B_KC, int EPI> static MfmaGemmParams make_params(const GemmArgs &g, int BM, int BN) {
+  MfmaGemmParams p;
+  p.M = (int)g.M;
+  p.N = (int)g.N;
+  p.K = (int)g.K;
+  p.A = (const bf16 *)g.A;
+  p.lda = A_KC ? g.a_rs : g.a_cs;
+  p.B = (const bf16 *)g.B;
+  p.ldb = B_KC ? g.b_rs : g.b_cs;
+  p.C = g.C;
+  p.ldc = g.ldc;
+  p.bias = (const bf16 *)g.bias;
+  p.residual = (const bf16 *)g.residual;
+  p.tiles_m = (int)ceil_div(g.M, BM);
+  p.tiles_n = (int)ceil_div(g.N, BN);
+  p.a_bytes = (uint32_t)((A_KC ? g.M * g.a_rs : g.K * g.a_cs) * 2);
+  p.b_bytes = (uint32_t)((B_KC ? g.N * g.b_rs : g.K * g.b_cs) * 2);
+  p.c_bytes = (uint32_t)(g.M * g.ldc * (EPI == 0 ? 2 : 4));
+  return p;
+}
+
+static std::string kernel_tag(const char *base, int bm, int bn, int bk, int ns, bool akc, bool bkc, int epi) {
+  return std::string(base) + "<" + std::to_string(bm) + "," + std::to_string(bn) + "," + std::to_string(bk) + "," +
+         std::to_string(ns) + "," + (akc ? "true" : "false") + "," + (bkc ? "true" : "false") + "," +
+         std::to_string(epi) + ">";
+}
+
+template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, int EPI>
+static int launch_direct(const GemmArgs &g, hipStream_t s) {
+  const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, BM, BN);
+  constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
+  static_assert(lds_bytes <= 160 * 1024, "LDS");
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_direct_kernel<BM, BN, BK, NSTAGE, A_KC, B_KC, EPI>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+      return fail(TM_ELAUNCH, "gemm_mfma: cannot reserve %d bytes of LDS", lds_bytes);
+    attr_set = true;
+  }
+  const int64_t nblk = (int64_t)p.tiles_m * p.tiles_n;
+  if (nblk > 0x7fffffff) return fail(TM_ESIZE, "gemm_mfma: too many tiles");
+  static const std::string name = kernel_tag("gemm_direct_kernel", BM, BN, BK, NSTAGE, A_KC, B_KC, EPI);
+  g_last_kernel = name.c_str();
+  gemm_direct_kernel<BM, BN, BK, NSTAGE, A_KC, B_KC, EPI><<<dim3((unsigned)nblk), 256, lds_bytes, s>>>(p);
+  return check_launch("gemm_direct");
+}
+
+template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs &g, hipStream_t s) {
+  const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, 128, 128);
+  static const std::string name = kernel_tag("gemm_staged_kernel", 128, 128, 64, 2, A_KC, B_KC, EPI);
+  g_last_kernel = name.c_str();
+  gemm_staged_kernel<A_KC, B_KC, EPI><<<dim3((unsigned)(p.tiles_m * p.tiles_n)), 256, 0, s>>>(p);
+  return check_launch("gemm_staged");
+}
+
+#ifndef TM_GEMM_BK
+#define TM_GEMM_BK 64
+#endif
+#ifndef TM_GEMM_NSTAGE
+#define TM_GEMM_NSTAGE 2
+#endif
+
+// The variants the host side launches are instantiated explicitly (an implicit instantiation from inside
+// the launcher templates leaves the host-side kernel handle undefined with this compiler).
+#define TM_GEMM_INSTANTIATE(AKC, BKC, EPI)                                                                       \
+  template __global__ void gemm_direct_kernel<256, 256, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_direct_kernel<256, 192, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_direct_kernel<192, 256, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_direct_kernel<192, 192, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_direct_kernel<256, 128, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_direct_kernel<128, 256, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_direct_kernel<192, 128, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_direct_kernel<128, 192, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_direct_kernel<128, 128, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams);
+
+template <bool A_KC, bool B_KC, int EPI> static int launch_layout(const GemmArgs &g, hipStream_t s) {
+  constexpr int BK = TM_GEMM_BK, NS = TM_GEMM_NSTAGE;
+  const bool k_tail = (A_KC || B_KC) && (g.K % BK != 0);  // a contiguous-reduction operand cannot be masked
+  if (k_tail) return launch_staged<A_KC, B_KC, EPI>(g, s);
+  int bm = 128, bn = 128;
+  gemm_pick_tile(g.M, g.N, bm, bn);
+#define TM_TRY_TILE(BM_, BN_) \
+  if (bm == BM_ && bn == BN_) return launch_direct<BM_, BN_, BK, NS, A_KC, B_KC, EPI>(g, s);
+  TM_TRY_TILE(256, 256)
+  TM_TRY_TILE(256, 192)
+  TM_TRY_TILE(192, 256)
+  TM_TRY_TILE(192, 192)
+  TM_TRY_TILE(256, 128)
+  TM_TRY_TILE(128, 256)
+  TM_TRY_TILE(192, 128)
+  TM_TRY_TILE(128, 192)
+#undef TM_TRY_TILE
+  return launch_direct<128, 128, BK, NS, A_KC, B_KC, EPI>(g, s);
+}
+
+}  // namespace tmk

@@ -1,0 +1,7 @@
+// MFMA GEMM kernels for one operand layout (see gemm_mfma_impl.h).
+#include "gemm_mfma_impl.h"
+
+namespace tmk {
+TM_GEMM_INSTANTIATE(false, false, 1)
+int gemm_mfma_tn(const GemmArgs &g, hipStream_t s) { return launch_layout<false, false, 1>(g, s); }
+}  // namespace tmk
