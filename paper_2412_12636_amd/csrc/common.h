@@ -49,6 +49,28 @@ template <typename T> __device__ __forceinline__ void store_vec(T *p, const floa
   *reinterpret_cast<u32x4 *>(p) = u.raw;
 }
 
+// ---- buffer-descriptor access: reads past `bytes` return zero, writes past it are dropped, so
+// ragged edges need no branches (a branch around a load keeps the compiler from batching loads) ----
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ __forceinline__ rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, bytes, 0x00020000);
+}
+template <typename T> __device__ __forceinline__ void buf_load_vec(rsrc_t r, uint32_t byte_off, float (&out)[Vec<T>::N]) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  union { u32x4 raw; Vec<T> v; } u;
+  u.raw = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0));
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) out[i] = to_f32(u.v.v[i]);
+}
+template <typename T> __device__ __forceinline__ void buf_store_vec(rsrc_t r, uint32_t byte_off, const float (&in)[Vec<T>::N]) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  typedef unsigned int v4u32 __attribute__((__vector_size__(16)));
+  union { u32x4 raw; Vec<T> v; } u;
+#pragma unroll
+  for (int i = 0; i < Vec<T>::N; ++i) u.v.v[i] = from_f32<T>(in[i]);
+  __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u32, u.raw), r, byte_off, 0, 0);
+}
+
 // ---- reductions ---------------------------------------------------------------
 constexpr int kWave = 64;
 

@@ -136,7 +136,9 @@ __device__ __forceinline__ void adam_one(float &p, float g, float &m, float &v, 
   p = p - a.lr * (mhat / (sqrtf(vhat) + a.eps) + a.weight_decay * p);
 }
 
-// 4 elements per thread and iteration; reads g,p,m,v and writes p,m,v (+ bf16 p, + zeroed g)
+// One 16-byte chunk of each array per thread, blocks in address order (no grid-stride loop: with a
+// long stride the HBM channels see scattered pages and the rate drops by a fifth), streaming
+// (non-temporal) accesses since nothing is re-read.  Reads g,p,m,v; writes p,m,v (+ bf16 p, + zeroed g).
 template <bool LOWP, bool ZERO>
 __global__ __launch_bounds__(kEwThreads) void adam_kernel(float *__restrict__ p, float *__restrict__ g,
                                                          float *__restrict__ m, float *__restrict__ v,
@@ -144,11 +146,12 @@ __global__ __launch_bounds__(kEwThreads) void adam_kernel(float *__restrict__ p,
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
   const int64_t nvec = n / 4;
-  for (int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x; i < nvec; i += (int64_t)gridDim.x * kEwThreads) {
-    f32x4 pv = reinterpret_cast<f32x4 *>(p)[i];
-    f32x4 gv = reinterpret_cast<const f32x4 *>(g)[i];
-    f32x4 mv = reinterpret_cast<f32x4 *>(m)[i];
-    f32x4 vv = reinterpret_cast<f32x4 *>(v)[i];
+  const int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
+  if (i < nvec) {
+    f32x4 pv = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(p) + i);
+    f32x4 gv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g) + i);
+    f32x4 mv = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(m) + i);
+    f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(v) + i);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       float pk = pv[k], mk = mv[k], vk = vv[k];
@@ -157,19 +160,19 @@ __global__ __launch_bounds__(kEwThreads) void adam_kernel(float *__restrict__ p,
       mv[k] = mk;
       vv[k] = vk;
     }
-    reinterpret_cast<f32x4 *>(p)[i] = pv;
-    reinterpret_cast<f32x4 *>(m)[i] = mv;
-    reinterpret_cast<f32x4 *>(v)[i] = vv;
+    __builtin_nontemporal_store(pv, reinterpret_cast<f32x4 *>(p) + i);
+    __builtin_nontemporal_store(mv, reinterpret_cast<f32x4 *>(m) + i);
+    __builtin_nontemporal_store(vv, reinterpret_cast<f32x4 *>(v) + i);
     if (LOWP) {
       bf16x4 lo;
 #pragma unroll
       for (int k = 0; k < 4; ++k) lo[k] = (bf16)pv[k];
-      reinterpret_cast<bf16x4 *>(p_lowp)[i] = lo;
+      __builtin_nontemporal_store(lo, reinterpret_cast<bf16x4 *>(p_lowp) + i);
     }
-    if (ZERO) reinterpret_cast<f32x4 *>(g)[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+    if (ZERO) __builtin_nontemporal_store(f32x4{0.f, 0.f, 0.f, 0.f}, reinterpret_cast<f32x4 *>(g) + i);
   }
-  // tail (n not a multiple of 4)
-  const int64_t tail = nvec * 4 + (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
+  // tail (n not a multiple of 4): the first threads of the grid
+  const int64_t tail = nvec * 4 + i;
   if (tail < n) {
     float pk = p[tail], mk = m[tail], vk = v[tail];
     adam_one(pk, g[tail], mk, vk, a);
@@ -181,10 +184,10 @@ __global__ __launch_bounds__(kEwThreads) void adam_kernel(float *__restrict__ p,
   }
 }
 
+// one chunk per thread, blocks in address order (see adam_kernel); the kernels' loops run once
 static unsigned ew_grid(int64_t nchunk) {
   const int64_t blocks = ceil_div(nchunk, kEwThreads);
-  const int64_t cap = 256 * 32;  // enough blocks to fill 256 compute units several times over
-  return (unsigned)(blocks < cap ? (blocks > 0 ? blocks : 1) : cap);
+  return (unsigned)(blocks > 0 ? blocks : 1);
 }
 
 }  // namespace tmk

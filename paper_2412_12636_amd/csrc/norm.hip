@@ -9,7 +9,8 @@ constexpr int kNormThreads = 256;
 constexpr int kNormMaxChunks = 8;  // 16-byte chunks per thread: hidden <= 256 * 8 * Vec::N
 
 // ---------------------------------------------------------------------------------------
-// forward: one block per token row; the row stays in registers between the passes
+// forward: one block per token row; the row stays in registers between the passes.
+// Every access goes through a per-row buffer descriptor (chunks past the row read as zero).
 // ---------------------------------------------------------------------------------------
 template <typename T, int KIND, int NCH>
 __global__ __launch_bounds__(kNormThreads) void norm_fwd_kernel(
@@ -18,24 +19,22 @@ __global__ __launch_bounds__(kNormThreads) void norm_fwd_kernel(
   constexpr int VN = Vec<T>::N;
   __shared__ float red[2 * kNormThreads / kWave];
   const int64_t row = blockIdx.x;
-  const T *xr = x + row * h;
-  T *orow = out + row * h;
+  const uint32_t row_bytes = (uint32_t)h * sizeof(T);
+  const rsrc_t rx = make_rsrc(x + row * h, row_bytes), ro = make_rsrc(out + row * h, row_bytes);
+  const rsrc_t rg = make_rsrc(gain, row_bytes), rf = make_rsrc(KIND == TM_NORM_LAYERNORM ? offset : gain, row_bytes);
   const int nchunk = h / VN;
 
   float vals[NCH][VN];
   float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-  for (int c = 0; c < NCH; ++c) {
-    const int ch = threadIdx.x + c * kNormThreads;
-    if (ch < nchunk) {
-      load_vec<T>(xr + ch * VN, vals[c]);
+  for (int c = 0; c < NCH; ++c) buf_load_vec<T>(rx, (threadIdx.x + c * kNormThreads) * 16u, vals[c]);
 #pragma unroll
-      for (int i = 0; i < VN; ++i) {
-        s1 += vals[c][i];
-        s2 += vals[c][i] * vals[c][i];
-      }
+  for (int c = 0; c < NCH; ++c)
+#pragma unroll
+    for (int i = 0; i < VN; ++i) {
+      s1 += vals[c][i];
+      s2 += vals[c][i] * vals[c][i];
     }
-  }
   block_sum2<kNormThreads>(s1, s2, red);
   float mu = 0.f, rstd;
   if (KIND == TM_NORM_LAYERNORM) {
@@ -43,13 +42,11 @@ __global__ __launch_bounds__(kNormThreads) void norm_fwd_kernel(
     float q = 0.f, dummy = 0.f;  // second pass over registers: sum of squared deviations
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int ch = threadIdx.x + c * kNormThreads;
-      if (ch < nchunk) {
+      const bool live = threadIdx.x + c * kNormThreads < nchunk;
 #pragma unroll
-        for (int i = 0; i < VN; ++i) {
-          const float dlt = vals[c][i] - mu;
-          q += dlt * dlt;
-        }
+      for (int i = 0; i < VN; ++i) {
+        const float dlt = vals[c][i] - mu;
+        q += live ? dlt * dlt : 0.f;
       }
     }
     block_sum2<kNormThreads>(q, dummy, red);
@@ -63,18 +60,16 @@ __global__ __launch_bounds__(kNormThreads) void norm_fwd_kernel(
   }
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int ch = threadIdx.x + c * kNormThreads;
-    if (ch < nchunk) {
-      float g[VN], o[VN], r[VN];
-      load_vec<T>(gain + ch * VN, g);
-      if (KIND == TM_NORM_LAYERNORM) load_vec<T>(offset + ch * VN, o);
+    const uint32_t off = (threadIdx.x + c * kNormThreads) * 16u;
+    float g[VN], o[VN], r[VN];
+    buf_load_vec<T>(rg, off, g);
+    if (KIND == TM_NORM_LAYERNORM) buf_load_vec<T>(rf, off, o);
 #pragma unroll
-      for (int i = 0; i < VN; ++i) {
-        const float xh = (vals[c][i] - mu) * rstd;
-        r[i] = (KIND == TM_NORM_LAYERNORM) ? xh * g[i] + o[i] : xh * g[i];
-      }
-      store_vec<T>(orow + ch * VN, r);
+    for (int i = 0; i < VN; ++i) {
+      const float xh = (vals[c][i] - mu) * rstd;
+      r[i] = (KIND == TM_NORM_LAYERNORM) ? xh * g[i] + o[i] : xh * g[i];
     }
+    buf_store_vec<T>(ro, off, r);
   }
 }
 
@@ -90,37 +85,45 @@ __global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
     float *__restrict__ partial, int64_t rows, int h) {
   constexpr int VN = Vec<T>::N;
   __shared__ float red[2 * kNormThreads / kWave];
-  const int nchunk = h / VN;
-  float gacc[NCH][VN], oacc[NCH][VN];
+  const uint32_t row_bytes = (uint32_t)h * sizeof(T);
+  const rsrc_t rg = make_rsrc(gain, row_bytes);
+  float gacc[NCH][VN], oacc[NCH][VN], gn[NCH][VN];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int ch = threadIdx.x + c * kNormThreads;
+    buf_load_vec<T>(rg, (threadIdx.x + c * kNormThreads) * 16u, gn[c]);
 #pragma unroll
     for (int i = 0; i < VN; ++i) gacc[c][i] = oacc[c][i] = 0.f;
-    (void)ch;
   }
   for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+    const rsrc_t rd = make_rsrc(dout + row * h, row_bytes), rx = make_rsrc(x + row * h, row_bytes);
+    const rsrc_t rr = make_rsrc(dres ? dres + row * h : dout, dres ? row_bytes : 0u);  // no residual: reads zeros
+    const rsrc_t ro = make_rsrc(dx + row * h, row_bytes);
     const float mu = (KIND == TM_NORM_LAYERNORM) ? mean[row] : 0.f;
     const float rs = rstd[row];
-    float w[NCH][VN], xh[NCH][VN];
+    float w[NCH][VN], xh[NCH][VN], res[NCH][VN];
+    // all loads of the row are issued back to back
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const uint32_t off = (threadIdx.x + c * kNormThreads) * 16u;
+      buf_load_vec<T>(rd, off, w[c]);
+      buf_load_vec<T>(rx, off, xh[c]);
+      buf_load_vec<T>(rr, off, res[c]);
+    }
+    const int nchunk = h / VN;
     float sw = 0.f, swx = 0.f;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int ch = threadIdx.x + c * kNormThreads;
-      if (ch < nchunk) {
-        float d[VN], xv[VN], gn[VN];
-        load_vec<T>(gain + ch * VN, gn);  // cache-resident after the first row
-        load_vec<T>(dout + row * h + ch * VN, d);
-        load_vec<T>(x + row * h + ch * VN, xv);
+      const bool live = threadIdx.x + c * kNormThreads < nchunk;  // x reads as 0 past the row: xhat would be -mu*rs
 #pragma unroll
-        for (int i = 0; i < VN; ++i) {
-          xh[c][i] = (xv[i] - mu) * rs;
-          w[c][i] = d[i] * gn[i];
-          gacc[c][i] += d[i] * xh[c][i];
-          oacc[c][i] += d[i];
-          sw += w[c][i];
-          swx += w[c][i] * xh[c][i];
-        }
+      for (int i = 0; i < VN; ++i) {
+        const float d = w[c][i];
+        const float xv = live ? (xh[c][i] - mu) * rs : 0.f;
+        xh[c][i] = xv;
+        w[c][i] = d * gn[c][i];
+        gacc[c][i] += d * xv;
+        oacc[c][i] += d;
+        sw += w[c][i];
+        swx += w[c][i] * xv;
       }
     }
     block_sum2<kNormThreads>(sw, swx, red);
@@ -128,43 +131,53 @@ __global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
     const float mwx = swx / h;
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const int ch = threadIdx.x + c * kNormThreads;
-      if (ch < nchunk) {
-        float r[VN];
-        if (dres) {
-          load_vec<T>(dres + row * h + ch * VN, r);
-        } else {
 #pragma unroll
-          for (int i = 0; i < VN; ++i) r[i] = 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < VN; ++i) r[i] += (w[c][i] - mw - xh[c][i] * mwx) * rs;
-        store_vec<T>(dx + row * h + ch * VN, r);
-      }
+      for (int i = 0; i < VN; ++i) res[c][i] += (w[c][i] - mw - xh[c][i] * mwx) * rs;
+      buf_store_vec<T>(ro, (threadIdx.x + c * kNormThreads) * 16u, res[c]);
     }
   }
-  float *pg = partial + (int64_t)blockIdx.x * 2 * h;
+  const rsrc_t rp = make_rsrc(partial + (int64_t)blockIdx.x * 2 * h, (uint32_t)h * 4u);
+  const rsrc_t rq = make_rsrc(partial + (int64_t)blockIdx.x * 2 * h + h, (uint32_t)h * 4u);
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
-    const int ch = threadIdx.x + c * kNormThreads;
-    if (ch < nchunk) {
+    const uint32_t col = (threadIdx.x + c * kNormThreads) * VN;
 #pragma unroll
-      for (int i = 0; i < VN; ++i) {
-        pg[ch * VN + i] = gacc[c][i];
-        pg[h + ch * VN + i] = oacc[c][i];
+    for (int v4 = 0; v4 < VN / 4; ++v4) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        a[i] = gacc[c][v4 * 4 + i];
+        b[i] = oacc[c][v4 * 4 + i];
       }
+      buf_store_vec<float>(rp, (col + v4 * 4) * 4u, a);
+      buf_store_vec<float>(rq, (col + v4 * 4) * 4u, b);
     }
   }
 }
 
-// out[c] += sum_{r<R} partial[r*ld + c], r ascending (fixed order)
-__global__ void reduce_partials_kernel(const float *__restrict__ partial, int R, int64_t ld, int n,
-                                       float *__restrict__ out) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= n) return;
+// out[c] += sum_{r<R} partial[r*ld + c].  Block = 64 columns x 4 row lanes; lane y adds rows
+// y, y+4, ... in ascending order, then the four lane sums are added in lane order: a fixed order.
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial, int R, int64_t ld,
+                                                              int n, float *__restrict__ out) {
+  __shared__ float sm[4][64];
+  const int lane = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
   float s = 0.f;
-  for (int r = 0; r < R; ++r) s += partial[r * ld + c];
-  out[c] += s;
+  if (c < n) {
+    int r = ry;
+    for (; r + 12 < R; r += 16) {  // four independent loads in flight per trip
+      const float a0 = partial[(int64_t)r * ld + c], a1 = partial[(int64_t)(r + 4) * ld + c];
+      const float a2 = partial[(int64_t)(r + 8) * ld + c], a3 = partial[(int64_t)(r + 12) * ld + c];
+      s += a0;
+      s += a1;
+      s += a2;
+      s += a3;
+    }
+    for (; r < R; r += 4) s += partial[(int64_t)r * ld + c];
+  }
+  sm[ry][lane] = s;
+  __syncthreads();
+  if (ry == 0 && c < n) out[c] += ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
 }
 
 // ---------------------------------------------------------------------------------------
@@ -308,7 +321,7 @@ extern "C" int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const v
               : norm_bwd_t<float>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s);
   if (e) return e;
   const int G = norm_bwd_blocks(T);
-  const int nb = (int)ceil_div(h, 256);
+  const int nb = (int)ceil_div(h, 64);
   reduce_partials_kernel<<<nb, 256, 0, s>>>(partial, G, 2 * h, (int)h, dgain);
   if (kind == TM_NORM_LAYERNORM) reduce_partials_kernel<<<nb, 256, 0, s>>>(partial + h, G, 2 * h, (int)h, doffset);
   return check_launch("norm_bwd reduce");
@@ -331,6 +344,6 @@ extern "C" int tm_op_bias_grad(int dtype, int64_t T, int64_t N, const void *dy, 
   else
     colsum_partial_kernel<float><<<grid, kColLanes * kColRowsPerBlock, 0, s>>>((const float *)dy, partial, T, (int)N,
                                                                                rows_per_group);
-  reduce_partials_kernel<<<(int)ceil_div(N, 256), 256, 0, s>>>(partial, R, N, (int)N, db);
+  reduce_partials_kernel<<<(int)ceil_div(N, 64), 256, 0, s>>>(partial, R, N, (int)N, db);
   return check_launch("bias_grad");
 }
