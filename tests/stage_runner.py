@@ -56,12 +56,20 @@ def oracle_iteration(cfg: si.StageConfig, layers: List[Dict[str, np.ndarray]], x
                      progress: bool = False):
     """fp64 forward and backward through all layers.  Returns y, dx, list of gradient dicts."""
     t0 = time.time()
-    y, stashes = so.stage_fwd(cfg, layers, x)
-    if progress:
-        print(f"  checker forward done in {time.time() - t0:.1f} s", flush=True)
-    dx, grads = so.stage_bwd(cfg, layers, stashes, dy)
-    if progress:
-        print(f"  checker backward done in {time.time() - t0:.1f} s", flush=True)
+    stashes = []
+    y = x
+    for i, p in enumerate(layers):
+        y, st = so.layer_fwd(cfg, p, y)
+        stashes.append(st)
+        if progress:
+            print(f"  checker forward layer {i} done at {time.time() - t0:.1f} s", flush=True)
+    grads = [None] * len(layers)
+    dx = dy
+    for i in reversed(range(len(layers))):
+        dx, grads[i] = so.layer_bwd(cfg, layers[i], stashes[i], dx)
+        stashes[i] = None
+        if progress:
+            print(f"  checker backward layer {i} done at {time.time() - t0:.1f} s", flush=True)
     return y, dx, grads
 
 
