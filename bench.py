@@ -29,6 +29,26 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 
+def recorded_traffic(kernel: str):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None when
+    there is none or the kernel's source has changed since the counters were taken."""
+    import glob
+    import hashlib
+    import re
+    for path in glob.glob(os.path.join(ROOT, "profiles", "*traffic*.txt")):
+        text = open(path).read()
+        m = re.search(r"^kernel:\s*(\S+)", text, re.M)
+        if not m or not kernel.startswith(m.group(1)):
+            continue
+        src = re.search(r"^source:\s*(\S+)\s+sha256:\s*([0-9a-f]+)", text, re.M)
+        val = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
+        if not src or not val:
+            continue
+        cur = hashlib.sha256(open(os.path.join(ROOT, src.group(1)), "rb").read()).hexdigest()
+        return float(val.group(1)) if cur == src.group(2) else None
+    return None
+
+
 def model_flops(cfg) -> float:
     """Model flops of one iteration: 3 x forward; attention counted causal (half the square), no
     credit for recomputation."""
@@ -85,6 +105,9 @@ def main() -> int:
     ap.add_argument("--layers", type=int, default=0, help="override the preset's layer count (0 = preset)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 4 GiB device copy before the timed region (reference reading "
+                         "for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's stage shard; this build has no multi-GPU path "
@@ -150,6 +173,13 @@ def main() -> int:
         if marks is not None:
             marks[3].record()
 
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # cold first call (the gap the sandboxed warm-up exists to hide)
     torch.cuda.synchronize()
     t0 = time.time()
@@ -209,7 +239,17 @@ def main() -> int:
         roofline = {"bound": "hbm", "achieved": round(ach, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(ach / PEAK_HBM_GBS, 4), "traffic": None}
     roofline.update({"kernel": top["kernel"], "avg_launch_ms": round(top["ms"] / top["launches"], 5),
-                     "launches": top["launches"]})
+                     "launches": top["launches"], "traffic": recorded_traffic(top["kernel"])})
+    # the largest matrix-core kernel as well (the single largest kernel is the Adam sweep)
+    roofline_mfma = None
+    for e in prof:
+        if e["flops"] > 0 and "gemm" in e["kernel"]:
+            ach = e["flops"] / (e["ms"] * 1e-3) / 1e12
+            roofline_mfma = {"bound": "mfma", "kernel": e["kernel"], "achieved": round(ach, 2), "peak": PEAK_BF16_TFLOPS,
+                             "unit": "TFLOP/s", "frac": round(ach / PEAK_BF16_TFLOPS, 4),
+                             "avg_launch_ms": round(e["ms"] / e["launches"], 5), "launches": e["launches"],
+                             "traffic": None}
+            break
 
     tokens = cfg.seq * cfg.micro_batch
     flops = model_flops(cfg)
@@ -230,7 +270,7 @@ def main() -> int:
         "adam_gbps": round(adam_bytes / (adam_ms * 1e-3) / 1e9, 1), "adam_frac_hbm": round(adam_bytes / (adam_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
         "first_step_ms": round(first_ms, 2), "host_wall_ms_per_step": round(wall_ms / args.steps, 4),
         "profiled_ms_per_step": round(prof_ms_step, 4),
-        "roofline": roofline, "kernels": kernels[:12],
+        "roofline": roofline, "roofline_mfma": roofline_mfma, "kernels": kernels[:14],
     }
     tm.tm_stage_destroy(h)
     if not args.no_cpu_baseline:
