@@ -2,7 +2,7 @@
 """Throughput of the stage-shard iteration (forward + backward + Adam) on one MI355X.
 
 A step is one pass of the whole hot path over one synthetic micro-batch of the chosen shard
-preset: tm_stage_fwd, tm_stage_bwd, tm_adam_step (gradients cleared inside the Adam kernel).
+preset: tm_stage_fwd, tm_stage_bwd (storing, not adding, the gradients), tm_adam_step.
 Inputs and all state are resident in HBM before the timed region.  One JSON line is printed.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--preset gpt175b] [--cpu-seconds 20]
@@ -152,7 +152,10 @@ def main() -> int:
     dy = torch.empty(shape, dtype=torch.float32, device="cuda").normal_(0, 1e-2, generator=gen).to(td)
     y, dx = torch.empty_like(x), torch.empty_like(x)
     h = tm.tm_stage_init(cfg, params, master if bf16 else None, grads, m, v, ws)
-    hp = tm.make_hparams(**{**si.ADAM_DEFAULTS, "zero_grads": 1})
+    # one micro-batch per iteration: the backward pass stores the gradients (their old contents are
+    # dead), so nothing has to clear the buffer and Adam only reads it
+    tm.tm_stage_grad_mode(h, True)
+    hp = tm.make_hparams(**si.ADAM_DEFAULTS)
     stream = int(torch.cuda.current_stream().cuda_stream)
     step_no = [0]
 
@@ -254,7 +257,7 @@ def main() -> int:
     tokens = cfg.seq * cfg.micro_batch
     flops = model_flops(cfg)
     tf = flops / ((fwd_ms + bwd_ms) * 1e-3) / 1e12
-    adam_bytes = (34.0 if bf16 else 32.0) * n
+    adam_bytes = (30.0 if bf16 else 28.0) * n
     out = {
         "metric": "stage-shard fwd+bwd+Adam tokens/s per GPU; MFMA util % of bf16 peak",
         "value": round(tokens / (ms_step * 1e-3), 1), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,

@@ -33,16 +33,17 @@ int tm_op_linear_fwd(int dtype, int64_t T, int64_t N, int64_t K, const void *x, 
 int tm_op_linear_dgrad(int dtype, int64_t T, int64_t N, int64_t K, const void *dy, const void *w,
                        void *dx, void *stream);
 
-/* dw[N,K] += dy[T,N]^T x[T,K]   (weight gradient, accumulated in fp32) */
+/* Weight gradient in fp32: dw[N,K] += dy[T,N]^T x[T,K] when accumulate != 0, dw = ... otherwise
+ * (the old contents are then not read). */
 int tm_op_linear_wgrad(int dtype, int64_t T, int64_t N, int64_t K, const void *dy, const void *x,
-                       float *dw, void *stream);
+                       float *dw, int accumulate, void *stream);
 
 /* Bytes of fp32 scratch the reductions below need for a [T, width] input. */
 int64_t tm_op_reduce_scratch_bytes(int64_t T, int64_t width);
 
-/* db[N] += sum over rows of dy[T,N]; fixed summation order (bit-reproducible). */
+/* db[N] (+)= sum over rows of dy[T,N]; fixed summation order (bit-reproducible); accumulate as above. */
 int tm_op_bias_grad(int dtype, int64_t T, int64_t N, const void *dy, float *db, void *scratch,
-                    void *stream);
+                    int accumulate, void *stream);
 
 /* LayerNorm / RMSNorm over rows of x[T,h]: out = gain*xhat (+ offset); writes mean[T]
  * (LayerNorm only, may be NULL for RMSNorm) and rstd[T]. */
@@ -50,11 +51,12 @@ int tm_op_norm_fwd(int dtype, int kind, int64_t T, int64_t h, double eps, const 
                    const void *gain, const void *offset, void *out, float *mean, float *rstd,
                    void *stream);
 
-/* dx[T,h] = (dres or 0) + gradient of the norm w.r.t. x for output gradient dout; dgain[h] +=,
- * doffset[h] += (LayerNorm).  dres may be NULL and may alias dx.  scratch: see above with width 2h. */
+/* dx[T,h] = (dres or 0) + gradient of the norm w.r.t. x for output gradient dout; dgain[h] (+)=,
+ * doffset[h] (+)= (LayerNorm), accumulate as above.  dres may be NULL and may alias dx.
+ * scratch: see above with width 2h. */
 int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x,
                    const float *mean, const float *rstd, const void *gain, const void *dres,
-                   void *dx, float *dgain, float *doffset, void *scratch, void *stream);
+                   void *dx, float *dgain, float *doffset, void *scratch, int accumulate, void *stream);
 
 /* g[T,f] = gelu(u[T,f])  or  silu(u[T,0:f]) * u[T,f:2f]  for TM_ACT_SWIGLU (u is [T,2f]). */
 int tm_op_act_fwd(int dtype, int act, int64_t T, int64_t f, const void *u, void *g, void *stream);

@@ -150,6 +150,15 @@ int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void *stream);
 int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stream);
 
 /*
+ * Gradient-buffer mode of the following tm_stage_bwd calls.  overwrite == 0 (the default): parameter
+ * gradients are ADDED into buffers.grads (gradient accumulation over micro-batches).  overwrite != 0:
+ * they are STORED, the buffer's old contents are not read - for the first micro-batch of an iteration,
+ * when those contents are dead; it saves one read of the fp32 gradient buffer per backward pass and
+ * makes clearing the buffer unnecessary.
+ */
+int tm_stage_grad_mode(tm_stage_t *st, int overwrite);
+
+/*
  * Adam with bias correction at step >= 1 on the whole shard:
  *   g' = grad_scale*g;  m = b1*m + (1-b1)*g';  v = b2*v + (1-b2)*g'^2
  *   p -= lr*( (m/(1-b1^step)) / (sqrt(v/(1-b2^step)) + eps) + weight_decay*p )

@@ -62,17 +62,18 @@ EXPORTS = {
     "tm_adam_step": (C.c_int, [C.c_void_p, C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
     "tm_adam_step_flat": (C.c_int, [C.c_int64] + [C.c_void_p] * 5 + [C.POINTER(tm_adam_hparams_t), C.c_int64,
                                                                        C.c_void_p]),
+    "tm_stage_grad_mode": (C.c_int, [C.c_void_p, C.c_int]),
     "tm_stage_destroy": (None, [C.c_void_p]),
     "tm_stage_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "tm_stage_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(tm_profile_entry_t), C.c_int]),
     "tm_last_error": (C.c_char_p, []),
     "tm_op_linear_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 6),
     "tm_op_linear_dgrad": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 4),
-    "tm_op_linear_wgrad": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 4),
+    "tm_op_linear_wgrad": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 3 + [C.c_int, C.c_void_p]),
     "tm_op_reduce_scratch_bytes": (C.c_int64, [C.c_int64, C.c_int64]),
-    "tm_op_bias_grad": (C.c_int, [C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 4),
+    "tm_op_bias_grad": (C.c_int, [C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 3 + [C.c_int, C.c_void_p]),
     "tm_op_norm_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_double] + [C.c_void_p] * 7),
-    "tm_op_norm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 11),
+    "tm_op_norm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 10 + [C.c_int, C.c_void_p]),
     "tm_op_act_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 3),
     "tm_op_act_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 4),
     "tm_op_rotary": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_double, C.c_int, C.c_void_p, C.c_void_p]),
@@ -175,6 +176,10 @@ def tm_adam_step_flat(n: int, p, g, m, v, p_bf16, hp: tm_adam_hparams_t, step: i
     _check(lib().tm_adam_step_flat(n, _ptr(p), _ptr(g), _ptr(m), _ptr(v), _ptr(p_bf16), C.byref(hp), step, stream))
 
 
+def tm_stage_grad_mode(handle: int, overwrite: bool) -> None:
+    _check(lib().tm_stage_grad_mode(handle, int(overwrite)))
+
+
 def tm_stage_destroy(handle: int) -> None:
     lib().tm_stage_destroy(handle)
 
@@ -204,16 +209,16 @@ def tm_op_linear_dgrad(dtype, T, N, K, dy, w, dx, stream=0):
     _check(lib().tm_op_linear_dgrad(dtype, T, N, K, _ptr(dy), _ptr(w), _ptr(dx), stream))
 
 
-def tm_op_linear_wgrad(dtype, T, N, K, dy, x, dw, stream=0):
-    _check(lib().tm_op_linear_wgrad(dtype, T, N, K, _ptr(dy), _ptr(x), _ptr(dw), stream))
+def tm_op_linear_wgrad(dtype, T, N, K, dy, x, dw, accumulate=1, stream=0):
+    _check(lib().tm_op_linear_wgrad(dtype, T, N, K, _ptr(dy), _ptr(x), _ptr(dw), int(accumulate), stream))
 
 
 def tm_op_reduce_scratch_bytes(T, width) -> int:
     return _check(lib().tm_op_reduce_scratch_bytes(T, width))
 
 
-def tm_op_bias_grad(dtype, T, N, dy, db, scratch, stream=0):
-    _check(lib().tm_op_bias_grad(dtype, T, N, _ptr(dy), _ptr(db), _ptr(scratch), stream))
+def tm_op_bias_grad(dtype, T, N, dy, db, scratch, accumulate=1, stream=0):
+    _check(lib().tm_op_bias_grad(dtype, T, N, _ptr(dy), _ptr(db), _ptr(scratch), int(accumulate), stream))
 
 
 def tm_op_norm_fwd(dtype, kind, T, h, eps, x, gain, offset, out, mean, rstd, stream=0):
@@ -221,9 +226,11 @@ def tm_op_norm_fwd(dtype, kind, T, h, eps, x, gain, offset, out, mean, rstd, str
                                 _ptr(rstd), stream))
 
 
-def tm_op_norm_bwd(dtype, kind, T, h, dout, x, mean, rstd, gain, dres, dx, dgain, doffset, scratch, stream=0):
+def tm_op_norm_bwd(dtype, kind, T, h, dout, x, mean, rstd, gain, dres, dx, dgain, doffset, scratch, accumulate=1,
+                   stream=0):
     _check(lib().tm_op_norm_bwd(dtype, kind, T, h, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gain),
-                                _ptr(dres), _ptr(dx), _ptr(dgain), _ptr(doffset), _ptr(scratch), stream))
+                                _ptr(dres), _ptr(dx), _ptr(dgain), _ptr(doffset), _ptr(scratch), int(accumulate),
+                                stream))
 
 
 def tm_op_act_fwd(dtype, act, T, f, u, g, stream=0):

@@ -5,8 +5,9 @@
 namespace tmk {
 
 // C[m,n] = sum_k A(m,k) * B(n,k) with A(m,k) = A[m*a_rs + k*a_cs], B(n,k) = B[n*b_rs + k*b_cs].
-// accumulate_f32 == false: C (stage dtype, row stride ldc) = result (+ bias[n]) (+ residual[m*ldc + n])
-// accumulate_f32 == true : C is fp32 and the result is added to it (weight gradients)
+// c_mode 0: C (stage dtype, row stride ldc) = result (+ bias[n]) (+ residual[m*ldc + n])
+// c_mode 1: C is fp32 and the result is added to it (weight gradients, accumulating)
+// c_mode 2: C is fp32 and is overwritten with the result (first micro-batch of an iteration)
 struct GemmArgs {
   int64_t M, N, K;
   const void *A;
@@ -17,7 +18,7 @@ struct GemmArgs {
   int64_t ldc;
   const void *bias;
   const void *residual;
-  bool accumulate_f32;
+  int c_mode;
 };
 
 int gemm_generic(int dtype, const GemmArgs &g, hipStream_t s);

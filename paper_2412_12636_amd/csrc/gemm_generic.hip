@@ -8,7 +8,7 @@ namespace tmk {
 constexpr int GT = 64, GK = 16;
 
 // C[m,n] = sum_k A(m,k) B(n,k), A(m,k) = A[m*a_rs + k*a_cs], B(n,k) = B[n*b_rs + k*b_cs]
-// EPI 0: C = acc (+bias[n]) (+residual[m,n]) stored as TC ; EPI 1: C(fp32) += acc
+// EPI 0: C = acc (+bias[n]) (+residual[m,n]) stored as TC ; EPI 1: C(fp32) += acc ; EPI 2: C(fp32) = acc
 template <typename TA, typename TC, int EPI>
 __global__ __launch_bounds__(256) void gemm_generic_kernel(int M, int N, int K, const TA *__restrict__ A,
                                                           int64_t a_rs, int64_t a_cs, const TA *__restrict__ B,
@@ -62,8 +62,10 @@ __global__ __launch_bounds__(256) void gemm_generic_kernel(int M, int N, int K, 
         if (bias) v += to_f32(bias[n]);
         if (residual) v += to_f32(residual[(int64_t)m * ldc + n]);
         C[(int64_t)m * ldc + n] = from_f32<TC>(v);
-      } else {
+      } else if (EPI == 1) {
         C[(int64_t)m * ldc + n] = from_f32<TC>(to_f32(C[(int64_t)m * ldc + n]) + v);
+      } else {
+        C[(int64_t)m * ldc + n] = from_f32<TC>(v);
       }
     }
   }
@@ -73,8 +75,12 @@ template <typename T>
 static int launch_generic(const GemmArgs &g, hipStream_t s) {
   dim3 grid((unsigned)ceil_div(g.N, GT), (unsigned)ceil_div(g.M, GT));
   g_last_kernel = "gemm_generic_kernel";
-  if (g.accumulate_f32)
+  if (g.c_mode == 1)
     gemm_generic_kernel<T, float, 1><<<grid, 256, 0, s>>>((int)g.M, (int)g.N, (int)g.K, (const T *)g.A, g.a_rs, g.a_cs,
+                                                          (const T *)g.B, g.b_rs, g.b_cs, (float *)g.C, g.ldc, nullptr,
+                                                          nullptr);
+  else if (g.c_mode == 2)
+    gemm_generic_kernel<T, float, 2><<<grid, 256, 0, s>>>((int)g.M, (int)g.N, (int)g.K, (const T *)g.A, g.a_rs, g.a_cs,
                                                           (const T *)g.B, g.b_rs, g.b_cs, (float *)g.C, g.ldc, nullptr,
                                                           nullptr);
   else

@@ -23,10 +23,10 @@ bool gemm_mfma_supported(const GemmArgs &g) {
   if (!operand_ok(g.A, g.a_rs, g.a_cs, g.M) || !operand_ok(g.B, g.b_rs, g.b_cs, g.N)) return false;
   const bool akc = g.a_cs == 1, bkc = g.b_cs == 1;
   const int64_t a_bytes = (akc ? g.M * g.a_rs : g.K * g.a_cs) * 2, b_bytes = (bkc ? g.N * g.b_rs : g.K * g.b_cs) * 2;
-  const int64_t c_bytes = g.M * g.ldc * (g.accumulate_f32 ? 4 : 2);
+  const int64_t c_bytes = g.M * g.ldc * (g.c_mode ? 4 : 2);
   if (a_bytes >= (1LL << 31) || b_bytes >= (1LL << 31) || c_bytes >= (1LL << 31)) return false;  // 32-bit offsets
   if (g.ldc % 8 || (((uintptr_t)g.C) & 15)) return false;
-  return g.accumulate_f32 ? (!akc && !bkc) : akc;
+  return g.c_mode ? (!akc && !bkc) : akc;
 }
 
 // Block tile: the candidate with the lowest estimated time.  A compute unit holds `occ` blocks of a
@@ -69,9 +69,9 @@ void gemm_pick_tile(int64_t M, int64_t N, int &bm, int &bn) {
 
 int gemm_mfma(const GemmArgs &g, hipStream_t s) {
   const bool akc = g.a_cs == 1, bkc = g.b_cs == 1;
-  if (!g.accumulate_f32 && akc && bkc) return gemm_mfma_nt(g, s);
-  if (!g.accumulate_f32 && akc && !bkc) return gemm_mfma_nn(g, s);
-  if (g.accumulate_f32 && !akc && !bkc) return gemm_mfma_tn(g, s);
+  if (!g.c_mode && akc && bkc) return gemm_mfma_nt(g, s);
+  if (!g.c_mode && akc && !bkc) return gemm_mfma_nn(g, s);
+  if (g.c_mode && !akc && !bkc) return gemm_mfma_tn(g, s);
   return fail(TM_EINVAL, "gemm_mfma: operand layout not instantiated");
 }
 

@@ -88,7 +88,7 @@ __device__ __forceinline__ void tile_of_block(const MfmaGemmParams &p, int BM, i
 // ---- epilogue shared by both kernels -------------------------------------------------------------
 // acc[i][j] is the transposed 32x32 tile (rows = output columns): register 4q+e of lane l holds
 // C[row = .. + l%32][col = .. + 8q + 4*(l/32) + e].   EPI 0: bf16 C = acc (+bias) (+residual);
-// EPI 1: fp32 C += acc.
+// EPI 1: fp32 C += acc;  EPI 2: fp32 C = acc.
 template <int TM, int TN, int EPI>
 __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (&acc)[TM][TN], int row_base,
                                          int col_base, int l32, int hh) {
@@ -130,11 +130,16 @@ __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = (bf16)r[e];
           __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rc, off, 0, 0);
-        } else {
+        } else if (EPI == 1) {
           const f32x4 old = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rc, off, 0, 0));
           f32x4 o;
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = old[e] + acc[i][j][4 * q + e];
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u32, o), rc, off, 0, 0);
+        } else {
+          f32x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = acc[i][j][4 * q + e];
           __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u32, o), rc, off, 0, 0);
         }
       }

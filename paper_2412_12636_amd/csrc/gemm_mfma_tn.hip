@@ -3,5 +3,8 @@
 
 namespace tmk {
 TM_GEMM_INSTANTIATE(false, false, 1)
-int gemm_mfma_tn(const GemmArgs &g, hipStream_t s) { return launch_layout<false, false, 1>(g, s); }
+TM_GEMM_INSTANTIATE(false, false, 2)
+int gemm_mfma_tn(const GemmArgs &g, hipStream_t s) {
+  return g.c_mode == 2 ? launch_layout<false, false, 2>(g, s) : launch_layout<false, false, 1>(g, s);
+}
 }  // namespace tmk

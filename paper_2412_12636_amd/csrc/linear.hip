@@ -23,7 +23,7 @@ extern "C" int tm_op_linear_fwd(int dtype, int64_t T, int64_t N, int64_t K, cons
                                 const void *bias, const void *residual, void *y, void *stream) {
   if (int e = check_linear("linear_fwd", dtype, T, N, K)) return e;
   if (!x || !w || !y) return fail(TM_EINVAL, "linear_fwd: NULL pointer");
-  GemmArgs g{T, N, K, x, K, 1, w, K, 1, y, N, bias, residual, false};
+  GemmArgs g{T, N, K, x, K, 1, w, K, 1, y, N, bias, residual, 0};
   return run(dtype, g, (hipStream_t)stream);
 }
 
@@ -32,15 +32,15 @@ extern "C" int tm_op_linear_dgrad(int dtype, int64_t T, int64_t N, int64_t K, co
   if (int e = check_linear("linear_dgrad", dtype, T, N, K)) return e;
   if (!dy || !w || !dx) return fail(TM_EINVAL, "linear_dgrad: NULL pointer");
   // dx[t,k] = sum_n dy[t,n] w[n,k]: reduction over n; w is read along its strided axis
-  GemmArgs g{T, K, N, dy, N, 1, w, 1, K, dx, K, nullptr, nullptr, false};
+  GemmArgs g{T, K, N, dy, N, 1, w, 1, K, dx, K, nullptr, nullptr, 0};
   return run(dtype, g, (hipStream_t)stream);
 }
 
 extern "C" int tm_op_linear_wgrad(int dtype, int64_t T, int64_t N, int64_t K, const void *dy, const void *x, float *dw,
-                                  void *stream) {
+                                  int accumulate, void *stream) {
   if (int e = check_linear("linear_wgrad", dtype, T, N, K)) return e;
   if (!dy || !x || !dw) return fail(TM_EINVAL, "linear_wgrad: NULL pointer");
-  // dw[n,k] += sum_t dy[t,n] x[t,k]: reduction over tokens, both operands read along their strided axis
-  GemmArgs g{N, K, T, dy, 1, N, x, 1, K, dw, K, nullptr, nullptr, true};
+  // dw[n,k] (+)= sum_t dy[t,n] x[t,k]: reduction over tokens, both operands read along their strided axis
+  GemmArgs g{N, K, T, dy, 1, N, x, 1, K, dw, K, nullptr, nullptr, accumulate ? 1 : 2};
   return run(dtype, g, (hipStream_t)stream);
 }

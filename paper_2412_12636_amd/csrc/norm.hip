@@ -155,10 +155,10 @@ __global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
   }
 }
 
-// out[c] += sum_{r<R} partial[r*ld + c].  Block = 64 columns x 4 row lanes; lane y adds rows
+// out[c] (+)= sum_{r<R} partial[r*ld + c].  Block = 64 columns x 4 row lanes; lane y adds rows
 // y, y+4, ... in ascending order, then the four lane sums are added in lane order: a fixed order.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partial, int R, int64_t ld,
-                                                              int n, float *__restrict__ out) {
+                                                              int n, float *__restrict__ out, int accumulate) {
   __shared__ float sm[4][64];
   const int lane = threadIdx.x & 63, ry = threadIdx.x >> 6;
   const int c = blockIdx.x * 64 + lane;
@@ -177,7 +177,10 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
   }
   sm[ry][lane] = s;
   __syncthreads();
-  if (ry == 0 && c < n) out[c] += ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
+  if (ry == 0 && c < n) {
+    const float t = ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
+    out[c] = accumulate ? out[c] + t : t;
+  }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -307,7 +310,7 @@ extern "C" int tm_op_norm_fwd(int dtype, int kind, int64_t T, int64_t h, double 
 
 extern "C" int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x,
                               const float *mean, const float *rstd, const void *gain, const void *dres, void *dx,
-                              float *dgain, float *doffset, void *scratch, void *stream) {
+                              float *dgain, float *doffset, void *scratch, int accumulate, void *stream) {
   if (int e = check_width("norm_bwd", dtype, T, h)) return e;
   if (kind != TM_NORM_LAYERNORM && kind != TM_NORM_RMSNORM) return fail(TM_EINVAL, "norm_bwd: unknown kind %d", kind);
   if (!dout || !x || !rstd || !gain || !dx || !dgain || !scratch || (kind == TM_NORM_LAYERNORM && (!mean || !doffset)))
@@ -322,13 +325,13 @@ extern "C" int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const v
   if (e) return e;
   const int G = norm_bwd_blocks(T);
   const int nb = (int)ceil_div(h, 64);
-  reduce_partials_kernel<<<nb, 256, 0, s>>>(partial, G, 2 * h, (int)h, dgain);
-  if (kind == TM_NORM_LAYERNORM) reduce_partials_kernel<<<nb, 256, 0, s>>>(partial + h, G, 2 * h, (int)h, doffset);
+  reduce_partials_kernel<<<nb, 256, 0, s>>>(partial, G, 2 * h, (int)h, dgain, accumulate);
+  if (kind == TM_NORM_LAYERNORM) reduce_partials_kernel<<<nb, 256, 0, s>>>(partial + h, G, 2 * h, (int)h, doffset, accumulate);
   return check_launch("norm_bwd reduce");
 }
 
 extern "C" int tm_op_bias_grad(int dtype, int64_t T, int64_t N, const void *dy, float *db, void *scratch,
-                               void *stream) {
+                               int accumulate, void *stream) {
   if (int e = check_width("bias_grad", dtype, T, N)) return e;
   if (!dy || !db || !scratch) return fail(TM_EINVAL, "bias_grad: NULL pointer");
   hipStream_t s = (hipStream_t)stream;
@@ -344,6 +347,6 @@ extern "C" int tm_op_bias_grad(int dtype, int64_t T, int64_t N, const void *dy, 
   else
     colsum_partial_kernel<float><<<grid, kColLanes * kColRowsPerBlock, 0, s>>>((const float *)dy, partial, T, (int)N,
                                                                                rows_per_group);
-  reduce_partials_kernel<<<(int)ceil_div(N, 64), 256, 0, s>>>(partial, R, N, (int)N, db);
+  reduce_partials_kernel<<<(int)ceil_div(N, 64), 256, 0, s>>>(partial, R, N, (int)N, db, accumulate);
   return check_launch("bias_grad");
 }

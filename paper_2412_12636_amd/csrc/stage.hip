@@ -227,6 +227,7 @@ struct tm_stage {
   Plan plan;
   int64_t n_params;
   bool have_fwd;
+  bool grad_overwrite = false;
   std::vector<TensorInfo> tensors;
 };
 
@@ -307,6 +308,12 @@ extern "C" void tm_stage_destroy(tm_stage_t *st) {
   if (!st) return;
   st->prof.release();
   delete st;
+}
+
+extern "C" int tm_stage_grad_mode(tm_stage_t *st, int overwrite) {
+  if (!st) return fail(TM_EINVAL, "grad_mode: NULL handle");
+  st->grad_overwrite = overwrite != 0;
+  return TM_OK;
 }
 
 extern "C" int tm_stage_profile_enable(tm_stage_t *st, int enable) {
@@ -463,6 +470,7 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
   const Plan &pl = st->plan;
   void *red = ws + pl.reduce;
   const bool bias = c.has_bias != 0;
+  const int acc = st->grad_overwrite ? 0 : 1;
   const double es = (double)d.es, Th = (double)d.T * d.h;
   const double attn_flops = 2.0 * c.micro_batch * c.n_q_heads * (double)c.seq * c.seq * c.head_dim;
   auto mm = [&](int64_t n, int64_t kk) { return 2.0 * d.T * n * kk; };
@@ -479,26 +487,26 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
     // y = x1 + g W2^T + b2
     void *dg = (c.act == TM_ACT_SWIGLU) ? (void *)(ws + pl.dmid) : (void *)(ws + pl.dwide);
     TM_STEP(mm(d.h, d.f), 0, tm_op_linear_dgrad(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, s));
-    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), s));
-    if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, s));
+    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), acc, s));
+    if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, acc, s));
     // activation
     void *du = ws + pl.dwide;
     TM_STEP(0, es * d.T * (d.f + 2 * d.f1), tm_op_act_bwd(dt, c.act, d.T, d.f, dg, ws + k.u, du, s));
     // u = c W1^T + b1
     void *dc = ws + pl.dnorm;
     TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_dgrad(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, s));
-    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), s));
-    if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, s));
+    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), acc, s));
+    if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, acc, s));
     // c = Norm(x1): dx1 = dy + norm gradient
     void *dx1 = ws + pl.dx1;
     TM_STEP(0, 4 * es * Th,
             tm_op_norm_bwd(dt, c.norm, d.T, d.h, dc, ws + k.x1, (const float *)(ws + k.mean2),
                            (const float *)(ws + k.rstd2), P(o.norm2_gain), dy, dx1, G(o.norm2_gain),
-                           G(o.norm2_offset), red, s));
+                           G(o.norm2_offset), red, acc, s));
     // x1 = x + ctx Wout^T + bout
     TM_STEP(mm(d.h, d.A), 0, tm_op_linear_dgrad(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, s));
-    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), s));
-    if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, s));
+    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), acc, s));
+    if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, acc, s));
     // attention, rotary
     TM_STEP(2 * attn_flops, 0,
             tm_op_attn_bwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
@@ -510,13 +518,13 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
     // qkv = a Wqkv^T + b
     void *da = ws + pl.dnorm;
     TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_dgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, s));
-    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), s));
-    if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, s));
+    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), acc, s));
+    if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, acc, s));
     // a = Norm(x): dx = dx1 + norm gradient
     TM_STEP(0, 4 * es * Th,
             tm_op_norm_bwd(dt, c.norm, d.T, d.h, da, ws + k.x, (const float *)(ws + k.mean1),
                            (const float *)(ws + k.rstd1), P(o.norm1_gain), dx1, dx, G(o.norm1_gain),
-                           G(o.norm1_offset), red, s));
+                           G(o.norm1_offset), red, acc, s));
     dy = dx;
   }
   return TM_OK;

@@ -48,7 +48,7 @@ def test_linear_full_size_sampled_rows(env, name, T, N, K):
     res = x[:, :N].contiguous() if K >= N else None
     tm.tm_op_linear_fwd(BF16, T, N, K, x, w, bias, res, y, s)
     tm.tm_op_linear_dgrad(BF16, T, N, K, dy, w, dx, s)
-    tm.tm_op_linear_wgrad(BF16, T, N, K, dy, x, dw, s)
+    tm.tm_op_linear_wgrad(BF16, T, N, K, dy, x, dw, 1, s)
     torch.cuda.synchronize()
     rng = np.random.default_rng(T + N)
     rows_t = sorted(set([0, 127, 128, T - 1] + rng.integers(0, T, 12).tolist()))

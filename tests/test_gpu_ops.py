@@ -65,10 +65,30 @@ def test_linear_fwd_dgrad_wgrad(env, dtype, T, N, K):
 
     g0 = rng.standard_normal((N, K)).astype(np.float32)
     dw = f32_dev(torch, g0)
-    tm.tm_op_linear_wgrad(dtype, T, N, K, dyd, xd, dw, s)
+    tm.tm_op_linear_wgrad(dtype, T, N, K, dyd, xd, dw, 1, s)
     ref = g0.astype(np.float64) + dy.astype(np.float64).T @ x.astype(np.float64)
     # fp32 accumulation of exact products: far tighter than the storage tolerance
     assert rel_err(to_host(dw), ref) <= 1e-5
+
+
+def test_gradient_overwrite_mode_ignores_old_contents(env):
+    torch, tm = env
+    rng = np.random.default_rng(4)
+    T, N, K = 300, 264, 192
+    x, dy = rand(rng, (T, K), 1.0, BF16), rand(rng, (T, N), 0.1, BF16)
+    xd, dyd = to_dev(torch, x, BF16), to_dev(torch, dy, BF16)
+    s = stream_ptr(torch)
+    dw = torch.full((N, K), float("nan"), dtype=torch.float32, device="cuda")
+    tm.tm_op_linear_wgrad(BF16, T, N, K, dyd, xd, dw, 0, s)
+    assert rel_err(to_host(dw), dy.astype(np.float64).T @ x.astype(np.float64)) <= 1e-5
+    db = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
+    scratch = torch.empty(tm.tm_op_reduce_scratch_bytes(T, 2 * N), dtype=torch.uint8, device="cuda")
+    tm.tm_op_bias_grad(BF16, T, N, dyd, db, scratch, 0, s)
+    assert rel_err(to_host(db), dy.astype(np.float64).sum(axis=0)) <= 1e-5
+    # fp32 stage dtype goes through the plain-ALU kernel
+    dwf = torch.full((N, K), float("nan"), dtype=torch.float32, device="cuda")
+    tm.tm_op_linear_wgrad(FP32, T, N, K, dyd.float(), xd.float(), dwf, 0, s)
+    assert rel_err(to_host(dwf), dy.astype(np.float64).T @ x.astype(np.float64)) <= 1e-5
 
 
 def test_linear_results_are_bit_reproducible(env):
@@ -82,7 +102,7 @@ def test_linear_results_are_bit_reproducible(env):
         y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
         dw = torch.zeros((N, K), dtype=torch.float32, device="cuda")
         tm.tm_op_linear_fwd(BF16, T, N, K, xd, wd, None, None, y, stream_ptr(torch))
-        tm.tm_op_linear_wgrad(BF16, T, N, K, dyd, xd, dw, stream_ptr(torch))
+        tm.tm_op_linear_wgrad(BF16, T, N, K, dyd, xd, dw, 1, stream_ptr(torch))
         outs.append((y, dw))
     assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
 
@@ -96,7 +116,7 @@ def test_bias_grad(env, dtype, T, N):
     g0 = rng.standard_normal(N).astype(np.float32)
     db = f32_dev(torch, g0)
     scratch = torch.empty(tm.tm_op_reduce_scratch_bytes(T, N), dtype=torch.uint8, device="cuda")
-    tm.tm_op_bias_grad(dtype, T, N, to_dev(torch, dy, dtype), db, scratch, stream_ptr(torch))
+    tm.tm_op_bias_grad(dtype, T, N, to_dev(torch, dy, dtype), db, scratch, 1, stream_ptr(torch))
     assert rel_err(to_host(db), g0 + dy.astype(np.float64).sum(axis=0)) <= 1e-5
 
 
@@ -132,16 +152,19 @@ def test_norm_fwd_bwd(env, dtype, kind, T, h):
     dgain, doff = f32_dev(torch, g0), f32_dev(torch, o0)
     scratch = torch.empty(tm.tm_op_reduce_scratch_bytes(T, 2 * h), dtype=torch.uint8, device="cuda")
     tm.tm_op_norm_bwd(dtype, kind, T, h, to_dev(torch, dout, dtype), xd, mean if ln else None, rstd, gd,
-                      to_dev(torch, dres, dtype), dx, dgain, doff if ln else None, scratch, s)
+                      to_dev(torch, dres, dtype), dx, dgain, doff if ln else None, scratch, 1, s)
     rdx, rdg, rdo = so.norm_bwd(dout, xhat, r, gain.astype(np.float64), kind)
     assert rel_err(to_host(dx), rdx + dres) <= tol_of(dtype)
     assert rel_err(to_host(dgain), g0 + rdg) <= 1e-4
     if ln:
         assert rel_err(to_host(doff), o0 + rdo) <= 1e-4
-    # without a residual gradient
+    # without a residual gradient, and storing instead of adding the gain / offset gradients
     tm.tm_op_norm_bwd(dtype, kind, T, h, to_dev(torch, dout, dtype), xd, mean if ln else None, rstd, gd, None, dx,
-                      dgain, doff if ln else None, scratch, s)
+                      dgain, doff if ln else None, scratch, 0, s)
     assert rel_err(to_host(dx), rdx) <= tol_of(dtype)
+    assert rel_err(to_host(dgain), rdg) <= 1e-4
+    if ln:
+        assert rel_err(to_host(doff), rdo) <= 1e-4
 
 
 # ------------------------------------------------------------------ activations

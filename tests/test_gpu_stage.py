@@ -108,6 +108,29 @@ def test_backward_needs_forward_and_gradients_accumulate(env):
     st.close()
 
 
+def test_overwrite_mode_equals_accumulation_into_zeros(env):
+    torch, tm = env
+    cfg = SMALL_GPT
+    flat = si.make_flat_params(cfg)
+    x, dy = to_dev(torch, si.make_x(cfg), cfg.dtype), to_dev(torch, si.make_dy(cfg), cfg.dtype)
+    a = GpuStage(torch, tm, cfg, flat)
+    a.fwd(x)
+    a.bwd(dy)
+    b = GpuStage(torch, tm, cfg, flat)
+    b.grads.fill_(float("nan"))                 # dead contents: must never be read
+    tm.tm_stage_grad_mode(b.handle, True)
+    b.fwd(x)
+    b.bwd(dy)
+    torch.cuda.synchronize()
+    assert torch.equal(a.grads, b.grads) and torch.equal(a.dx, b.dx)
+    tm.tm_stage_grad_mode(b.handle, False)      # back to accumulation: a second pass doubles the gradients
+    b.bwd(dy)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(b.grads), 2.0 * to_host(a.grads)) <= 1e-6
+    a.close()
+    b.close()
+
+
 def test_two_runs_are_bit_identical(env):
     torch, tm = env
     cfg = SMALL_LLAMA
