@@ -13,7 +13,7 @@ int attn_bwd_generic_launch(int dtype, int64_t seq, int64_t batch, int64_t nq, i
                             const void *qkv, const void *dctx, const float *lse, const float *dvec, void *dqkv,
                             hipStream_t s);
 
-// bf16, head_dim 64 or 128
+// bf16, head size 128
 bool attn_mfma_supported(int dtype, int64_t d);
 int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d, const void *qkv, void *ctx,
                          float *lse, hipStream_t s);

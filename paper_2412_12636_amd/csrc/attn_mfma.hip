@@ -1,16 +1,23 @@
-// Flash-style causal attention on the CDNA4 matrix cores (bf16 in, fp32 accumulate).
+// Flash-style causal attention on the CDNA4 matrix cores (bf16 in, fp32 accumulate), head size 128.
 //
-// The s x s score matrix is never stored: a block walks key/value tiles of 64 rows, keeps running
-// row maxima and sums in registers (online softmax) and accumulates the output in MFMA accumulators.
+// The s x s score matrix is never stored: a block walks tiles of 64 rows, keeps running row maxima
+// and sums in registers (online softmax) and accumulates its outputs in MFMA accumulators.
 //
-// Layout trick used throughout: the products are formed TRANSPOSED (S^T = K Q^T, O^T = V^T P^T, ...),
-// so that in every 32x32 accumulator tile the lane index is the row that owns the softmax
-// statistics (a query row in the forward and dQ kernels, a key row in the dK/dV kernel) and the 16
-// accumulator registers run along the reduction axis of the NEXT product.  A lane's 8 consecutive
-// accumulator registers are then exactly the 8 reduction-axis values the next MFMA expects from it,
-// under a fixed permutation of that axis (slot (half h, e) <-> offset 8*(e/4) + 4*h + e%4) which the
-// other operand follows by reading two 8-byte pieces from an LDS tile stored transposed.
-// Row statistics therefore need one cross-half exchange per tile and no row-wise shuffles.
+// Transposed products.  Everything is formed transposed (S^T = K Q^T, O^T = V^T P^T, ...), so that
+// in every 32x32 accumulator tile the lane index is the row that owns the softmax statistics (a query
+// row in the forward and dQ kernels, a key row in the dK/dV kernel) and the 16 accumulator registers
+// run along the reduction axis of the NEXT product.  A lane's 8 consecutive accumulator registers are
+// then exactly the 8 reduction-axis values the next MFMA expects from it, under a fixed permutation of
+// that axis (slot (half h, e) <-> offset 8*(e/4) + 4*h + e%4).  Row statistics need one cross-half
+// exchange per tile and no row-wise shuffles.
+//
+// One tile format.  Every staged tile is [64 rows][128] bf16, row-major as in global memory, fetched
+// straight into LDS (buffer_load ... lds), double buffered.  An operand that is needed with the tile's
+// rows as MFMA rows is read with plain 16-byte LDS reads; an operand that is needed TRANSPOSED (V in
+// O^T = V^T P^T, K in dQ^T = K^T dS^T, Q and dO in the dK/dV kernel) is read from the same tile with
+// the transposing LDS read ds_read_b64_tr_b16, which can also deliver the permuted reduction order
+// directly.  The chunk placement inside a row is chosen so that both kinds of read are free of bank
+// conflicts.
 //
 // Gradients are accumulated without atomics: dK/dV by a block that owns 128 key rows and loops over
 // the query heads of its group and all later query tiles; dQ by a block that owns 128 query rows.
@@ -22,16 +29,28 @@ namespace tmk {
 
 typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
-constexpr int TILE = 64;        // rows of a staged tile (keys in fwd/dQ, queries in dK/dV)
-constexpr int TRB = TILE * 2;   // bytes per row of a transposed tile [D][TILE]
+constexpr int D = 128;               // head size
+constexpr int TILE = 64;             // rows of a staged tile
+constexpr int ROWB = D * 2;          // bytes per tile row
+constexpr int TILE_BYTES = TILE * ROWB;
 constexpr float kLog2e = 1.4426950408889634f;
 
-__device__ __forceinline__ int swz8(int r) { return (r ^ (r >> 3)) & 7; }
+// Position of 16-byte chunk c (of 16) in tile row `row`.  row_key takes 16 distinct values over 16
+// consecutive rows (plain reads of one chunk column by 16 lanes hit 16 different bank groups); its bits
+// 2:1 are the row's low bits (the 4 rows of a transposing read land in 4 different 32-byte windows);
+// and chunk bit 1 is folded into bit 3 (the two 16-lane groups of a half-wave use different 128-byte halves).
+__device__ __forceinline__ int row_key(int row) { return ((row & 3) << 1) | ((row >> 2) & 1) | (((row >> 3) & 1) << 3); }
+__device__ __forceinline__ int place(int c, int row) { return c ^ row_key(row) ^ (((c >> 1) & 1) << 3); }
+__device__ __forceinline__ int unplace(int pc, int row) {
+  const int t = pc ^ row_key(row);
+  return t ^ (((t >> 1) & 1) << 3);
+}
 
 struct FlashParams {
   const bf16 *qkv;
@@ -43,48 +62,56 @@ struct FlashParams {
   const float *dvec;
   int seq, batch, nq, nkv, row;  // row = (nq + 2 nkv) * D
   float scale;                   // 1 / sqrt(D)
+  uint32_t qkv_bytes, ctx_bytes;
 };
 
-// ---- staging of a [TILE][D] tile from global memory --------------------------------------------
-// src points at (row 0, column 0) of the tile; consecutive rows are `stride` elements apart.
-// Rows >= rows_valid are filled with zeros.  RM: row-major copy; TR: transposed copy [D][TILE].
-template <int D, bool RM, bool TR>
-__device__ __forceinline__ void stage_tile(const bf16 *src, int64_t stride, int rows_valid, char *rm, char *tr) {
-  constexpr int CPR = D / 8;               // 16-byte chunks per row
-  constexpr int RPP = 256 / CPR;           // rows per pass
-  const int c = threadIdx.x % CPR, r0 = threadIdx.x / CPR;
+// ---- global -> LDS: one [64][128] tile, 4 wave-wide loads per wave -------------------------------
+struct TileLoader {
+  uint32_t voff[4];
+  // row_stride: elements between consecutive tile rows in global memory
+  __device__ __forceinline__ void init(int64_t row_stride, int wave, int lane) {
 #pragma unroll
-  for (int i = 0; i < TILE / RPP; ++i) {
-    const int r = r0 + i * RPP;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (r < rows_valid) v = *reinterpret_cast<const u32x4 *>(src + (int64_t)r * stride + c * 8);
-    if (RM) *reinterpret_cast<u32x4 *>(rm + r * (D * 2) + ((c ^ swz8(r)) << 4)) = v;
-    if (TR) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int dcol = c * 8 + e;
-        const uint16_t h = (uint16_t)((e & 1) ? (v[e >> 1] >> 16) : (v[e >> 1] & 0xffffu));
-        *reinterpret_cast<uint16_t *>(tr + dcol * TRB + (((r >> 3) ^ swz8(dcol)) << 4) + ((r & 7) << 1)) = h;
-      }
+    for (int i = 0; i < 4; ++i) {
+      const int idx = (i * 4 + wave) * 64 + lane;  // chunk position in the LDS tile
+      const int row = idx >> 4, c = unplace(idx & 15, row);
+      voff[i] = (uint32_t)(((int64_t)row * row_stride + c * 8) * 2);
     }
   }
-}
+  // rows0: element offset of tile row 0 (a multiple of the row stride), base: element offset of column 0
+  // inside a row (below the row stride).  The row part travels in the per-lane offset, which the
+  // hardware checks against the buffer size, so rows past the tensor read as zero.
+  __device__ __forceinline__ void issue(rsrc_t rs, char *tile, int64_t rows0, int64_t base, int wave) const {
+    const uint32_t roff = (uint32_t)(rows0 * 2), soff = (uint32_t)(base * 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * 4 + wave) * 1024), 16, voff[i] + roff, soff, 0,
+                                               0);
+  }
+};
 
-// A-operand fragment from a row-major tile: 8 consecutive reduction elements of row r
-template <int D> __device__ __forceinline__ bf16x8 frag_rm(const char *rm, int r, int ks, int hh) {
-  return *reinterpret_cast<const bf16x8 *>(rm + r * (D * 2) + ((((2 * ks + hh)) ^ swz8(r)) << 4));
+// A-operand fragment, tile rows as MFMA rows: row r32 + lane%32, reduction slots 16ks + 8hh + 0..7
+__device__ __forceinline__ bf16x8 frag_rows(const char *tile, int r32, int ks, int lane) {
+  const int r = r32 + (lane & 31), hh = lane >> 5;
+  return *reinterpret_cast<const bf16x8 *>(tile + r * ROWB + (place(2 * ks + hh, r) << 4));
 }
-// A-operand fragment from a transposed tile: row dcol, permuted reduction slots of step kk
-__device__ __forceinline__ bf16x8 frag_tr(const char *tr, int dcol, int kk, int hh) {
-  const char *base = tr + dcol * TRB + (hh << 3);
-  const int sw = swz8(dcol);
-  union { u32x2 u[2]; bf16x8 v; } x;
-  x.u[0] = *reinterpret_cast<const u32x2 *>(base + (((2 * kk) ^ sw) << 4));
-  x.u[1] = *reinterpret_cast<const u32x2 *>(base + (((2 * kk + 1) ^ sw) << 4));
+// A-operand fragment of the TRANSPOSED tile: MFMA row = tile column c32 + lane%32, reduction axis =
+// tile rows 16kk .. 16kk+15 in the permuted order (slot (hh, e) <-> row 16kk + 8*(e/4) + 4hh + e%4).
+// ds_read_b64_tr_b16: within 16 lanes, lane i receives element i%4 of the 8-byte pieces addressed by
+// lanes i/4, i/4+4, i/4+8, i/4+12; lane s addresses tile[row0 + s/4][col0 + 4*(s%4) ..+3].
+__device__ __forceinline__ bf16x8 frag_cols(const char *tile, int c32, int kk, int lane) {
+  const int g = lane >> 4, s = lane & 15;
+  const int col = c32 + 16 * (g & 1) + 4 * (s & 3);
+  const int c = col >> 3, half = (col >> 2) & 1;
+  union { s16x4 h[2]; bf16x8 v; } x;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int row = 16 * kk + 8 * t + 4 * (g >> 1) + (s >> 2);
+    const char *a = tile + row * ROWB + (place(c, row) << 4) + (half << 3);
+    x.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(a));
+  }
   return x.v;
 }
-// B-operand fragments straight from global memory: 8 consecutive elements of row (l32) per step
-template <int D>
+// B-operand fragments straight from global memory: 8 consecutive elements of row (lane%32) per step
 __device__ __forceinline__ void load_row_frags(const bf16 *rowptr, bool valid, int hh, bf16x8 (&f)[D / 16]) {
 #pragma unroll
   for (int ks = 0; ks < D / 16; ++ks) {
@@ -105,7 +132,6 @@ __device__ __forceinline__ bf16x8 pack8(const f32x16 &a, int v0) {
 __device__ __forceinline__ int acc_row(int v, int hh) { return 8 * (v >> 2) + 4 * hh + (v & 3); }
 
 // writes O^T-style accumulators (rows = head-dim slots, lane = token row) to out[token][col0 + d]
-template <int D>
 __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 32], float mul, bf16 *dst_row, int hh) {
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
@@ -117,26 +143,28 @@ __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 32], fl
       *reinterpret_cast<bf16x4 *>(dst_row + dt * 32 + 8 * q4 + 4 * hh) = o;
     }
 }
+__device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // =================================================================================================
 // forward: block = 128 query rows of one (batch entry, query head); wave = 32 query rows
 // =================================================================================================
-template <int D>
-__global__ __launch_bounds__(256) void flash_fwd_kernel(const FlashParams p) {
-  __shared__ __align__(16) char k_rm[TILE * D * 2];
-  __shared__ __align__(16) char v_tr[D * TRB];
+__global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) {
+  __shared__ __align__(16) char lds[2][2][TILE_BYTES];  // [stage][K, V]
   const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
   const int kap = g / (p.nq / p.nkv);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
   const int q0w = qt * 128 + wave * 32;
   const int q = q0w + l32;
   const bool qvalid = q < p.seq;
   const int64_t tstride = (int64_t)p.batch * p.row;  // elements between consecutive positions
-  const bf16 *base = p.qkv + (int64_t)n * p.row;
   const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
+  const rsrc_t rs = make_rsrc(p.qkv, p.qkv_bytes);
+  TileLoader ld;
+  ld.init(tstride, wave, lane);
 
   bf16x8 qf[D / 16];
-  load_row_frags<D>(base + (int64_t)q * tstride + g * D, qvalid, hh, qf);
+  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)q * tstride + g * D, qvalid, hh, qf);
 
   f32x16 o[D / 32];
 #pragma unroll
@@ -148,13 +176,19 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const FlashParams p) {
 
   const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
   const int ntile = (kv_end + TILE - 1) / TILE;
+  ld.issue(rs, lds[0][0], 0, (int64_t)n * p.row + koff, wave);
+  ld.issue(rs, lds[0][1], 0, (int64_t)n * p.row + voff, wave);
   for (int jt = 0; jt < ntile; ++jt) {
-    const int j0 = jt * TILE;
-    __syncthreads();
-    stage_tile<D, true, false>(base + (int64_t)j0 * tstride + koff, tstride, p.seq - j0, k_rm, nullptr);
-    stage_tile<D, false, true>(base + (int64_t)j0 * tstride + voff, tstride, p.seq - j0, nullptr, v_tr);
-    __syncthreads();
+    const int j0 = jt * TILE, cur = jt & 1;
+    wait_loads();
+    __builtin_amdgcn_s_barrier();  // tile jt is in LDS; everyone is done with the other stage
+    if (jt + 1 < ntile) {
+      const int64_t r0 = (int64_t)(j0 + TILE) * tstride;
+      ld.issue(rs, lds[cur ^ 1][0], r0, (int64_t)n * p.row + koff, wave);
+      ld.issue(rs, lds[cur ^ 1][1], r0, (int64_t)n * p.row + voff, wave);
+    }
     if (j0 > q0w + 31) continue;  // every key of this tile lies after every query row of the wave
+    const char *kt = lds[cur][0], *vt = lds[cur][1];
 
     f32x16 s[2];
 #pragma unroll
@@ -163,7 +197,7 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const FlashParams p) {
       for (int v = 0; v < 16; ++v) s[t][v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks)
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm<D>(k_rm, t * 32 + l32, ks, hh), qf[ks], s[t], 0, 0, 0);
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt, t * 32, ks, lane), qf[ks], s[t], 0, 0, 0);
     }
     const bool diag = j0 + TILE - 1 > q0w;  // some key index may exceed some query index
     float mx = m;
@@ -198,13 +232,14 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const FlashParams p) {
       const bf16x8 pf = pack8(s[kk >> 1], 8 * (kk & 1));
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt)
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(v_tr, dt * 32 + l32, kk, hh), pf, o[dt], 0, 0, 0);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(vt, dt * 32, kk, lane), pf, o[dt], 0, 0, 0);
     }
   }
+  wait_loads();
   l += __shfl_xor(l, 32, 64);
   if (qvalid) {
     const int64_t trow = (int64_t)q * p.batch + n;
-    store_transposed<D>(o, 1.f / l, p.ctx + trow * (p.nq * D) + g * D, hh);
+    store_transposed(o, 1.f / l, p.ctx + trow * (p.nq * D) + g * D, hh);
     if (hh == 0) p.lse[((int64_t)n * p.nq + g) * p.seq + q] = (m + log2f(l)) * 0.6931471805599453f;
   }
 }
@@ -212,25 +247,25 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const FlashParams p) {
 // =================================================================================================
 // dQ: same walk as the forward pass; dQ^T += K^T dS^T
 // =================================================================================================
-template <int D>
-__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const FlashParams p) {
-  __shared__ __align__(16) char k_rm[TILE * D * 2];
-  __shared__ __align__(16) char v_rm[TILE * D * 2];
-  __shared__ __align__(16) char k_tr[D * TRB];
+__global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams p) {
+  __shared__ __align__(16) char lds[2][2][TILE_BYTES];  // [stage][K, V]
   const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
   const int kap = g / (p.nq / p.nkv);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
   const int q0w = qt * 128 + wave * 32;
   const int q = q0w + l32;
   const bool qvalid = q < p.seq;
   const int64_t tstride = (int64_t)p.batch * p.row;
-  const bf16 *base = p.qkv + (int64_t)n * p.row;
   const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
   const int64_t cstride = (int64_t)p.batch * p.nq * D;
+  const rsrc_t rs = make_rsrc(p.qkv, p.qkv_bytes);
+  TileLoader ld;
+  ld.init(tstride, wave, lane);
 
   bf16x8 qf[D / 16], dof[D / 16];
-  load_row_frags<D>(base + (int64_t)q * tstride + g * D, qvalid, hh, qf);
-  load_row_frags<D>(p.dctx + (int64_t)n * p.nq * D + (int64_t)q * cstride + g * D, qvalid, hh, dof);
+  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)q * tstride + g * D, qvalid, hh, qf);
+  load_row_frags(p.dctx + (int64_t)n * p.nq * D + (int64_t)q * cstride + g * D, qvalid, hh, dof);
   const int64_t si = ((int64_t)n * p.nq + g) * p.seq + q;
   const float lse2 = qvalid ? p.lse_in[si] * kLog2e : 0.f;
   const float dq_d = qvalid ? p.dvec[si] : 0.f;
@@ -244,13 +279,19 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const FlashParams p) 
 
   const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
   const int ntile = (kv_end + TILE - 1) / TILE;
+  ld.issue(rs, lds[0][0], 0, (int64_t)n * p.row + koff, wave);
+  ld.issue(rs, lds[0][1], 0, (int64_t)n * p.row + voff, wave);
   for (int jt = 0; jt < ntile; ++jt) {
-    const int j0 = jt * TILE;
-    __syncthreads();
-    stage_tile<D, true, true>(base + (int64_t)j0 * tstride + koff, tstride, p.seq - j0, k_rm, k_tr);
-    stage_tile<D, true, false>(base + (int64_t)j0 * tstride + voff, tstride, p.seq - j0, v_rm, nullptr);
-    __syncthreads();
+    const int j0 = jt * TILE, cur = jt & 1;
+    wait_loads();
+    __builtin_amdgcn_s_barrier();
+    if (jt + 1 < ntile) {
+      const int64_t r0 = (int64_t)(j0 + TILE) * tstride;
+      ld.issue(rs, lds[cur ^ 1][0], r0, (int64_t)n * p.row + koff, wave);
+      ld.issue(rs, lds[cur ^ 1][1], r0, (int64_t)n * p.row + voff, wave);
+    }
     if (j0 > q0w + 31) continue;
+    const char *kt = lds[cur][0], *vt = lds[cur][1];
 
     const bool diag = j0 + TILE - 1 > q0w;
     f32x16 ds[2];
@@ -261,8 +302,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const FlashParams p) 
       for (int v = 0; v < 16; ++v) s[v] = dp[v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm<D>(k_rm, t * 32 + l32, ks, hh), qf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm<D>(v_rm, t * 32 + l32, ks, hh), dof[ks], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt, t * 32, ks, lane), qf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt, t * 32, ks, lane), dof[ks], dp, 0, 0, 0);
       }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
@@ -276,35 +317,39 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const FlashParams p) 
       const bf16x8 df = pack8(ds[kk >> 1], 8 * (kk & 1));
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt)
-        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(k_tr, dt * 32 + l32, kk, hh), df, acc[dt], 0, 0, 0);
+        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(kt, dt * 32, kk, lane), df, acc[dt], 0, 0, 0);
     }
   }
-  if (qvalid) store_transposed<D>(acc, p.scale, p.dqkv + ((int64_t)q * p.batch + n) * p.row + g * D, hh);
+  wait_loads();
+  if (qvalid) store_transposed(acc, p.scale, p.dqkv + ((int64_t)q * p.batch + n) * p.row + g * D, hh);
 }
 
 // =================================================================================================
 // dK, dV: block = 128 key rows of one (batch entry, kv head); wave = 32 key rows; loops over the
 // query heads of the group and over query tiles of 64 rows from the diagonal to the end
 // =================================================================================================
-template <int D>
 __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p) {
-  extern __shared__ __align__(16) char smem[];  // 4 tiles + 2 * TILE floats (above the static 64 KB limit)
-  char *q_rm = smem, *do_rm = smem + TILE * D * 2, *q_tr = smem + 2 * TILE * D * 2, *do_tr = q_tr + D * TRB;
-  float *lse_s = reinterpret_cast<float *>(do_tr + D * TRB), *dv_s = lse_s + TILE;
+  extern __shared__ __align__(16) char smem[];  // [stage][Q, dO] tiles, then [stage][lse, D] rows of floats
   const int kt = blockIdx.x, kap = blockIdx.y, n = blockIdx.z;
   const int group = p.nq / p.nkv;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, hh = lane >> 5;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int l32 = lane & 31, hh = lane >> 5;
   const int j0w = kt * 128 + wave * 32;
   const int j = j0w + l32;
   const bool jvalid = j < p.seq;
   const int64_t tstride = (int64_t)p.batch * p.row;
-  const bf16 *base = p.qkv + (int64_t)n * p.row;
   const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
   const int64_t cstride = (int64_t)p.batch * p.nq * D;
+  const rsrc_t rq = make_rsrc(p.qkv, p.qkv_bytes), rdo = make_rsrc(p.dctx, p.ctx_bytes);
+  TileLoader lq, ldo;
+  lq.init(tstride, wave, lane);
+  ldo.init(cstride, wave, lane);
+  auto tile = [&](int stage, int which) { return smem + (stage * 2 + which) * TILE_BYTES; };
+  float *stats = reinterpret_cast<float *>(smem + 4 * TILE_BYTES);  // [stage][2][TILE]
 
   bf16x8 kf[D / 16], vf[D / 16];
-  load_row_frags<D>(base + (int64_t)j * tstride + koff, jvalid, hh, kf);
-  load_row_frags<D>(base + (int64_t)j * tstride + voff, jvalid, hh, vf);
+  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)j * tstride + koff, jvalid, hh, kf);
+  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)j * tstride + voff, jvalid, hh, vf);
 
   f32x16 dk[D / 32], dv[D / 32];
 #pragma unroll
@@ -315,101 +360,118 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p)
 
   const int it_begin = (kt * 128) / TILE;
   const int it_end = (p.seq + TILE - 1) / TILE;
-  for (int gi = 0; gi < group; ++gi) {
-    const int g = kap * group + gi;
-    const float *lse_g = p.lse_in + ((int64_t)n * p.nq + g) * p.seq;
-    const float *dvec_g = p.dvec + ((int64_t)n * p.nq + g) * p.seq;
-    for (int it = it_begin; it < it_end; ++it) {
-      const int i0 = it * TILE;
-      __syncthreads();
-      stage_tile<D, true, true>(base + (int64_t)i0 * tstride + g * D, tstride, p.seq - i0, q_rm, q_tr);
-      stage_tile<D, true, true>(p.dctx + (int64_t)n * p.nq * D + (int64_t)i0 * cstride + g * D, cstride, p.seq - i0,
-                                do_rm, do_tr);
-      if (threadIdx.x < TILE) {
-        const int i = i0 + threadIdx.x;
-        lse_s[threadIdx.x] = i < p.seq ? lse_g[i] * kLog2e : 0.f;
-        dv_s[threadIdx.x] = i < p.seq ? dvec_g[i] : 0.f;
-      }
-      __syncthreads();
-      if (i0 + TILE - 1 < j0w) continue;  // every query of this tile lies before every key row of the wave
+  const int per_head = it_end - it_begin, total = group * per_head;
+  // one flat sequence of (query head, query tile) steps, double buffered; the row statistics of a
+  // step are fetched into registers one step ahead by the first wave and put into LDS just before
+  // the barrier that publishes the step's tiles
+  float st_lse = 0.f, st_d = 0.f;
+  auto issue_step = [&](int step, int stage) {
+    const int g = kap * group + step / per_head, i0 = (it_begin + step % per_head) * TILE;
+    lq.issue(rq, tile(stage, 0), (int64_t)i0 * tstride, (int64_t)n * p.row + g * D, wave);
+    ldo.issue(rdo, tile(stage, 1), (int64_t)i0 * cstride, (int64_t)n * p.nq * D + g * D, wave);
+    if (threadIdx.x < TILE) {
+      const int i = i0 + threadIdx.x;
+      const int64_t sidx = ((int64_t)n * p.nq + g) * p.seq + i;
+      st_lse = i < p.seq ? p.lse_in[sidx] * kLog2e : 0.f;
+      st_d = i < p.seq ? p.dvec[sidx] : 0.f;
+    }
+  };
+  issue_step(0, 0);
+  for (int step = 0; step < total; ++step) {
+    const int cur = step & 1;
+    const int i0 = (it_begin + step % per_head) * TILE;
+    wait_loads();
+    if (threadIdx.x < TILE) {
+      float *st = stats + cur * 2 * TILE;
+      st[threadIdx.x] = st_lse;
+      st[TILE + threadIdx.x] = st_d;
+    }
+    __syncthreads();  // tiles and statistics of this step are visible; the other stage is free
+    if (step + 1 < total) issue_step(step + 1, cur ^ 1);
+    if (i0 + TILE - 1 < j0w) continue;  // every query of this tile lies before every key row of the wave
+    const char *qt = tile(cur, 0), *dot = tile(cur, 1);
+    const float *lse_s = stats + cur * 2 * TILE, *dv_s = lse_s + TILE;
 
-      const bool diag = i0 < j0w + 31;  // some query index may be below some key index
-      f32x16 pr[2], ds[2];
+    const bool diag = i0 < j0w + 31;  // some query index may be below some key index
+    f32x16 pr[2], ds[2];
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        f32x16 s, dp;
+    for (int t = 0; t < 2; ++t) {
+      f32x16 s, dp;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[v] = dp[v] = 0.f;
+      for (int v = 0; v < 16; ++v) s[v] = dp[v] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks) {
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm<D>(q_rm, t * 32 + l32, ks, hh), kf[ks], s, 0, 0, 0);
-          dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rm<D>(do_rm, t * 32 + l32, ks, hh), vf[ks], dp, 0, 0, 0);
-        }
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const int ib = t * 32 + 8 * q4 + 4 * hh;  // four consecutive query rows of this lane
-          const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + ib);
-          const f32x4 d4 = *reinterpret_cast<const f32x4 *>(dv_s + ib);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const int v = q4 * 4 + e;
-            float x = __builtin_amdgcn_exp2f(s[v] * sc2 - l4[e]);
-            if (diag && i0 + ib + e < j) x = 0.f;
-            pr[t][v] = x;
-            ds[t][v] = x * (dp[v] - d4[e]);
-          }
-        }
+      for (int ks = 0; ks < D / 16; ++ks) {
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(qt, t * 32, ks, lane), kf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot, t * 32, ks, lane), vf[ks], dp, 0, 0, 0);
       }
 #pragma unroll
-      for (int kk = 0; kk < TILE / 16; ++kk) {
-        const bf16x8 pf = pack8(pr[kk >> 1], 8 * (kk & 1));
-        const bf16x8 df = pack8(ds[kk >> 1], 8 * (kk & 1));
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const int ib = t * 32 + 8 * q4 + 4 * hh;  // four consecutive query rows of this lane
+        const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + ib);
+        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(dv_s + ib);
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt) {
-          dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(do_tr, dt * 32 + l32, kk, hh), pf, dv[dt], 0, 0, 0);
-          dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_tr(q_tr, dt * 32 + l32, kk, hh), df, dk[dt], 0, 0, 0);
+        for (int e = 0; e < 4; ++e) {
+          const int v = q4 * 4 + e;
+          float x = __builtin_amdgcn_exp2f(s[v] * sc2 - l4[e]);
+          if (diag && i0 + ib + e < j) x = 0.f;
+          pr[t][v] = x;
+          ds[t][v] = x * (dp[v] - d4[e]);
         }
       }
     }
+#pragma unroll
+    for (int kk = 0; kk < TILE / 16; ++kk) {
+      const bf16x8 pf = pack8(pr[kk >> 1], 8 * (kk & 1));
+      const bf16x8 df = pack8(ds[kk >> 1], 8 * (kk & 1));
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt) {
+        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot, dt * 32, kk, lane), pf, dv[dt], 0, 0, 0);
+        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt, dt * 32, kk, lane), df, dk[dt], 0, 0, 0);
+      }
+    }
   }
+  wait_loads();
   if (jvalid) {
     bf16 *out = p.dqkv + ((int64_t)j * p.batch + n) * p.row;
-    store_transposed<D>(dk, p.scale, out + koff, hh);
-    store_transposed<D>(dv, 1.f, out + voff, hh);
+    store_transposed(dk, p.scale, out + koff, hh);
+    store_transposed(dv, 1.f, out + voff, hh);
   }
 }
 
-bool attn_mfma_supported(int dtype, int64_t d) { return dtype == TM_DTYPE_BF16 && (d == 128 || d == 64); }
+bool attn_mfma_supported(int dtype, int64_t d) { return dtype == TM_DTYPE_BF16 && d == D; }
 
-static FlashParams make_params(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d) {
+static FlashParams make_params(int64_t seq, int64_t batch, int64_t nq, int64_t nkv) {
   FlashParams p = {};
   p.seq = (int)seq;
   p.batch = (int)batch;
   p.nq = (int)nq;
   p.nkv = (int)nkv;
-  p.row = (int)((nq + 2 * nkv) * d);
-  p.scale = (float)(1.0 / sqrt((double)d));
+  p.row = (int)((nq + 2 * nkv) * D);
+  p.scale = (float)(1.0 / sqrt((double)D));
+  p.qkv_bytes = (uint32_t)(seq * batch * p.row * 2);
+  p.ctx_bytes = (uint32_t)(seq * batch * nq * D * 2);
   return p;
 }
 
 int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d, const void *qkv, void *ctx,
                          float *lse, hipStream_t s) {
-  FlashParams p = make_params(seq, batch, nq, nkv, d);
+  (void)d;
+  if (seq * batch * (nq + 2 * nkv) * D * 2 >= (1LL << 31)) return fail(TM_ESIZE, "flash_fwd: qkv tensor above 2 GiB");
+  FlashParams p = make_params(seq, batch, nq, nkv);
   p.qkv = (const bf16 *)qkv;
   p.ctx = (bf16 *)ctx;
   p.lse = lse;
   dim3 grid((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
   g_last_kernel = "flash_fwd_kernel";
-  if (d == 128)
-    flash_fwd_kernel<128><<<grid, 256, 0, s>>>(p);
-  else
-    flash_fwd_kernel<64><<<grid, 256, 0, s>>>(p);
+  flash_fwd_kernel<<<grid, 256, 0, s>>>(p);
   return check_launch("flash_fwd");
 }
 
 int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d, const void *qkv,
                          const void *dctx, const float *lse, const float *dvec, void *dqkv, hipStream_t s) {
-  FlashParams p = make_params(seq, batch, nq, nkv, d);
+  (void)d;
+  if (seq * batch * (nq + 2 * nkv) * D * 2 >= (1LL << 31)) return fail(TM_ESIZE, "flash_bwd: qkv tensor above 2 GiB");
+  FlashParams p = make_params(seq, batch, nq, nkv);
   p.qkv = (const bf16 *)qkv;
   p.dctx = (const bf16 *)dctx;
   p.lse_in = lse;
@@ -417,24 +479,17 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   p.dqkv = (bf16 *)dqkv;
   dim3 gq((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
   dim3 gk((unsigned)ceil_div(seq, 128), (unsigned)nkv, (unsigned)batch);
-  const int lds = (int)(4 * TILE * d * 2 + 2 * TILE * sizeof(float));
+  const int lds = 4 * TILE_BYTES + 2 * 2 * TILE * (int)sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(flash_bwd_dkv_kernel<128>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILE * 128 * 2 + 2 * TILE * 4) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void *>(flash_bwd_dkv_kernel<64>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TILE * 64 * 2 + 2 * TILE * 4) != hipSuccess)
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&flash_bwd_dkv_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
       return fail(TM_ELAUNCH, "flash_bwd: cannot reserve LDS");
     attr_set = true;
   }
   g_last_kernel = "flash_bwd_dq_kernel+flash_bwd_dkv_kernel";
-  if (d == 128) {
-    flash_bwd_dq_kernel<128><<<gq, 256, 0, s>>>(p);
-    flash_bwd_dkv_kernel<128><<<gk, 256, lds, s>>>(p);
-  } else {
-    flash_bwd_dq_kernel<64><<<gq, 256, 0, s>>>(p);
-    flash_bwd_dkv_kernel<64><<<gk, 256, lds, s>>>(p);
-  }
+  flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
+  flash_bwd_dkv_kernel<<<gk, 256, lds, s>>>(p);
   return check_launch("flash_bwd");
 }
 
