@@ -155,6 +155,8 @@ def main() -> int:
     # one micro-batch per iteration: the backward pass stores the gradients (their old contents are
     # dead), so nothing has to clear the buffer and Adam only reads it
     tm.tm_stage_grad_mode(h, True)
+    # once per process: time the GEMM tile configurations on this shard's twelve products
+    tm.tm_stage_tune(h, int(torch.cuda.current_stream().cuda_stream))
     hp = tm.make_hparams(**si.ADAM_DEFAULTS)
     stream = int(torch.cuda.current_stream().cuda_stream)
     step_no = [0]

@@ -132,6 +132,19 @@ int tm_stage_param_layout(const tm_stage_config_t *cfg, int index, const char **
 int tm_stage_init(const tm_stage_config_t *cfg, const tm_stage_buffers_t *buffers, tm_stage_t **out);
 
 /*
+ * Optional, bf16 stages: measures the tile configurations of the matrix-core
+ * GEMM kernel on the twelve products of this stage's shard shape (three per
+ * linear map of the transformer block, section 6.1's per-rank share) and makes
+ * every later product of those shapes, in this process, use the fastest.
+ * Runs on `stream`, WAITS for it, and uses the workspace as operands and
+ * results: call it before the first forward pass (a stash from an earlier
+ * forward pass is invalidated: the next call must be tm_stage_fwd).  Without
+ * it a cost model picks the configurations.  The choice changes speed only:
+ * every configuration accumulates each output in the same order.
+ */
+int tm_stage_tune(tm_stage_t *st, void *stream);
+
+/*
  * Forward pass of all layers (section 4.2: the forward half of the shadow
  * iteration; the pipeline receive is served by x_in).  x_in and y_out are
  * device pointers to [seq, micro_batch, hidden] tensors of the stage dtype,

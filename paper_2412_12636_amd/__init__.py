@@ -63,6 +63,7 @@ EXPORTS = {
     "tm_adam_step_flat": (C.c_int, [C.c_int64] + [C.c_void_p] * 5 + [C.POINTER(tm_adam_hparams_t), C.c_int64,
                                                                        C.c_void_p]),
     "tm_stage_grad_mode": (C.c_int, [C.c_void_p, C.c_int]),
+    "tm_stage_tune": (C.c_int, [C.c_void_p, C.c_void_p]),
     "tm_stage_destroy": (None, [C.c_void_p]),
     "tm_stage_profile_enable": (C.c_int, [C.c_void_p, C.c_int]),
     "tm_stage_profile_collect": (C.c_int, [C.c_void_p, C.POINTER(tm_profile_entry_t), C.c_int]),
@@ -174,6 +175,10 @@ def tm_adam_step(handle: int, hp: tm_adam_hparams_t, step: int, stream: int = 0)
 
 def tm_adam_step_flat(n: int, p, g, m, v, p_bf16, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:
     _check(lib().tm_adam_step_flat(n, _ptr(p), _ptr(g), _ptr(m), _ptr(v), _ptr(p_bf16), C.byref(hp), step, stream))
+
+
+def tm_stage_tune(handle: int, stream: int = 0) -> None:
+    _check(lib().tm_stage_tune(handle, stream))
 
 
 def tm_stage_grad_mode(handle: int, overwrite: bool) -> None:

@@ -28,6 +28,9 @@ int gemm_generic(int dtype, const GemmArgs &g, hipStream_t s);
 // 16-byte aligned base pointers.
 bool gemm_mfma_supported(const GemmArgs &g);
 int gemm_mfma(const GemmArgs &g, hipStream_t s);
-void gemm_pick_tile(int64_t M, int64_t N, int &bm, int &bn);
+// Measures the tile configurations for one layout and shape, on n instances of the product that live
+// in different memory (the launches cycle through them), and makes later gemm_mfma() calls of that layout
+// and shape use the fastest.  Overwrites every C; waits for the stream.  Without it a cost model picks.
+int gemm_mfma_tune(const GemmArgs *variants, int n, hipStream_t s);
 
 }  // namespace tmk

@@ -1,15 +1,20 @@
-// bf16 GEMM through the matrix cores: layout dispatch and tile choice.  The kernels live in
-// gemm_mfma_impl.h and are instantiated in one translation unit per operand layout.
+// bf16 GEMM through the matrix cores: layout dispatch and choice of the tile configuration.  The kernels
+// live in gemm_mfma_impl.h and are instantiated in one translation unit per operand layout.
 #include <stdio.h>
 #include <stdlib.h>
+
+#include <map>
+#include <mutex>
+#include <tuple>
+#include <vector>
 
 #include "gemm.h"
 
 namespace tmk {
 
-int gemm_mfma_nt(const GemmArgs &g, hipStream_t s);  // y = x W^T         (both reduction axes contiguous)
-int gemm_mfma_nn(const GemmArgs &g, hipStream_t s);  // dx = dy W         (W read along its strided axis)
-int gemm_mfma_tn(const GemmArgs &g, hipStream_t s);  // dW += dy^T x      (both strided, fp32 accumulate)
+int gemm_mfma_nt(const GemmArgs &g, int config, hipStream_t s);  // y = x W^T       (both reduction axes contiguous)
+int gemm_mfma_nn(const GemmArgs &g, int config, hipStream_t s);  // dx = dy W       (W read along its strided axis)
+int gemm_mfma_tn(const GemmArgs &g, int config, hipStream_t s);  // dW (+)= dy^T x  (both strided, fp32 result)
 
 bool gemm_mfma_supported(const GemmArgs &g) {
   auto operand_ok = [&](const void *ptr, int64_t rs, int64_t cs, int64_t rows) {
@@ -29,50 +34,134 @@ bool gemm_mfma_supported(const GemmArgs &g) {
   return g.c_mode ? (!akc && !bkc) : akc;
 }
 
-// Block tile: the candidate with the lowest estimated time.  A compute unit holds `occ` blocks of a
-// tile shape at once (LDS: two stages of (BM+BN) x 128 bytes out of 160 KB), so the chip works through
-// the tiles in passes of 256*occ, each pass taking occ * BM * BN / speed, where speed is the shape's
-// measured rate relative to 128x192 on the 175B-shard products.  TM_GEMM_TILE=<BM>x<BN> in the
-// environment overrides the choice (tuning aid).
-void gemm_pick_tile(int64_t M, int64_t N, int &bm, int &bn) {
-  static const int cand[9][2] = {{128, 192}, {128, 128}, {256, 256}, {256, 192}, {192, 192},
-                                 {256, 128}, {128, 256}, {192, 128}, {192, 256}};
-  static const double speed[9] = {1.0, 0.97, 1.05, 0.95, 0.9, 0.87, 0.87, 0.87, 0.75};
-  static const int occ[9] = {2, 2, 1, 1, 1, 1, 1, 2, 1};
-  static int forced_m = -1, forced_n = -1;
-  if (forced_m < 0) {
-    forced_m = forced_n = 0;
-    if (const char *e = getenv("TM_GEMM_TILE")) {
-      int a = 0, b = 0;
-      if (sscanf(e, "%dx%d", &a, &b) == 2)
-        for (int c = 0; c < 9; ++c)
-          if (cand[c][0] == a && cand[c][1] == b) forced_m = a, forced_n = b;
-    }
-  }
-  if (forced_m > 0) {
-    bm = forced_m;
-    bn = forced_n;
-    return;
-  }
+// ---- tile configurations -------------------------------------------------------------------------
+// Same order as TM_GEMM_CONFIGS in gemm_mfma_impl.h.  occ: blocks a compute unit holds at once (LDS: two
+// stages of (BM+BN) x 128 bytes out of 160 KB; four-wave blocks of up to 256x128 outputs leave room for
+// two).  speed: measured rate per busy compute unit relative to 128x192 on the 175B-shard products.
+struct TileConfig {
+  int bm, bn, wgm, wgn, occ;
+  double speed;
+};
+static const TileConfig kConfigs[] = {
+    {128, 192, 2, 2, 2, 1.00}, {128, 128, 2, 2, 2, 0.92}, {192, 128, 2, 2, 2, 0.90}, {256, 192, 4, 2, 1, 1.08},
+    {192, 256, 2, 4, 1, 1.00}, {256, 256, 2, 4, 1, 1.04}, {256, 256, 4, 2, 1, 1.04}, {256, 128, 4, 2, 1, 0.85},
+};
+constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
+
+static int layout_of(const GemmArgs &g) { return g.c_mode ? 2 : (g.b_cs == 1 ? 0 : 1); }
+
+// Estimated time: the chip works through the tiles in passes of 256*occ blocks, each pass taking
+// occ * BM * BN / speed.
+static int heuristic_config(const GemmArgs &g) {
   double best = 1e300;
-  for (int c = 0; c < 9; ++c) {
-    const int64_t nb = ceil_div(M, cand[c][0]) * ceil_div(N, cand[c][1]);
-    const double passes = (double)ceil_div(nb, 256 * occ[c]);
-    const double cost = passes * occ[c] * cand[c][0] * cand[c][1] / speed[c];
-    if (cost < best) {
-      best = cost;
-      bm = cand[c][0];
-      bn = cand[c][1];
-    }
+  int pick = 0;
+  for (int c = 0; c < kNumConfigs; ++c) {
+    const TileConfig &t = kConfigs[c];
+    const int64_t nb = ceil_div(g.M, t.bm) * ceil_div(g.N, t.bn);
+    const double passes = (double)ceil_div(nb, 256 * t.occ);
+    const double cost = passes * t.occ * t.bm * t.bn / t.speed;
+    if (cost < best) best = cost, pick = c;
   }
+  return pick;
 }
 
-int gemm_mfma(const GemmArgs &g, hipStream_t s) {
+// TM_GEMM_TILE=<BM>x<BN>x<WGM>x<WGN> in the environment forces one configuration (tuning aid).
+static int forced_config() {
+  static int forced = -2;
+  if (forced == -2) {
+    forced = -1;
+    if (const char *e = getenv("TM_GEMM_TILE")) {
+      int a = 0, b = 0, c = 0, d = 0;
+      if (sscanf(e, "%dx%dx%dx%d", &a, &b, &c, &d) == 4)
+        for (int i = 0; i < kNumConfigs; ++i)
+          if (kConfigs[i].bm == a && kConfigs[i].bn == b && kConfigs[i].wgm == c && kConfigs[i].wgn == d) forced = i;
+    }
+  }
+  return forced;
+}
+
+// Configurations found by gemm_mfma_tune(), keyed by (layout, M, N, K).
+typedef std::tuple<int, int64_t, int64_t, int64_t> TuneKey;
+static std::map<TuneKey, int> g_tuned;
+static std::mutex g_tuned_mutex;
+
+static int pick_config(const GemmArgs &g) {
+  const int f = forced_config();
+  if (f >= 0) return f;
+  {
+    std::lock_guard<std::mutex> lock(g_tuned_mutex);
+    auto it = g_tuned.find(TuneKey(layout_of(g), g.M, g.N, g.K));
+    if (it != g_tuned.end()) return it->second;
+  }
+  return heuristic_config(g);
+}
+
+static int launch_config(const GemmArgs &g, int config, hipStream_t s) {
   const bool akc = g.a_cs == 1, bkc = g.b_cs == 1;
-  if (!g.c_mode && akc && bkc) return gemm_mfma_nt(g, s);
-  if (!g.c_mode && akc && !bkc) return gemm_mfma_nn(g, s);
-  if (g.c_mode && !akc && !bkc) return gemm_mfma_tn(g, s);
+  if (!g.c_mode && akc && bkc) return gemm_mfma_nt(g, config, s);
+  if (!g.c_mode && akc && !bkc) return gemm_mfma_nn(g, config, s);
+  if (g.c_mode && !akc && !bkc) return gemm_mfma_tn(g, config, s);
   return fail(TM_EINVAL, "gemm_mfma: operand layout not instantiated");
+}
+
+int gemm_mfma(const GemmArgs &g, hipStream_t s) { return launch_config(g, pick_config(g), s); }
+
+// Times every configuration and remembers the fastest for this layout and shape.  `variants` are n
+// instances of the same product on different memory (say, the weights of different layers): the
+// launches cycle through them, so that an operand that is cold in the real sequence is cold here too.
+// The result buffers are overwritten several times; an accumulating product is timed in its
+// overwriting form.  Synchronises the stream.
+int gemm_mfma_tune(const GemmArgs *variants, int n, hipStream_t s) {
+  if (n <= 0 || forced_config() >= 0) return TM_OK;
+  std::vector<GemmArgs> v(variants, variants + n);
+  for (GemmArgs &g : v) {
+    if (!gemm_mfma_supported(g) || g.K % 64 != 0) return TM_OK;
+    if (g.M != v[0].M || g.N != v[0].N || g.K != v[0].K || layout_of(g) != layout_of(v[0]))
+      return fail(TM_EINVAL, "gemm_mfma_tune: variants differ in shape or layout");
+    g.bias = nullptr;
+    g.residual = nullptr;
+    if (g.c_mode == 1) g.c_mode = 2;
+  }
+  const TuneKey key(layout_of(v[0]), v[0].M, v[0].N, v[0].K);
+  {
+    std::lock_guard<std::mutex> lock(g_tuned_mutex);
+    if (g_tuned.count(key)) return TM_OK;
+  }
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+    return fail(TM_ELAUNCH, "gemm_mfma_tune: cannot create events");
+  float ms_of[kNumConfigs];
+  int rc = TM_OK, turn = 0;
+  for (int c = 0; c < kNumConfigs && rc == TM_OK; ++c) {
+    ms_of[c] = 1e30f;
+    rc = launch_config(v[turn++ % n], c, s);  // warm-up: code object load, clocks
+    for (int r = 0; r < 3 && rc == TM_OK; ++r) {
+      if (hipEventRecord(e0, s) != hipSuccess) rc = fail(TM_ELAUNCH, "gemm_mfma_tune: event record");
+      if (rc == TM_OK) rc = launch_config(v[turn++ % n], c, s);
+      if (rc == TM_OK && (hipEventRecord(e1, s) != hipSuccess || hipEventSynchronize(e1) != hipSuccess))
+        rc = fail(TM_ELAUNCH, "gemm_mfma_tune: event wait");
+      float ms = 0.f;
+      if (rc == TM_OK && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms < ms_of[c]) ms_of[c] = ms;
+    }
+  }
+  int best = 0;
+  for (int c = 1; c < kNumConfigs; ++c)
+    if (ms_of[c] < ms_of[best]) best = c;
+  // the cost model's pick stays unless it loses by more than 2 %: keeps the choice stable against timer noise
+  const int first = heuristic_config(v[0]);
+  if (ms_of[first] <= 1.02f * ms_of[best]) best = first;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != TM_OK) return rc;
+  if (getenv("TM_GEMM_TUNE_LOG")) {
+    fprintf(stderr, "tune layout %d M=%lld N=%lld K=%lld:", layout_of(v[0]), (long long)v[0].M, (long long)v[0].N, (long long)v[0].K);
+    for (int c = 0; c < kNumConfigs; ++c)
+      fprintf(stderr, " %dx%dx%dx%d=%.4f%s", kConfigs[c].bm, kConfigs[c].bn, kConfigs[c].wgm, kConfigs[c].wgn, ms_of[c], c == best ? "*" : "");
+    fprintf(stderr, "\n");
+  }
+  std::lock_guard<std::mutex> lock(g_tuned_mutex);
+  g_tuned[key] = best;
+  return TM_OK;
 }
 
 }  // namespace tmk

@@ -1,28 +1,33 @@
 // bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
-// One 256-thread block (four wavefronts in a 2x2 grid) owns a BM x BN output tile and walks the
-// reduction axis BK elements at a time through a ring of NSTAGE LDS buffers.
+// A block of WGM x WGN wavefronts (four or eight) owns a BM x BN output tile and walks the reduction
+// axis 64 elements at a time through two LDS stages.
 //
-// Main kernel (gemm_direct_kernel).  Operand tiles go from global memory STRAIGHT into LDS
+// Main kernel (gemm_pipe_kernel).  Operand tiles go from global memory STRAIGHT into LDS
 // (buffer_load ... lds, 16 bytes per lane): no staging registers, no LDS store instructions.  A
 // wave-wide load fills 1024 contiguous LDS bytes, so any layout permutation is applied on the
 // global side: each lane fetches the 16-byte chunk that belongs at its LDS position.
 //   * Operand with contiguous reduction axis (x and W in y = x W^T, dy in dx = dy W): LDS tile
-//     [row][BK], chunks XOR-swizzled by row; MFMA fragments are plain 16-byte LDS reads.
+//     [row][64], chunks XOR-swizzled by row; MFMA fragments are plain 16-byte LDS reads.
 //   * Operand with strided reduction axis (W in dx = dy W; dy and x in dW = dy^T x): LDS tile
 //     [k][rows], i.e. the global layout; MFMA fragments come from the transposing LDS read
 //     ds_read_b64_tr_b16, which hands each lane four consecutive k of one row.  No transposed copies
 //     in HBM, no register shuffles.
-// Loads run NSTAGE-1 steps ahead; one barrier per step; waits on the loads are explicit
-// (s_waitcnt vmcnt), since the compiler does not track the LDS side of these loads.
-// A reduction length that is not a multiple of BK on a contiguous-reduction operand cannot be
-// masked on this path; such shapes take the staged kernel below.
+// Loads run one step ahead; one barrier per step, placed before the LAST 16-wide slice of the step so
+// that the LDS reads and the global loads that follow it overlap that slice's MFMAs; the waits on the
+// loads are explicit (s_waitcnt vmcnt), since the compiler does not track the LDS side of these loads.
+// What bounds the kernel is the path from L2 into LDS (about 50 bytes per clock and compute unit, and
+// only whole 128-byte lines count: hence 64-element steps) together with the LDS reads, so the tile
+// shapes trade traffic per flop against how evenly the tiles fill the 256 compute units.
+// A reduction length that is not a multiple of 64 cannot be masked on this path; such shapes take the
+// staged kernel below.
 //
 // Staged kernel (gemm_staged_kernel): 128x128 tile, global -> registers -> LDS with the reduction
 // tail masked on the way; strided operands are transposed in registers.  Any K that is a multiple of 8.
 //
 // Global accesses use buffer descriptors: reads past the end of a tensor return zero and writes
-// past the end are dropped, so ragged M / N edges need no branches.
+// past the end are dropped, so ragged M / N edges need no branches.  Only the per-lane offset is
+// checked against the descriptor's size, so everything that can run past the end travels in it.
 //
 // Epilogue: the MFMA operands are passed swapped, so an accumulator tile is C^T and every lane owns
 // four CONSECUTIVE output columns of one row: 8-byte bf16 / 16-byte fp32 stores.
@@ -48,6 +53,7 @@ typedef unsigned int v4u32 __attribute__((__vector_size__(16)));  // the buffer 
 typedef __attribute__((address_space(3))) void *lds_ptr_t;
 
 constexpr int NXCD = 8;
+constexpr int GEMM_BK = 64;  // reduction elements per step: one 128-byte line per tile row
 
 __device__ __forceinline__ u32x4 buf_load16(rsrc_t r, uint32_t voff, uint32_t soff) {
   return __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
@@ -152,11 +158,12 @@ __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (
 // =================================================================================================
 
 // ---- operand with contiguous reduction axis: element (r, k) at base[r*ld + k]; LDS [R][BK] --------
-template <int R, int BK> struct DirectKC {
+template <int R, int BK, int NW = 4> struct DirectKC {
   static constexpr int ROWB = BK * 2;               // bytes per LDS row
   static constexpr int CPR = BK / 8;                // 16-byte chunks per row
   static constexpr int RPL = 64 / CPR;              // rows covered by one wave-wide load
-  static constexpr int NLOAD = R / (4 * RPL);       // loads per wave and step (R is a multiple of 64)
+  static constexpr int NLOAD = R / (NW * RPL);      // loads per wave and step
+  static_assert(R % (NW * RPL) == 0, "rows per load");
   static constexpr int BYTES = R * ROWB;
   // rows that are 8 apart in a fragment read must not share banks: XOR the chunk index with low row bits
   static __device__ __forceinline__ int swz(int row) {
@@ -166,7 +173,7 @@ template <int R, int BK> struct DirectKC {
   __device__ __forceinline__ void init(int64_t ld, int row0, int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
-      const int row = (i * 4 + wave) * RPL + lane / CPR;
+      const int row = (i * NW + wave) * RPL + lane / CPR;
       const int c = (lane % CPR) ^ swz(row);  // logical chunk that belongs at this lane's LDS position
       voff[i] = (uint32_t)(((int64_t)(row0 + row) * ld + c * 8) * 2);
     }
@@ -174,7 +181,7 @@ template <int R, int BK> struct DirectKC {
   __device__ __forceinline__ void issue(rsrc_t rs, char *tile, int k0, int64_t /*ld*/, int wave) const {
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * 4 + wave) * 1024), 16, voff[i],
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, voff[i],
                                                (uint32_t)k0 * 2u, 0, 0);
   }
   // fragment of the 32-row block starting at r32: lane's row r32 + lane%32, reduction slots 16ks + 8hh + 0..7
@@ -185,10 +192,11 @@ template <int R, int BK> struct DirectKC {
 };
 
 // ---- operand with strided reduction axis: element (r, k) at base[k*ld + r]; LDS [BK][R] ------------
-template <int R, int BK> struct DirectKS {
+template <int R, int BK, int NW = 4> struct DirectKS {
   static constexpr int ROWB = R * 2;                // bytes per LDS k-row
   static constexpr int CPR = R / 8;                 // chunks per k-row (32 or 16)
-  static constexpr int NLOAD = BK * CPR / 256;      // loads per wave and step
+  static constexpr int NLOAD = BK * CPR / (64 * NW);  // loads per wave and step
+  static_assert((BK * CPR) % (64 * NW) == 0, "chunks per load");
   static constexpr int BYTES = BK * ROWB;
   // The transposing read of a 16-lane group touches 4 k-rows x 32 contiguous bytes, a half-wave the
   // neighbouring 32 bytes as well; k-rows alias in the banks (row pitch 256/512 bytes).  The position
@@ -207,16 +215,17 @@ template <int R, int BK> struct DirectKS {
   __device__ __forceinline__ void init(int64_t ld, int row0, int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i) {
-      const int idx = (i * 4 + wave) * 64 + lane;
+      const int idx = (i * NW + wave) * 64 + lane;
       const int kk = idx / CPR, c = unplace(idx % CPR, kk);
       voff[i] = (uint32_t)(((int64_t)kk * ld + row0 + c * 8) * 2);
     }
   }
   __device__ __forceinline__ void issue(rsrc_t rs, char *tile, int k0, int64_t ld, int wave) const {
-    const uint32_t soff = (uint32_t)((int64_t)k0 * ld * 2);
+    // the step offset travels in the per-lane offset: that one is checked against the buffer size
+    const uint32_t koff = (uint32_t)((int64_t)k0 * ld * 2);
 #pragma unroll
     for (int i = 0; i < NLOAD; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * 4 + wave) * 1024), 16, voff[i], soff, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, voff[i] + koff, 0, 0, 0);
   }
   // ds_read_b64_tr_b16: within 16 lanes, lane i receives element (i%4) of the 8-byte pieces addressed
   // by lanes i/4, i/4+4, i/4+8, i/4+12.  With lane s addressing T[k0 + s/4][r0 + 4*(s%4) ..+3], lane i
@@ -236,45 +245,61 @@ template <int R, int BK> struct DirectKS {
   }
 };
 
-template <int R, int BK, bool KC> struct DirectSel { typedef DirectKC<R, BK> type; };
-template <int R, int BK> struct DirectSel<R, BK, false> { typedef DirectKS<R, BK> type; };
-
-// Compile-time construction of the scheduler's issue order (the builtin wants literal constants).
-// Masks: 0x008 MFMA, 0x020 global/buffer load, 0x100 LDS read.
-template <int MASK, int N> __device__ __forceinline__ void sched_group() {
-  if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
-}
-template <int KS, int MF, int LOADS, int DSN, int ks, int i> __device__ __forceinline__ void sched_slices() {
-  if constexpr (ks < KS) {
-    sched_group<0x008, 1>();
-    if constexpr (ks == 0) sched_group<0x020, LOADS * (i + 1) / MF - LOADS * i / MF>();
-    if constexpr (ks + 1 < KS) sched_group<0x100, DSN * (i + 1) / MF - DSN * i / MF>();
-    if constexpr (i + 1 < MF)
-      sched_slices<KS, MF, LOADS, DSN, ks, i + 1>();
-    else
-      sched_slices<KS, MF, LOADS, DSN, ks + 1, 0>();
-  }
-}
+template <int R, int BK, bool KC, int NW = 4> struct DirectSel { typedef DirectKC<R, BK, NW> type; };
+template <int R, int BK, int NW> struct DirectSel<R, BK, false, NW> { typedef DirectKS<R, BK, NW> type; };
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
-// Tiles of at most 256x128 keep their accumulators in 128 registers: two blocks fit on a compute unit
-// (two waves per SIMD), so one block's barrier and load waits are covered by the other's MFMAs.
-template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(256, (BM * BN <= 256 * 128 ? 2 : 1)) void gemm_direct_kernel(const MfmaGemmParams p) {
+// =================================================================================================
+// pipelined kernel: WGM x WGN waves, two LDS stages, the barrier sits before the LAST reduction slice
+// =================================================================================================
+// Per step: slices 0..KS-2 run MFMAs while the LDS reads of the next slice are in flight.  Before the
+// last slice every wave has read all it needs from the current stage and waits for its own loads of the
+// next stage; after the barrier the current stage may be overwritten (loads of step kt+2) and the next
+// stage may be read (its slice 0), and both overlap the MFMAs of the last slice, whose operands are
+// already in registers.  No LDS latency is exposed behind the barrier.
+// Issue order handed to the instruction scheduler, built at compile time (the builtin wants literal
+// constants).  Masks: 0x008 MFMA, 0x020 global/buffer load, 0x100 LDS read.
+template <int MASK, int N> __device__ __forceinline__ void sg() {
+  if constexpr (N > 0) __builtin_amdgcn_sched_group_barrier(MASK, N, 0);
+}
+template <int MF, int DSN, int i> __device__ __forceinline__ void sched_mid() {
+  if constexpr (i < MF) {
+    sg<0x008, 1>();
+    sg<0x100, DSN * (i + 1) / MF - DSN * i / MF>();
+    sched_mid<MF, DSN, i + 1>();
+  }
+}
+template <int MF, int DSN, int LOADS, int i> __device__ __forceinline__ void sched_last() {
+  if constexpr (i < MF) {
+    sg<0x008, 1>();
+    sg<0x020, LOADS * (i + 1) / MF - LOADS * i / MF>();
+    sg<0x100, DSN * (i + 1) / MF - DSN * i / MF>();
+    sched_last<MF, DSN, LOADS, i + 1>();
+  }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 * 128) ? 2 : 1) void gemm_pipe_kernel(
+    const MfmaGemmParams p) {
   extern __shared__ __align__(16) char lds[];
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
-  typedef typename DirectSel<BM, BK, A_KC>::type LA;
-  typedef typename DirectSel<BN, BK, B_KC>::type LB;
+  constexpr int NW = WGM * WGN;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+  typedef typename DirectSel<BM, BK, A_KC, NW>::type LA;
+  typedef typename DirectSel<BN, BK, B_KC, NW>::type LB;
   constexpr int STAGE = LA::BYTES + LB::BYTES;
   constexpr int LOADS = LA::NLOAD + LB::NLOAD;
-  static_assert((NSTAGE - 2) * LOADS <= 63, "vmcnt field");
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "fragment buffers alternate");
+  constexpr int MF = TM * TN;
+  constexpr int DSN = TM * (A_KC ? 1 : 2) + TN * (B_KC ? 1 : 2);
 
   int m0, n0;
   tile_of_block(p, BM, BN, m0, n0);
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WGN, wn = wave % WGN;
 
   LA la;
   LB lb;
@@ -291,58 +316,59 @@ __global__ __launch_bounds__(256, (BM * BN <= 256 * 128 ? 2 : 1)) void gemm_dire
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   const int nk = (p.K + BK - 1) / BK;
-  // Loads are issued unconditionally (a step past K reads zeros or unused rows) so that the number
-  // of loads in flight at each wait is a compile-time constant.
+  bf16x8 a[2][TM], b[2][TN];
+  // prologue: stage 0 in LDS, its slice 0 in registers, stage 1 in flight
+  la.issue(ra, lds, 0, p.lda, wave);
+  lb.issue(rb, lds + LA::BYTES, 0, p.ldb, wave);
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
 #pragma unroll
-  for (int s = 0; s < NSTAGE - 1; ++s) {
-    la.issue(ra, lds + s * STAGE, s * BK, p.lda, wave);
-    lb.issue(rb, lds + s * STAGE + LA::BYTES, s * BK, p.ldb, wave);
+  for (int i = 0; i < TM; ++i) a[0][i] = LA::frag(lds, wm * WM + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) b[0][j] = LB::frag(lds + LA::BYTES, wn * WN + j * 32, 0, lane);
+  {
+    const int k1 = nk > 1 ? BK : 0;  // never past K: a surplus fetch repeats the last step
+    la.issue(ra, lds + STAGE, k1, p.lda, wave);
+    lb.issue(rb, lds + STAGE + LA::BYTES, k1, p.ldb, wave);
   }
-  int cur = 0, nxt = NSTAGE - 1;  // ring positions of step kt and of step kt + NSTAGE - 1
+
   for (int kt = 0; kt < nk; ++kt) {
-    wait_vmcnt<(NSTAGE - 2) * LOADS>();  // this wave's part of step kt has landed
-    __builtin_amdgcn_s_barrier();        // ... everyone's has; and everyone is done reading step kt-1
-    const char *As = lds + cur * STAGE;
-    const char *Bs = As + LA::BYTES;
-    // Fragments are double buffered in registers: the LDS reads of reduction slice ks+1 are issued
-    // before the MFMAs of slice ks.
-    constexpr int KS = BK / 16;
-    bf16x8 a[2][TM], b[2][TN];
+    char *As = lds + (kt & 1) * STAGE;
+    char *Bs = As + LA::BYTES;
+    char *An = lds + ((kt & 1) ^ 1) * STAGE;
+    char *Bn = An + LA::BYTES;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) a[0][i] = LA::frag(As, wm * WM + i * 32, 0, lane);
+    for (int ks = 0; ks + 1 < KS; ++ks) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) b[0][j] = LB::frag(Bs, wn * WN + j * 32, 0, lane);
+      for (int i = 0; i < TM; ++i) a[(ks + 1) & 1][i] = LA::frag(As, wm * WM + i * 32, ks + 1, lane);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) a[(ks + 1) & 1][i] = LA::frag(As, wm * WM + i * 32, ks + 1, lane);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) b[(ks + 1) & 1][j] = LB::frag(Bs, wn * WN + j * 32, ks + 1, lane);
-      }
-      if (ks == 0) {
-        // The look-ahead loads write LDS, so the compiler keeps them ordered against the LDS reads:
-        // placed here they can sink between the MFMAs of slice 0 instead of delaying the first reads.
-        la.issue(ra, lds + nxt * STAGE, (kt + NSTAGE - 1) * BK, p.lda, wave);
-        lb.issue(rb, lds + nxt * STAGE + LA::BYTES, (kt + NSTAGE - 1) * BK, p.ldb, wave);
-      }
+      for (int j = 0; j < TN; ++j) b[(ks + 1) & 1][j] = LB::frag(Bs, wn * WN + j * 32, ks + 1, lane);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
+      sched_mid<MF, DSN, 0>();
     }
-    // Issue order for the scheduler (the step is one basic block): first the LDS reads of slice 0; then
-    // the MFMAs of slice ks, with this step's global->LDS loads (slice 0 only) and the LDS reads of
-    // slice ks+1 spread between them.  With one wave per SIMD nothing else can cover these latencies.
-    {
-      constexpr int MF = TM * TN;                                     // MFMAs per slice
-      constexpr int DSN = TM * (A_KC ? 1 : 2) + TN * (B_KC ? 1 : 2);  // LDS read instructions per slice
-      sched_group<0x100, DSN>();
-      sched_slices<KS, MF, LOADS, DSN, 0, 0>();
-    }
-    cur = cur + 1 == NSTAGE ? 0 : cur + 1;
-    nxt = nxt + 1 == NSTAGE ? 0 : nxt + 1;
+    __builtin_amdgcn_sched_barrier(0);
+    // all reads of the current stage are complete, and this wave's loads of the next stage have landed
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    // the current stage is free: fetch step kt+2 into it (at the end the last step again, never consumed)
+    const int kn = (kt + 2 < nk ? kt + 2 : nk - 1) * BK;
+    la.issue(ra, As, kn, p.lda, wave);
+    lb.issue(rb, Bs, kn, p.ldb, wave);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[0][i] = LA::frag(An, wm * WM + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[0][j] = LB::frag(Bn, wn * WN + j * 32, 0, lane);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[(KS - 1) & 1][j], a[(KS - 1) & 1][i], acc[i][j], 0, 0, 0);
+    sched_last<MF, DSN, LOADS, 0>();
   }
   wait_vmcnt<0>();  // drain the look-ahead loads before the block may exit
   epilogue<TM, TN, EPI>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
@@ -511,78 +537,69 @@ template <bool A_KC, bool B_KC, int EPI> static MfmaGemmParams make_params(const
   return p;
 }
 
-static std::string kernel_tag(const char *base, int bm, int bn, int bk, int ns, bool akc, bool bkc, int epi) {
-  return std::string(base) + "<" + std::to_string(bm) + "," + std::to_string(bn) + "," + std::to_string(bk) + "," +
-         std::to_string(ns) + "," + (akc ? "true" : "false") + "," + (bkc ? "true" : "false") + "," +
-         std::to_string(epi) + ">";
+static std::string kernel_tag(const char *base, int bm, int bn, int wgm, int wgn, bool akc, bool bkc, int epi) {
+  return std::string(base) + "<" + std::to_string(bm) + "x" + std::to_string(bn) + ",waves " + std::to_string(wgm) + "x" +
+         std::to_string(wgn) + "," + (akc ? "kc" : "ks") + "," + (bkc ? "kc" : "ks") + ",epi" + std::to_string(epi) + ">";
 }
 
-template <int BM, int BN, int BK, int NSTAGE, bool A_KC, bool B_KC, int EPI>
-static int launch_direct(const GemmArgs &g, hipStream_t s) {
+template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+static int launch_pipe(const GemmArgs &g, hipStream_t s) {
+  constexpr int BK = GEMM_BK;
   const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, BM, BN);
-  constexpr int lds_bytes = NSTAGE * (BM + BN) * BK * 2;
+  constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
   static_assert(lds_bytes <= 160 * 1024, "LDS");
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_direct_kernel<BM, BN, BK, NSTAGE, A_KC, B_KC, EPI>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_pipe_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
       return fail(TM_ELAUNCH, "gemm_mfma: cannot reserve %d bytes of LDS", lds_bytes);
     attr_set = true;
   }
   const int64_t nblk = (int64_t)p.tiles_m * p.tiles_n;
   if (nblk > 0x7fffffff) return fail(TM_ESIZE, "gemm_mfma: too many tiles");
-  static const std::string name = kernel_tag("gemm_direct_kernel", BM, BN, BK, NSTAGE, A_KC, B_KC, EPI);
+  static const std::string name = kernel_tag("gemm_pipe_kernel", BM, BN, WGM, WGN, A_KC, B_KC, EPI);
   g_last_kernel = name.c_str();
-  gemm_direct_kernel<BM, BN, BK, NSTAGE, A_KC, B_KC, EPI><<<dim3((unsigned)nblk), 256, lds_bytes, s>>>(p);
-  return check_launch("gemm_direct");
+  gemm_pipe_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI><<<dim3((unsigned)nblk), 64 * WGM * WGN, lds_bytes, s>>>(p);
+  return check_launch("gemm_pipe");
 }
 
 template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs &g, hipStream_t s) {
   const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, 128, 128);
-  static const std::string name = kernel_tag("gemm_staged_kernel", 128, 128, 64, 2, A_KC, B_KC, EPI);
+  static const std::string name = kernel_tag("gemm_staged_kernel", 128, 128, 2, 2, A_KC, B_KC, EPI);
   g_last_kernel = name.c_str();
   gemm_staged_kernel<A_KC, B_KC, EPI><<<dim3((unsigned)(p.tiles_m * p.tiles_n)), 256, 0, s>>>(p);
   return check_launch("gemm_staged");
 }
 
-#ifndef TM_GEMM_BK
-#define TM_GEMM_BK 64
-#endif
-#ifndef TM_GEMM_NSTAGE
-#define TM_GEMM_NSTAGE 2
-#endif
+// The tile configurations (BM, BN, wave grid).  gemm_mfma.hip holds the same list with each entry's
+// occupancy and measured relative speed, in the same order.
+#define TM_GEMM_CONFIGS(X) \
+  X(128, 192, 2, 2) X(128, 128, 2, 2) X(192, 128, 2, 2) X(256, 192, 4, 2) X(192, 256, 2, 4) X(256, 256, 2, 4) \
+  X(256, 256, 4, 2) X(256, 128, 4, 2)
 
 // The variants the host side launches are instantiated explicitly (an implicit instantiation from inside
 // the launcher templates leaves the host-side kernel handle undefined with this compiler).
-#define TM_GEMM_INSTANTIATE(AKC, BKC, EPI)                                                                       \
-  template __global__ void gemm_direct_kernel<256, 256, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
-  template __global__ void gemm_direct_kernel<256, 192, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
-  template __global__ void gemm_direct_kernel<192, 256, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
-  template __global__ void gemm_direct_kernel<192, 192, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
-  template __global__ void gemm_direct_kernel<256, 128, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
-  template __global__ void gemm_direct_kernel<128, 256, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
-  template __global__ void gemm_direct_kernel<192, 128, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
-  template __global__ void gemm_direct_kernel<128, 192, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams); \
-  template __global__ void gemm_direct_kernel<128, 128, TM_GEMM_BK, TM_GEMM_NSTAGE, AKC, BKC, EPI>(const MfmaGemmParams);
+#define TM_GEMM_INSTANTIATE_ONE(BM_, BN_, WGM_, WGN_, AKC, BKC, EPI) \
+  template __global__ void gemm_pipe_kernel<BM_, BN_, GEMM_BK, WGM_, WGN_, AKC, BKC, EPI>(const MfmaGemmParams);
+#define TM_GEMM_INSTANTIATE(AKC, BKC, EPI)                  \
+  TM_GEMM_INSTANTIATE_ONE(128, 192, 2, 2, AKC, BKC, EPI)    \
+  TM_GEMM_INSTANTIATE_ONE(128, 128, 2, 2, AKC, BKC, EPI)    \
+  TM_GEMM_INSTANTIATE_ONE(192, 128, 2, 2, AKC, BKC, EPI)    \
+  TM_GEMM_INSTANTIATE_ONE(256, 192, 4, 2, AKC, BKC, EPI)    \
+  TM_GEMM_INSTANTIATE_ONE(192, 256, 2, 4, AKC, BKC, EPI)    \
+  TM_GEMM_INSTANTIATE_ONE(256, 256, 2, 4, AKC, BKC, EPI)    \
+  TM_GEMM_INSTANTIATE_ONE(256, 256, 4, 2, AKC, BKC, EPI)    \
+  TM_GEMM_INSTANTIATE_ONE(256, 128, 4, 2, AKC, BKC, EPI)
 
-template <bool A_KC, bool B_KC, int EPI> static int launch_layout(const GemmArgs &g, hipStream_t s) {
-  constexpr int BK = TM_GEMM_BK, NS = TM_GEMM_NSTAGE;
-  const bool k_tail = (A_KC || B_KC) && (g.K % BK != 0);  // a contiguous-reduction operand cannot be masked
-  if (k_tail) return launch_staged<A_KC, B_KC, EPI>(g, s);
-  int bm = 128, bn = 128;
-  gemm_pick_tile(g.M, g.N, bm, bn);
-#define TM_TRY_TILE(BM_, BN_) \
-  if (bm == BM_ && bn == BN_) return launch_direct<BM_, BN_, BK, NS, A_KC, B_KC, EPI>(g, s);
-  TM_TRY_TILE(256, 256)
-  TM_TRY_TILE(256, 192)
-  TM_TRY_TILE(192, 256)
-  TM_TRY_TILE(192, 192)
-  TM_TRY_TILE(256, 128)
-  TM_TRY_TILE(128, 256)
-  TM_TRY_TILE(192, 128)
-  TM_TRY_TILE(128, 192)
-#undef TM_TRY_TILE
-  return launch_direct<128, 128, BK, NS, A_KC, B_KC, EPI>(g, s);
+// config: index into the list above, as chosen by gemm_mfma_config()
+template <bool A_KC, bool B_KC, int EPI> static int launch_layout(const GemmArgs &g, int config, hipStream_t s) {
+  if (g.K % GEMM_BK != 0) return launch_staged<A_KC, B_KC, EPI>(g, s);  // the pipelined kernel takes whole steps only
+  int idx = 0;
+#define X(BM_, BN_, WGM_, WGN_) \
+  if (config == idx++) return launch_pipe<BM_, BN_, WGM_, WGN_, A_KC, B_KC, EPI>(g, s);
+  TM_GEMM_CONFIGS(X)
+#undef X
+  return fail(TM_EINVAL, "gemm_mfma: no tile configuration %d", config);
 }
 
 }  // namespace tmk

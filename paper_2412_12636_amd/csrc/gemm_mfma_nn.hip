@@ -3,5 +3,5 @@
 
 namespace tmk {
 TM_GEMM_INSTANTIATE(true, false, 0)
-int gemm_mfma_nn(const GemmArgs &g, hipStream_t s) { return launch_layout<true, false, 0>(g, s); }
+int gemm_mfma_nn(const GemmArgs &g, int config, hipStream_t s) { return launch_layout<true, false, 0>(g, config, s); }
 }  // namespace tmk

@@ -3,5 +3,5 @@
 
 namespace tmk {
 TM_GEMM_INSTANTIATE(true, true, 0)
-int gemm_mfma_nt(const GemmArgs &g, hipStream_t s) { return launch_layout<true, true, 0>(g, s); }
+int gemm_mfma_nt(const GemmArgs &g, int config, hipStream_t s) { return launch_layout<true, true, 0>(g, config, s); }
 }  // namespace tmk

@@ -4,7 +4,7 @@
 namespace tmk {
 TM_GEMM_INSTANTIATE(false, false, 1)
 TM_GEMM_INSTANTIATE(false, false, 2)
-int gemm_mfma_tn(const GemmArgs &g, hipStream_t s) {
-  return g.c_mode == 2 ? launch_layout<false, false, 2>(g, s) : launch_layout<false, false, 1>(g, s);
+int gemm_mfma_tn(const GemmArgs &g, int config, hipStream_t s) {
+  return g.c_mode == 2 ? launch_layout<false, false, 2>(g, config, s) : launch_layout<false, false, 1>(g, config, s);
 }
 }  // namespace tmk

@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "common.h"
+#include "gemm.h"
 #include "../../include/tm_ops.h"
 
 namespace tmk {
@@ -395,6 +396,48 @@ Dims dims_of(const tm_stage_config_t &c) {
       st->prof.recs.push_back({g_last_kernel, (double)(FLOPS), (double)(BYTES), _e0, _e1}); \
     }                                                                           \
   } while (0)
+
+extern "C" int tm_stage_tune(tm_stage_t *st, void *stream) {
+  if (!st) return fail(TM_EINVAL, "stage_tune: NULL handle");
+  const tm_stage_config_t &c = st->cfg;
+  if (c.dtype != TM_DTYPE_BF16) return TM_OK;  // the fp32 path has one kernel per product
+  const Dims d = dims_of(c);
+  hipStream_t s = (hipStream_t)stream;
+  char *ws = (char *)st->buf.workspace;
+  const char *par = (const char *)st->buf.params;
+  const LayerOffsets &o = st->lo;
+  st->have_fwd = false;  // the stash is about to be overwritten
+  const int64_t wide = std::max(std::max(d.h, d.f1), d.nqkv);
+  const int64_t in_a = 0, in_b = (d.T * wide * 2 + 255) / 256 * 256, out = 2 * in_b;
+  struct Lin {
+    int64_t N, K, w;
+  } lins[4] = {{d.nqkv, d.h, o.w_qkv}, {d.h, d.A, o.w_out}, {d.f1, d.h, o.w_fc1}, {d.h, d.f, o.w_fc2}};
+  // Weights: every layer's own (cold in the real sequence, so cold here).  Activations and results: the
+  // same workspace region every time (just written by the previous step in the real sequence).
+  std::vector<GemmArgs> v((size_t)c.n_layers);
+  for (const Lin &l : lins) {
+    auto weights = [&](int layer) -> const void * { return par + ((int64_t)layer * o.total + l.w) * 2; };
+    if (out + d.T * std::max(l.N, l.K) * 2 <= st->plan.total) {
+      // y = x W^T
+      for (int i = 0; i < c.n_layers; ++i)
+        v[i] = GemmArgs{d.T, l.N, l.K, ws + in_a, l.K, 1, weights(i), l.K, 1, ws + out, l.N, nullptr, nullptr, 0};
+      TM_TRY(gemm_mfma_tune(v.data(), c.n_layers, s));
+      // dx = dy W
+      for (int i = 0; i < c.n_layers; ++i)
+        v[i] = GemmArgs{d.T, l.K, l.N, ws + in_a, l.N, 1, weights(i), 1, l.K, ws + out, l.K, nullptr, nullptr, 0};
+      TM_TRY(gemm_mfma_tune(v.data(), c.n_layers, s));
+    }
+    // dW = dy^T x; the results rotate through as many separate regions as the workspace holds
+    const int64_t dw_bytes = (l.N * l.K * 4 + 255) / 256 * 256;
+    const int n_out = (int)std::min<int64_t>((st->plan.total - out) / dw_bytes, c.n_layers);
+    if (n_out > 0) {
+      for (int i = 0; i < n_out; ++i)
+        v[i] = GemmArgs{l.N, l.K, d.T, ws + in_a, 1, l.N, ws + in_b, 1, l.K, ws + out + i * dw_bytes, l.K, nullptr, nullptr, 2};
+      TM_TRY(gemm_mfma_tune(v.data(), n_out, s));
+    }
+  }
+  return TM_OK;
+}
 
 extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void *stream) {
   if (!st || !x_in || !y_out) return fail(TM_EINVAL, "stage_fwd: NULL argument");

@@ -5,7 +5,7 @@ import pytest
 
 import synth_inputs as si
 from oracle import stage_oracle as so
-from tests.gpu_util import TOL_ADAM, TOL_BF16, TOL_FP32, rel_err, require_gpu, to_dev, to_host
+from tests.gpu_util import TOL_ADAM, TOL_BF16, TOL_FP32, rel_err, require_gpu, stream_ptr, to_dev, to_host
 from tests.stage_runner import GpuStage, flatten_grads, oracle_iteration
 
 pytestmark = pytest.mark.gpu
@@ -129,6 +129,30 @@ def test_overwrite_mode_equals_accumulation_into_zeros(env):
     assert rel_err(to_host(b.grads), 2.0 * to_host(a.grads)) <= 1e-6
     a.close()
     b.close()
+
+
+def test_tuning_changes_speed_only(env):
+    """Timing the tile configurations keeps every result bit for bit (each configuration accumulates an
+    output element in the same order), overwrites the workspace, and asks for a new forward pass."""
+    torch, tm = env
+    cfg = SMALL_GPT.replace(hidden=512, ffn=1024, n_q_heads=4, n_kv_heads=4, seq=192)   # every K a multiple of 64
+    flat = si.make_flat_params(cfg)
+    x, dy = to_dev(torch, si.make_x(cfg), cfg.dtype), to_dev(torch, si.make_dy(cfg), cfg.dtype)
+    st = GpuStage(torch, tm, cfg, flat)
+    st.fwd(x)
+    st.bwd(dy)
+    torch.cuda.synchronize()
+    y0, dx0, g0 = st.y.clone(), st.dx.clone(), st.grads.clone()
+    tm.tm_stage_tune(st.handle, stream_ptr(torch))
+    with pytest.raises(tm.TmError) as ei:
+        st.bwd(dy)                               # the stash is gone
+    assert ei.value.code == tm.TM_ESTATE
+    st.grads.zero_()
+    st.fwd(x)
+    st.bwd(dy)
+    torch.cuda.synchronize()
+    assert torch.equal(st.y, y0) and torch.equal(st.dx, dx0) and torch.equal(st.grads, g0)
+    st.close()
 
 
 def test_two_runs_are_bit_identical(env):
