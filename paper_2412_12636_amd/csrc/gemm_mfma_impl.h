@@ -92,13 +92,44 @@ __device__ __forceinline__ void tile_of_block(const MfmaGemmParams &p, int BM, i
 }
 
 // ---- epilogue shared by both kernels -------------------------------------------------------------
-// acc[i][j] is the transposed 32x32 tile (rows = output columns): register 4q+e of lane l holds
-// C[row = .. + l%32][col = .. + 8q + 4*(l/32) + e].   EPI 0: bf16 C = acc (+bias) (+residual);
-// EPI 1: fp32 C += acc;  EPI 2: fp32 C = acc.
+// EPI 0: bf16 C = acc (+bias) (+residual); acc[i][j] is the transposed 32x32 tile (rows = output columns):
+// register 4q+e of lane l holds C[row = .. + l%32][col = .. + 8q + 4*(l/32) + e].
+// EPI 1: fp32 C += acc;  EPI 2: fp32 C = acc; acc[i][j] is the tile itself: register v of lane l holds
+// C[row = .. + 8*(v/4) + 4*(l/32) + v%4][col = .. + l%32].
+// bf16 results: operands swapped, the accumulator tile is C^T (lane = row, 4 consecutive columns per
+// register quad: 8-byte stores).  fp32 results: natural order, the tile is C (lane%32 = column): a store
+// instruction writes two whole 128-byte lines.
+template <int EPI> __device__ __forceinline__ f32x16 mfma_for(bf16x8 a, bf16x8 b, f32x16 c) {
+  if constexpr (EPI == 0) return __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, c, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
 template <int TM, int TN, int EPI>
 __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (&acc)[TM][TN], int row_base,
                                          int col_base, int l32, int hh) {
-  const uint32_t c_elem = EPI == 0 ? 2u : 4u;
+  if constexpr (EPI != 0) {
+    // fp32 results (weight gradients): whole lines, written once and next read by the optimizer: streamed
+    // past the caches, which keeps the operands of the following products resident
+    constexpr int kStoreNonTemporal = 2;  // cache-policy operand of the buffer store: the nt bit
+    const rsrc_t rc = make_rsrc(p.C, p.c_bytes);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = col_base + j * 32 + l32;
+        const bool col_ok = col < p.N;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = row_base + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+          const uint32_t off = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
+          float o = acc[i][j][v];
+          if (EPI == 1) o += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 0));
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, o), rc, off, 0, kStoreNonTemporal);
+        }
+      }
+    return;
+  }
+  const uint32_t c_elem = 2u;
   const rsrc_t rc = make_rsrc(p.C, p.c_bytes);
   const rsrc_t rres = make_rsrc(p.residual ? (const void *)p.residual : p.C, p.c_bytes);
   const rsrc_t rbias = make_rsrc(p.bias ? (const void *)p.bias : p.C, (uint32_t)p.N * 2u);
@@ -121,7 +152,7 @@ __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (
       for (int i = 0; i < TM; ++i) {
         const int row = row_base + i * 32 + l32;
         const uint32_t off = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * c_elem) : 0xfffffff0u;
-        if (EPI == 0) {
+        {
           float r[4];
 #pragma unroll
           for (int e = 0; e < 4; ++e) r[e] = acc[i][j][4 * q + e] + bv[e];
@@ -136,17 +167,6 @@ __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = (bf16)r[e];
           __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, o), rc, off, 0, 0);
-        } else if (EPI == 1) {
-          const f32x4 old = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(rc, off, 0, 0));
-          f32x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = old[e] + acc[i][j][4 * q + e];
-          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u32, o), rc, off, 0, 0);
-        } else {
-          f32x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = acc[i][j][4 * q + e];
-          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u32, o), rc, off, 0, 0);
         }
       }
     }
@@ -347,7 +367,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[ks & 1][j], a[ks & 1][i], acc[i][j], 0, 0, 0);
+          acc[i][j] = mfma_for<EPI>(a[ks & 1][i], b[ks & 1][j], acc[i][j]);
       sched_mid<MF, DSN, 0>();
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -367,7 +387,7 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int j = 0; j < TN; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[(KS - 1) & 1][j], a[(KS - 1) & 1][i], acc[i][j], 0, 0, 0);
+        acc[i][j] = mfma_for<EPI>(a[(KS - 1) & 1][i], b[(KS - 1) & 1][j], acc[i][j]);
     sched_last<MF, DSN, LOADS, 0>();
   }
   wait_vmcnt<0>();  // drain the look-ahead loads before the block may exit
@@ -501,7 +521,7 @@ __global__ __launch_bounds__(256) void gemm_staged_kernel(const MfmaGemmParams p
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma_for<EPI>(a[i], b[j], acc[i][j]);
     }
     if (kt + 1 < nk) {
       char *nx = lds + (cur ^ 1) * STAGE;
