@@ -230,6 +230,9 @@ struct tm_stage {
   bool have_fwd;
   bool grad_overwrite = false;
   std::vector<TensorInfo> tensors;
+  // backward pass: the weight-gradient products run on a second stream beside the chain of input gradients
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork[4] = {nullptr, nullptr, nullptr, nullptr}, ev_join = nullptr;
 };
 
 static std::deque<std::string> &name_pool() {  // deque: growing it never moves the strings
@@ -308,6 +311,10 @@ extern "C" int tm_stage_init(const tm_stage_config_t *cfg, const tm_stage_buffer
 extern "C" void tm_stage_destroy(tm_stage_t *st) {
   if (!st) return;
   st->prof.release();
+  for (hipEvent_t e : st->ev_fork)
+    if (e) (void)hipEventDestroy(e);
+  if (st->ev_join) (void)hipEventDestroy(st->ev_join);
+  if (st->side) (void)hipStreamDestroy(st->side);
   delete st;
 }
 
@@ -518,8 +525,36 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
   const double attn_flops = 2.0 * c.micro_batch * c.n_q_heads * (double)c.seq * c.seq * c.head_dim;
   auto mm = [&](int64_t n, int64_t kk) { return 2.0 * d.T * n * kk; };
 
+  // Two streams (not while profiling, which times the steps one by one): a weight gradient depends only
+  // on tensors the main chain has already produced, so it is forked onto the side stream, and the main
+  // stream waits for the side stream before it reuses the scratch buffers (start of the next layer) and
+  // before the call returns in stream order.
+  bool two = !st->prof.on && getenv("TM_BWD_ONE_STREAM") == nullptr;
+  if (two && !st->side) {
+    bool ok = hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking) == hipSuccess;
+    for (hipEvent_t &e : st->ev_fork) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&st->ev_join, hipEventDisableTiming) == hipSuccess;
+    if (!ok) return fail(TM_ELAUNCH, "stage_bwd: cannot create the side stream");
+  }
+  hipStream_t sw = two ? st->side : s;  // the stream of the weight-gradient products
+  int n_fork = 0;
+  auto fork = [&]() -> int {            // what the main stream has enqueued so far precedes later side work
+    if (!two) return TM_OK;
+    hipEvent_t e = st->ev_fork[n_fork++ & 3];
+    if (hipEventRecord(e, s) != hipSuccess || hipStreamWaitEvent(st->side, e, 0) != hipSuccess)
+      return fail(TM_ELAUNCH, "stage_bwd: fork failed");
+    return TM_OK;
+  };
+  auto join = [&]() -> int {            // what the side stream has enqueued so far precedes later main work
+    if (!two) return TM_OK;
+    if (hipEventRecord(st->ev_join, st->side) != hipSuccess || hipStreamWaitEvent(s, st->ev_join, 0) != hipSuccess)
+      return fail(TM_ELAUNCH, "stage_bwd: join failed");
+    return TM_OK;
+  };
+
   const void *dy = dy_in;
   for (int l = c.n_layers - 1; l >= 0; --l) {
+    TM_TRY(join());  // the layer above is done with the scratch buffers
     const LayerStash &k = pl.layer[l];
     const LayerOffsets &o = st->lo;
     const int64_t pb = (int64_t)l * o.total;
@@ -530,7 +565,8 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
     // y = x1 + g W2^T + b2
     void *dg = (c.act == TM_ACT_SWIGLU) ? (void *)(ws + pl.dmid) : (void *)(ws + pl.dwide);
     TM_STEP(mm(d.h, d.f), 0, tm_op_linear_dgrad(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, s));
-    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), acc, s));
+    TM_TRY(fork());
+    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), acc, sw));
     if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, acc, s));
     // activation
     void *du = ws + pl.dwide;
@@ -538,7 +574,8 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
     // u = c W1^T + b1
     void *dc = ws + pl.dnorm;
     TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_dgrad(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, s));
-    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), acc, s));
+    TM_TRY(fork());
+    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), acc, sw));
     if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, acc, s));
     // c = Norm(x1): dx1 = dy + norm gradient
     void *dx1 = ws + pl.dx1;
@@ -548,7 +585,8 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
                            G(o.norm2_offset), red, acc, s));
     // x1 = x + ctx Wout^T + bout
     TM_STEP(mm(d.h, d.A), 0, tm_op_linear_dgrad(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, s));
-    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), acc, s));
+    TM_TRY(fork());
+    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), acc, sw));
     if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, acc, s));
     // attention, rotary
     TM_STEP(2 * attn_flops, 0,
@@ -561,7 +599,8 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
     // qkv = a Wqkv^T + b
     void *da = ws + pl.dnorm;
     TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_dgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, s));
-    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), acc, s));
+    TM_TRY(fork());
+    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), acc, sw));
     if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, acc, s));
     // a = Norm(x): dx = dx1 + norm gradient
     TM_STEP(0, 4 * es * Th,
@@ -570,7 +609,7 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
                            G(o.norm1_offset), red, acc, s));
     dy = dx;
   }
-  return TM_OK;
+  return join();
 }
 
 extern "C" int tm_adam_step(tm_stage_t *st, const tm_adam_hparams_t *hp, int64_t step, void *stream) {
