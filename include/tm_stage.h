@@ -181,6 +181,22 @@ int tm_stage_grad_mode(tm_stage_t *st, int overwrite);
 int tm_adam_step(tm_stage_t *st, const tm_adam_hparams_t *hp, int64_t step, void *stream);
 
 /*
+ * Backward pass plus optimizer step in one call, for the LAST micro-batch of an
+ * iteration: the same results, bit for bit, as tm_stage_bwd followed by
+ * tm_adam_step, but every layer's update is enqueued as soon as that layer's
+ * gradients are complete and runs beside the backward pass of the layers below
+ * it (the update is bound by HBM bandwidth, the backward pass by the matrix
+ * cores, so the two share the chip well).  Valid only when nothing global is
+ * derived from this pass's gradients before the update: hp->grad_scale must
+ * not depend on them (no norm-based clipping).  Uses internal streams that are
+ * ordered after everything enqueued on `stream` so far, and `stream` waits for
+ * them before the call's work counts as done.  (Shadow iteration, section 4.2:
+ * the last steps of the iteration the sandbox replays.)
+ */
+int tm_stage_bwd_adam(tm_stage_t *st, const void *dy, void *dx, const tm_adam_hparams_t *hp,
+                      int64_t step, void *stream);
+
+/*
  * The same update on bare flat device arrays of n elements (p, m, v updated in
  * place; g read, and cleared if hp->zero_grads; p_bf16 may be NULL).  This is
  * what a distributed-optimizer rank would call on its slice.  Pointers must be

@@ -60,6 +60,7 @@ EXPORTS = {
     "tm_stage_fwd": (C.c_int, [C.c_void_p] * 4),
     "tm_stage_bwd": (C.c_int, [C.c_void_p] * 4),
     "tm_adam_step": (C.c_int, [C.c_void_p, C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
+    "tm_stage_bwd_adam": (C.c_int, [C.c_void_p] * 3 + [C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
     "tm_adam_step_flat": (C.c_int, [C.c_int64] + [C.c_void_p] * 5 + [C.POINTER(tm_adam_hparams_t), C.c_int64,
                                                                        C.c_void_p]),
     "tm_stage_grad_mode": (C.c_int, [C.c_void_p, C.c_int]),
@@ -167,6 +168,10 @@ def tm_stage_fwd(handle: int, x_in, y_out, stream: int = 0) -> None:
 
 def tm_stage_bwd(handle: int, dy_in, dx_out, stream: int = 0) -> None:
     _check(lib().tm_stage_bwd(handle, _ptr(dy_in), _ptr(dx_out), stream))
+
+
+def tm_stage_bwd_adam(handle: int, dy_in, dx_out, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:
+    _check(lib().tm_stage_bwd_adam(handle, _ptr(dy_in), _ptr(dx_out), C.byref(hp), step, stream))
 
 
 def tm_adam_step(handle: int, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:

@@ -233,6 +233,9 @@ struct tm_stage {
   // backward pass: the weight-gradient products run on a second stream beside the chain of input gradients
   hipStream_t side = nullptr;
   hipEvent_t ev_fork[4] = {nullptr, nullptr, nullptr, nullptr}, ev_join = nullptr;
+  // ... and, in tm_stage_bwd_adam, each layer's optimizer update on a third
+  hipStream_t opt = nullptr;
+  hipEvent_t ev_opt[3] = {nullptr, nullptr, nullptr};
 };
 
 static std::deque<std::string> &name_pool() {  // deque: growing it never moves the strings
@@ -315,6 +318,9 @@ extern "C" void tm_stage_destroy(tm_stage_t *st) {
     if (e) (void)hipEventDestroy(e);
   if (st->ev_join) (void)hipEventDestroy(st->ev_join);
   if (st->side) (void)hipStreamDestroy(st->side);
+  for (hipEvent_t e : st->ev_opt)
+    if (e) (void)hipEventDestroy(e);
+  if (st->opt) (void)hipStreamDestroy(st->opt);
   delete st;
 }
 
@@ -506,7 +512,17 @@ extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void 
   return TM_OK;
 }
 
-extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stream) {
+static int adam_slice(tm_stage *st, int64_t first, int64_t count, const tm_adam_hparams_t *hp, int64_t step,
+                      hipStream_t s) {
+  const bool lowp = st->cfg.dtype == TM_DTYPE_BF16;
+  float *p = lowp ? st->buf.master : (float *)st->buf.params;
+  return tm_adam_step_flat(count, p + first, st->buf.grads + first, st->buf.exp_avg + first,
+                           st->buf.exp_avg_sq + first, lowp ? (char *)st->buf.params + first * 2 : nullptr, hp, step, s);
+}
+
+// hp != NULL: every layer's parameters are updated as soon as its gradients are complete
+static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stream, const tm_adam_hparams_t *hp,
+                     int64_t step) {
   if (!st || !dy_in || !dx_out) return fail(TM_EINVAL, "stage_bwd: NULL argument");
   if ((((uintptr_t)dy_in) | ((uintptr_t)dx_out)) & 255) return fail(TM_EALIGN, "stage_bwd: tensors must be 256-byte aligned");
   if (!st->have_fwd) return fail(TM_ESTATE, "stage_bwd: no forward pass to differentiate");
@@ -535,6 +551,11 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
     for (hipEvent_t &e : st->ev_fork) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&st->ev_join, hipEventDisableTiming) == hipSuccess;
     if (!ok) return fail(TM_ELAUNCH, "stage_bwd: cannot create the side stream");
+  }
+  if (two && hp && !st->opt) {
+    bool ok = hipStreamCreateWithFlags(&st->opt, hipStreamNonBlocking) == hipSuccess;
+    for (hipEvent_t &e : st->ev_opt) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
+    if (!ok) return fail(TM_ELAUNCH, "stage_bwd: cannot create the optimizer stream");
   }
   hipStream_t sw = two ? st->side : s;  // the stream of the weight-gradient products
   int n_fork = 0;
@@ -608,8 +629,37 @@ extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, voi
                            (const float *)(ws + k.rstd1), P(o.norm1_gain), dx1, dx, G(o.norm1_gain),
                            G(o.norm1_offset), red, acc, s));
     dy = dx;
+    if (hp) {
+      // this layer's gradients: the products on the side stream and the norm / bias gradients on the main one
+      hipStream_t so = two ? st->opt : s;
+      if (two) {
+        if (hipEventRecord(st->ev_opt[0], s) != hipSuccess || hipStreamWaitEvent(st->opt, st->ev_opt[0], 0) != hipSuccess ||
+            hipEventRecord(st->ev_opt[1], st->side) != hipSuccess ||
+            hipStreamWaitEvent(st->opt, st->ev_opt[1], 0) != hipSuccess)
+          return fail(TM_ELAUNCH, "stage_bwd: optimizer fork failed");
+      }
+      const double per_param = 28.0 + (d.es == 2 ? 2.0 : 0.0) + (hp->zero_grads ? 4.0 : 0.0);
+      hipStream_t s_keep = s;
+      s = so;  // TM_STEP brackets the stream named s
+      TM_STEP(0, per_param * (double)o.total, adam_slice(st, pb, o.total, hp, step, so));
+      s = s_keep;
+    }
+  }
+  if (hp && two) {
+    if (hipEventRecord(st->ev_opt[2], st->opt) != hipSuccess || hipStreamWaitEvent(s, st->ev_opt[2], 0) != hipSuccess)
+      return fail(TM_ELAUNCH, "stage_bwd: optimizer join failed");
   }
   return join();
+}
+
+extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stream) {
+  return stage_bwd(st, dy_in, dx_out, stream, nullptr, 0);
+}
+
+extern "C" int tm_stage_bwd_adam(tm_stage_t *st, const void *dy_in, void *dx_out, const tm_adam_hparams_t *hp,
+                                 int64_t step, void *stream) {
+  if (!hp) return fail(TM_EINVAL, "stage_bwd_adam: NULL hyper-parameters");
+  return stage_bwd(st, dy_in, dx_out, stream, hp, step);
 }
 
 extern "C" int tm_adam_step(tm_stage_t *st, const tm_adam_hparams_t *hp, int64_t step, void *stream) {

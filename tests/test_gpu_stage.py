@@ -155,6 +155,30 @@ def test_tuning_changes_speed_only(env):
     st.close()
 
 
+def test_backward_with_overlapped_optimizer_equals_the_two_calls(env):
+    """tm_stage_bwd_adam = tm_stage_bwd then tm_adam_step, bit for bit: master weights, both moments, the
+    bf16 copy, the input gradient; two iterations, so that the second forward pass sees updated weights."""
+    torch, tm = env
+    cfg = SMALL_GPT.replace(n_layers=3)
+    flat = si.make_flat_params(cfg)
+    x, dy = to_dev(torch, si.make_x(cfg), cfg.dtype), to_dev(torch, si.make_dy(cfg), cfg.dtype)
+    a, b = GpuStage(torch, tm, cfg, flat), GpuStage(torch, tm, cfg, flat)
+    hp = tm.make_hparams(**si.ADAM_DEFAULTS)
+    for st in (a, b):
+        tm.tm_stage_grad_mode(st.handle, True)
+    for step in (1, 2):
+        a.fwd(x)
+        a.bwd(dy)
+        a.adam(step=step)
+        b.fwd(x)
+        tm.tm_stage_bwd_adam(b.handle, dy, b.dx, hp, step, stream_ptr(torch))
+        torch.cuda.synchronize()
+        for name in ("y", "dx", "grads", "master", "m", "v", "params"):
+            assert torch.equal(getattr(a, name), getattr(b, name)), (step, name)
+    a.close()
+    b.close()
+
+
 def test_two_runs_are_bit_identical(env):
     torch, tm = env
     cfg = SMALL_LLAMA
