@@ -28,7 +28,7 @@ def _hipcc() -> str:
 
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    extra = os.environ.get("TM_EXTRA_HIPCC_FLAGS", "").split()   # tuning aid, e.g. -DTM_GEMM_BK=32
+    extra = os.environ.get("TM_EXTRA_HIPCC_FLAGS", "").split()   # tuning aid, e.g. -Rpass-analysis=kernel-resource-usage
     cmd = [_hipcc(), *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
