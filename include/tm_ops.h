@@ -77,9 +77,14 @@ int tm_op_rotary(int dtype, int64_t seq, int64_t batch, int64_t n_heads, int64_t
 int tm_op_attn_fwd(int dtype, int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d,
                    const void *qkv, void *ctx, float *lse, void *stream);
 
-/* dqkv (same layout as qkv) from dctx; dvec is fp32 scratch of batch*nq*seq elements. */
+/* Bytes of scratch tm_op_attn_bwd needs: the row statistics D = rowsum(dctx * ctx) [batch, nq, seq] fp32
+ * and, when query heads share kv heads, one fp32 partial of dK and dV per query head.  Negative: status. */
+int64_t tm_op_attn_bwd_scratch_bytes(int dtype, int64_t seq, int64_t batch, int64_t nq, int64_t nkv,
+                                     int64_t d);
+
+/* dqkv (same layout as qkv) from dctx; scratch: see above, 16-byte aligned, contents undefined afterwards. */
 int tm_op_attn_bwd(int dtype, int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d,
-                   const void *qkv, const void *ctx, const void *dctx, const float *lse, float *dvec,
+                   const void *qkv, const void *ctx, const void *dctx, const float *lse, void *scratch,
                    void *dqkv, void *stream);
 
 #ifdef __cplusplus

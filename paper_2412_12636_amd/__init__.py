@@ -80,6 +80,7 @@ EXPORTS = {
     "tm_op_act_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 4),
     "tm_op_rotary": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_double, C.c_int, C.c_void_p, C.c_void_p]),
     "tm_op_attn_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 4),
+    "tm_op_attn_bwd_scratch_bytes": (C.c_int64, [C.c_int] + [C.c_int64] * 5),
     "tm_op_attn_bwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 7),
 }
 
@@ -259,6 +260,10 @@ def tm_op_attn_fwd(dtype, seq, batch, nq, nkv, d, qkv, ctx, lse, stream=0):
     _check(lib().tm_op_attn_fwd(dtype, seq, batch, nq, nkv, d, _ptr(qkv), _ptr(ctx), _ptr(lse), stream))
 
 
-def tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, qkv, ctx, dctx, lse, dvec, dqkv, stream=0):
+def tm_op_attn_bwd_scratch_bytes(dtype, seq, batch, nq, nkv, d) -> int:
+    return _check(lib().tm_op_attn_bwd_scratch_bytes(dtype, seq, batch, nq, nkv, d))
+
+
+def tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, qkv, ctx, dctx, lse, scratch, dqkv, stream=0):
     _check(lib().tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, _ptr(qkv), _ptr(ctx), _ptr(dctx), _ptr(lse),
-                                _ptr(dvec), _ptr(dqkv), stream))
+                                _ptr(scratch), _ptr(dqkv), stream))

@@ -17,7 +17,10 @@ int attn_bwd_generic_launch(int dtype, int64_t seq, int64_t batch, int64_t nq, i
 bool attn_mfma_supported(int dtype, int64_t d);
 int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d, const void *qkv, void *ctx,
                          float *lse, hipStream_t s);
+// fp32 elements of the partial buffer the backward kernels need (0 unless query heads share kv heads)
+int64_t attn_bwd_mfma_partial_floats(int64_t seq, int64_t batch, int64_t nq, int64_t nkv);
 int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d, const void *qkv,
-                         const void *dctx, const float *lse, const float *dvec, void *dqkv, hipStream_t s);
+                         const void *dctx, const float *lse, const float *dvec, float *part, void *dqkv,
+                         hipStream_t s);
 
 }  // namespace tmk

@@ -1,5 +1,5 @@
 // Causal attention entry points: argument checks and dispatch between the MFMA flash-style
-// kernels (bf16, head size 64 or 128) and the plain-ALU kernels (everything else).
+// kernels (bf16, head size 128) and the plain-ALU kernels (everything else).
 #include "attn.h"
 #include "../../include/tm_ops.h"
 
@@ -13,7 +13,7 @@ static int check_attn(const char *what, int dtype, int64_t seq, int64_t batch, i
   if (nq > 65535 || batch > 65535) return fail(TM_ESIZE, "%s: more than 65535 heads or batch entries", what);
   if (seq * batch * (nq + 2 * nkv) * d >= (1LL << 40)) return fail(TM_ESIZE, "%s: tensor too large", what);
   if (!attn_mfma_supported(dtype, d) && seq > attn_generic_max_seq())
-    return fail(TM_ESIZE, "%s: sequences above %d need bf16 with head size 64 or 128", what, attn_generic_max_seq());
+    return fail(TM_ESIZE, "%s: sequences above %d need bf16 with head size 128", what, attn_generic_max_seq());
   return TM_OK;
 }
 
@@ -26,13 +26,25 @@ extern "C" int tm_op_attn_fwd(int dtype, int64_t seq, int64_t batch, int64_t nq,
   return attn_fwd_generic_launch(dtype, seq, batch, nq, nkv, d, qkv, ctx, lse, s);
 }
 
+extern "C" int64_t tm_op_attn_bwd_scratch_bytes(int dtype, int64_t seq, int64_t batch, int64_t nq, int64_t nkv,
+                                                int64_t d) {
+  if (int e = check_attn("attn_bwd_scratch_bytes", dtype, seq, batch, nq, nkv, d)) return e;
+  const int64_t dvec = (batch * nq * seq + 63) / 64 * 64;  // the row statistics D, padded to 256 bytes
+  const int64_t part = attn_mfma_supported(dtype, d) ? attn_bwd_mfma_partial_floats(seq, batch, nq, nkv) : 0;
+  return (dvec + part) * (int64_t)sizeof(float);
+}
+
 extern "C" int tm_op_attn_bwd(int dtype, int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d,
-                              const void *qkv, const void *ctx, const void *dctx, const float *lse, float *dvec,
+                              const void *qkv, const void *ctx, const void *dctx, const float *lse, void *scratch,
                               void *dqkv, void *stream) {
   if (int e = check_attn("attn_bwd", dtype, seq, batch, nq, nkv, d)) return e;
-  if (!qkv || !ctx || !dctx || !lse || !dvec || !dqkv) return fail(TM_EINVAL, "attn_bwd: NULL pointer");
+  if (!qkv || !ctx || !dctx || !lse || !scratch || !dqkv) return fail(TM_EINVAL, "attn_bwd: NULL pointer");
+  if (((uintptr_t)scratch) & 15) return fail(TM_EALIGN, "attn_bwd: scratch must be 16-byte aligned");
   hipStream_t s = (hipStream_t)stream;
+  float *dvec = (float *)scratch;
+  float *part = dvec + (batch * nq * seq + 63) / 64 * 64;
   if (int e = attn_dvec_launch(dtype, seq, batch, nq, nkv, d, ctx, dctx, dvec, s)) return e;
-  if (attn_mfma_supported(dtype, d)) return attn_bwd_mfma_launch(seq, batch, nq, nkv, d, qkv, dctx, lse, dvec, dqkv, s);
+  if (attn_mfma_supported(dtype, d))
+    return attn_bwd_mfma_launch(seq, batch, nq, nkv, d, qkv, dctx, lse, dvec, part, dqkv, s);
   return attn_bwd_generic_launch(dtype, seq, batch, nq, nkv, d, qkv, dctx, lse, dvec, dqkv, s);
 }

@@ -19,8 +19,12 @@
 // directly.  The chunk placement inside a row is chosen so that both kinds of read are free of bank
 // conflicts.
 //
-// Gradients are accumulated without atomics: dK/dV by a block that owns 128 key rows and loops over
-// the query heads of its group and all later query tiles; dQ by a block that owns 128 query rows.
+// Gradients are accumulated without atomics: dQ by a block that owns 128 query rows; dK/dV by a block
+// that owns 128 key rows and loops over all later query tiles of ONE query head.  With grouped-query
+// attention (several query heads per kv head) each head's block writes an fp32 partial and a small
+// kernel adds the partials of a group in head order (a block looping over the whole group instead would
+// leave a chip of 256 compute units with seq/128 * kv heads blocks: 32 for a 4096-token sequence and one
+// kv head).
 #include <math.h>
 
 #include "attn.h"
@@ -60,6 +64,7 @@ struct FlashParams {
   float *lse;
   const float *lse_in;
   const float *dvec;
+  float *part;                   // grouped-query dK/dV partials [batch][nq][seq][2][D] fp32, or NULL
   int seq, batch, nq, nkv, row;  // row = (nq + 2 nkv) * D
   float scale;                   // 1 / sqrt(D)
   uint32_t qkv_bytes, ctx_bytes;
@@ -141,6 +146,18 @@ __device__ __forceinline__ void store_transposed(const f32x16 (&acc)[D / 32], fl
 #pragma unroll
       for (int e = 0; e < 4; ++e) o[e] = (bf16)(acc[dt][q4 * 4 + e] * mul);
       *reinterpret_cast<bf16x4 *>(dst_row + dt * 32 + 8 * q4 + 4 * hh) = o;
+    }
+}
+// the same accumulators as fp32: part_row points at [D] floats of this lane's token
+__device__ __forceinline__ void store_transposed_f32(const f32x16 (&acc)[D / 32], float mul, float *part_row, int hh) {
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      f32x4 o;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = acc[dt][q4 * 4 + e] * mul;
+      *reinterpret_cast<f32x4 *>(part_row + dt * 32 + 8 * q4 + 4 * hh) = o;
     }
 }
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
@@ -325,13 +342,14 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
 }
 
 // =================================================================================================
-// dK, dV: block = 128 key rows of one (batch entry, kv head); wave = 32 key rows; loops over the
-// query heads of the group and over query tiles of 64 rows from the diagonal to the end
+// dK, dV: block = 128 key rows of one (batch entry, query head); wave = 32 key rows; loops over query
+// tiles of 64 rows from the diagonal to the end.  One query head per kv head: the block's result is the
+// gradient.  Grouped heads: it is that head's fp32 partial.
 // =================================================================================================
 __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p) {
   extern __shared__ __align__(16) char smem[];  // [stage][Q, dO] tiles, then [stage][lse, D] rows of floats
-  const int kt = blockIdx.x, kap = blockIdx.y, n = blockIdx.z;
-  const int group = p.nq / p.nkv;
+  const int kt = blockIdx.x, g = blockIdx.y, n = blockIdx.z;
+  const int group = p.nq / p.nkv, kap = g / group;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
   const int j0w = kt * 128 + wave * 32;
@@ -360,13 +378,13 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p)
 
   const int it_begin = (kt * 128) / TILE;
   const int it_end = (p.seq + TILE - 1) / TILE;
-  const int per_head = it_end - it_begin, total = group * per_head;
-  // one flat sequence of (query head, query tile) steps, double buffered; the row statistics of a
+  const int per_head = it_end - it_begin, total = per_head;
+  // the query tiles of this head, double buffered; the row statistics of a
   // step are fetched into registers one step ahead by the first wave and put into LDS just before
   // the barrier that publishes the step's tiles
   float st_lse = 0.f, st_d = 0.f;
   auto issue_step = [&](int step, int stage) {
-    const int g = kap * group + step / per_head, i0 = (it_begin + step % per_head) * TILE;
+    const int i0 = (it_begin + step) * TILE;
     lq.issue(rq, tile(stage, 0), (int64_t)i0 * tstride, (int64_t)n * p.row + g * D, wave);
     ldo.issue(rdo, tile(stage, 1), (int64_t)i0 * cstride, (int64_t)n * p.nq * D + g * D, wave);
     if (threadIdx.x < TILE) {
@@ -379,7 +397,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p)
   issue_step(0, 0);
   for (int step = 0; step < total; ++step) {
     const int cur = step & 1;
-    const int i0 = (it_begin + step % per_head) * TILE;
+    const int i0 = (it_begin + step) * TILE;
     wait_loads();
     if (threadIdx.x < TILE) {
       float *st = stats + cur * 2 * TILE;
@@ -432,10 +450,41 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p)
   }
   wait_loads();
   if (jvalid) {
-    bf16 *out = p.dqkv + ((int64_t)j * p.batch + n) * p.row;
-    store_transposed(dk, p.scale, out + koff, hh);
-    store_transposed(dv, 1.f, out + voff, hh);
+    if (p.part) {
+      float *out = p.part + (((int64_t)n * p.nq + g) * p.seq + j) * (2 * D);
+      store_transposed_f32(dk, p.scale, out, hh);
+      store_transposed_f32(dv, 1.f, out + D, hh);
+    } else {
+      bf16 *out = p.dqkv + ((int64_t)j * p.batch + n) * p.row;
+      store_transposed(dk, p.scale, out + koff, hh);
+      store_transposed(dv, 1.f, out + voff, hh);
+    }
   }
+}
+
+// dK, dV of a kv head = sum of its query heads' partials, added in head order; thread = 4 columns
+__global__ __launch_bounds__(256) void flash_dkv_reduce_kernel(const FlashParams p) {
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // over [batch][nkv][seq][2 * D / 4]
+  const int64_t total = (int64_t)p.batch * p.nkv * p.seq * (2 * D / 4);
+  if (idx >= total) return;
+  const int c4 = (int)(idx % (2 * D / 4));
+  const int64_t r = idx / (2 * D / 4);
+  const int j = (int)(r % p.seq);
+  const int kap = (int)((r / p.seq) % p.nkv), n = (int)(r / ((int64_t)p.seq * p.nkv));
+  const int group = p.nq / p.nkv;
+  f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+  for (int gg = 0; gg < group; ++gg) {
+    const float *src = p.part + (((int64_t)n * p.nq + kap * group + gg) * p.seq + j) * (2 * D) + c4 * 4;
+    const f32x4 v = *reinterpret_cast<const f32x4 *>(src);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sum[e] += v[e];
+  }
+  bf16x4 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (bf16)sum[e];
+  const int which = c4 / (D / 4), col = (c4 % (D / 4)) * 4;  // 0: dK, 1: dV
+  bf16 *out = p.dqkv + ((int64_t)j * p.batch + n) * p.row + (p.nq + which * p.nkv + kap) * D + col;
+  *reinterpret_cast<bf16x4 *>(out) = o;
 }
 
 bool attn_mfma_supported(int dtype, int64_t d) { return dtype == TM_DTYPE_BF16 && d == D; }
@@ -467,8 +516,13 @@ int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   return check_launch("flash_fwd");
 }
 
+int64_t attn_bwd_mfma_partial_floats(int64_t seq, int64_t batch, int64_t nq, int64_t nkv) {
+  return nq == nkv ? 0 : batch * nq * seq * 2 * D;
+}
+
 int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d, const void *qkv,
-                         const void *dctx, const float *lse, const float *dvec, void *dqkv, hipStream_t s) {
+                         const void *dctx, const float *lse, const float *dvec, float *part, void *dqkv,
+                         hipStream_t s) {
   (void)d;
   if (seq * batch * (nq + 2 * nkv) * D * 2 >= (1LL << 31)) return fail(TM_ESIZE, "flash_bwd: qkv tensor above 2 GiB");
   FlashParams p = make_params(seq, batch, nq, nkv);
@@ -477,8 +531,10 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   p.lse_in = lse;
   p.dvec = dvec;
   p.dqkv = (bf16 *)dqkv;
+  p.part = nq == nkv ? nullptr : part;
+  if (nq != nkv && !part) return fail(TM_EINVAL, "flash_bwd: grouped heads need the partial buffer");
   dim3 gq((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
-  dim3 gk((unsigned)ceil_div(seq, 128), (unsigned)nkv, (unsigned)batch);
+  dim3 gk((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
   const int lds = 4 * TILE_BYTES + 2 * 2 * TILE * (int)sizeof(float);
   static bool attr_set = false;
   if (!attr_set) {
@@ -490,6 +546,10 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   g_last_kernel = "flash_bwd_dq_kernel+flash_bwd_dkv_kernel";
   flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
   flash_bwd_dkv_kernel<<<gk, 256, lds, s>>>(p);
+  if (p.part) {
+    const int64_t total = batch * nkv * seq * (2 * D / 4);
+    flash_dkv_reduce_kernel<<<(unsigned)ceil_div(total, (int64_t)256), 256, 0, s>>>(p);
+  }
   return check_launch("flash_bwd");
 }
 

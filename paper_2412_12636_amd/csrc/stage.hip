@@ -140,7 +140,7 @@ struct Plan {
   int64_t dnorm;       // [T, h]  : gradient w.r.t. a norm's output (dc, da)
   int64_t dctx;        // [T, A]
   int64_t dqkv;        // [T, Nqkv]
-  int64_t dvec;        // [b, nq, s] fp32
+  int64_t dvec;        // scratch of the attention backward pass
   int64_t reduce;      // scratch of the column reductions
   int64_t total;
 };
@@ -182,7 +182,7 @@ static Plan make_plan(const tm_stage_config_t *c) {
   p.dnorm = take(T * h * es);
   p.dctx = take(T * A * es);
   p.dqkv = take(T * nqkv * es);
-  p.dvec = take(stat);
+  p.dvec = take(tm_op_attn_bwd_scratch_bytes(c->dtype, c->seq, c->micro_batch, c->n_q_heads, c->n_kv_heads, c->head_dim));
   const int64_t widest = std::max(std::max(2 * h, f1), std::max(nqkv, h));
   p.reduce = take(tm_op_reduce_scratch_bytes(T, widest));
   p.total = at;
@@ -612,7 +612,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     // attention, rotary
     TM_STEP(2 * attn_flops, 0,
             tm_op_attn_bwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
-                           ws + pl.dctx, (const float *)(ws + k.lse), (float *)(ws + pl.dvec), ws + pl.dqkv, s));
+                           ws + pl.dctx, (const float *)(ws + k.lse), ws + pl.dvec, ws + pl.dqkv, s));
     if (c.pos == TM_POS_ROTARY)
       TM_STEP(0, 2 * es * d.T * (c.n_q_heads + c.n_kv_heads) * c.head_dim,
               tm_op_rotary(dt, c.seq, c.micro_batch, c.n_q_heads + c.n_kv_heads, c.head_dim, d.nqkv, c.rope_theta, 1,

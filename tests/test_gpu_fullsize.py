@@ -73,7 +73,7 @@ def test_attention_long_context_sampled_rows(env):
     s = stream_ptr(torch)
     ctx = torch.empty((seq, batch, A), dtype=torch.bfloat16, device="cuda")
     lse = torch.empty((batch, nq, seq), dtype=torch.float32, device="cuda")
-    dvec = torch.empty_like(lse)
+    dvec = torch.empty(tm.tm_op_attn_bwd_scratch_bytes(BF16, seq, batch, nq, nkv, d), dtype=torch.uint8, device="cuda")
     dqkv = torch.empty_like(qkv)
     tm.tm_op_attn_fwd(BF16, seq, batch, nq, nkv, d, qkv, ctx, lse, s)
     tm.tm_op_attn_bwd(BF16, seq, batch, nq, nkv, d, qkv, ctx, dctx, lse, dvec, dqkv, s)

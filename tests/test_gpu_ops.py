@@ -259,7 +259,7 @@ def test_attention_fwd_bwd(env, dtype, seq, batch, nq, nkv, d):
             assert np.abs(to_host(lse[n, g]) - ref_lse).max() <= (1e-3 if dtype == BF16 else 1e-4)
 
     dqkv = torch.zeros((seq, batch, W), dtype=td, device="cuda")
-    dvec = torch.empty((batch, nq, seq), dtype=torch.float32, device="cuda")
+    dvec = torch.empty(tm.tm_op_attn_bwd_scratch_bytes(dtype, seq, batch, nq, nkv, d), dtype=torch.uint8, device="cuda")
     tm.tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, qd, ctx, to_dev(torch, dctx, dtype), lse, dvec, dqkv, s)
     dq, dk, dv = so.attention_bwd(dctx.astype(np.float64).reshape(seq, batch, nq, d), q, k, v)
     got = to_host(dqkv)
@@ -280,7 +280,7 @@ def test_attention_is_bit_reproducible(env):
         ctx = torch.empty((seq, batch, A), dtype=torch.bfloat16, device="cuda")
         lse = torch.empty((batch, nq, seq), dtype=torch.float32, device="cuda")
         dqkv = torch.empty((seq, batch, W), dtype=torch.bfloat16, device="cuda")
-        dvec = torch.empty((batch, nq, seq), dtype=torch.float32, device="cuda")
+        dvec = torch.empty(tm.tm_op_attn_bwd_scratch_bytes(BF16, seq, batch, nq, nkv, d), dtype=torch.uint8, device="cuda")
         tm.tm_op_attn_fwd(BF16, seq, batch, nq, nkv, d, qd, ctx, lse, stream_ptr(torch))
         tm.tm_op_attn_bwd(BF16, seq, batch, nq, nkv, d, qd, ctx, dc, lse, dvec, dqkv, stream_ptr(torch))
         outs.append((ctx, lse, dqkv))
