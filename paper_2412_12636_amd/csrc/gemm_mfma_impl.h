@@ -118,13 +118,22 @@ __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (
       for (int j = 0; j < TN; ++j) {
         const int col = col_base + j * 32 + l32;
         const bool col_ok = col < p.N;
+        uint32_t off[16];
+        float old[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           const int row = row_base + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-          const uint32_t off = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
-          float o = acc[i][j][v];
-          if (EPI == 1) o += __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, off, 0, 0));
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, o), rc, off, 0, kStoreNonTemporal);
+          off[v] = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
+        }
+        if (EPI == 1) {  // all sixteen reads of the tile are in flight before the first add
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            old[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rc, off[v], 0, kStoreNonTemporal));
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float o = EPI == 1 ? old[v] + acc[i][j][v] : acc[i][j][v];
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, o), rc, off[v], 0, kStoreNonTemporal);
         }
       }
     return;
