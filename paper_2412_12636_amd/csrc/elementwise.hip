@@ -136,17 +136,20 @@ __device__ __forceinline__ void adam_one(float &p, float g, float &m, float &v, 
   p = p - a.lr * (mhat / (sqrtf(vhat) + a.eps) + a.weight_decay * p);
 }
 
+// One wave per block measured 3 % faster than four on this sweep (finer units for the dispatcher).
+constexpr int kAdamThreads = 64;
+
 // One 16-byte chunk of each array per thread, blocks in address order (no grid-stride loop: with a
 // long stride the HBM channels see scattered pages and the rate drops by a fifth), streaming
 // (non-temporal) accesses since nothing is re-read.  Reads g,p,m,v; writes p,m,v (+ bf16 p, + zeroed g).
 template <bool LOWP, bool ZERO>
-__global__ __launch_bounds__(kEwThreads) void adam_kernel(float *__restrict__ p, float *__restrict__ g,
+__global__ __launch_bounds__(kAdamThreads) void adam_kernel(float *__restrict__ p, float *__restrict__ g,
                                                          float *__restrict__ m, float *__restrict__ v,
                                                          bf16 *__restrict__ p_lowp, int64_t n, AdamScalars a) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
   const int64_t nvec = n / 4;
-  const int64_t i = (int64_t)blockIdx.x * kEwThreads + threadIdx.x;
+  const int64_t i = (int64_t)blockIdx.x * kAdamThreads + threadIdx.x;
   if (i < nvec) {
     f32x4 pv = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(p) + i);
     f32x4 gv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g) + i);
@@ -301,16 +304,18 @@ extern "C" int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float 
   a.inv_bc1 = (float)(1.0 / (1.0 - pow(hp->beta1, (double)step)));
   a.inv_bc2 = (float)(1.0 / (1.0 - pow(hp->beta2, (double)step)));
   hipStream_t s = (hipStream_t)stream;
-  const unsigned grid = ew_grid(n / 4 > 0 ? n / 4 : 1);
+  const int64_t nchunk = n / 4 > 0 ? n / 4 : 1;
+  if (ceil_div(nchunk, (int64_t)kAdamThreads) > 0x7fffffffLL) return fail(TM_ESIZE, "adam: array too long for one launch");
+  const unsigned grid = (unsigned)ceil_div(nchunk, (int64_t)kAdamThreads);
   const bool lowp = p_bf16 != nullptr, zero = hp->zero_grads != 0;
   g_last_kernel = "adam_kernel";
   if (lowp && zero)
-    adam_kernel<true, true><<<grid, kEwThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, n, a);
+    adam_kernel<true, true><<<grid, kAdamThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, n, a);
   else if (lowp)
-    adam_kernel<true, false><<<grid, kEwThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, n, a);
+    adam_kernel<true, false><<<grid, kAdamThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, n, a);
   else if (zero)
-    adam_kernel<false, true><<<grid, kEwThreads, 0, s>>>(p, g, m, v, nullptr, n, a);
+    adam_kernel<false, true><<<grid, kAdamThreads, 0, s>>>(p, g, m, v, nullptr, n, a);
   else
-    adam_kernel<false, false><<<grid, kEwThreads, 0, s>>>(p, g, m, v, nullptr, n, a);
+    adam_kernel<false, false><<<grid, kAdamThreads, 0, s>>>(p, g, m, v, nullptr, n, a);
   return check_launch("adam");
 }
