@@ -29,8 +29,10 @@
 // past the end are dropped, so ragged M / N edges need no branches.  Only the per-lane offset is
 // checked against the descriptor's size, so everything that can run past the end travels in it.
 //
-// Epilogue: the MFMA operands are passed swapped, so an accumulator tile is C^T and every lane owns
-// four CONSECUTIVE output columns of one row: 8-byte bf16 / 16-byte fp32 stores.
+// Epilogue.  bf16 results: the MFMA operands are passed swapped, so an accumulator tile is C^T and every
+// lane owns four consecutive output columns of one row; the block's tile is assembled in LDS and leaves
+// as whole rows (16 bytes per lane), a residual operand arrives the same way.  fp32 results: natural
+// orientation, a store instruction writes two whole 128-byte lines, streamed past the caches.
 //
 // Block index -> tile mapping: consecutive hardware block ids land on different XCDs (8 per chip,
 // each with its own L2); ids are re-numbered so that every XCD works on a contiguous range of
@@ -279,6 +281,84 @@ template <int R, int BK, int NW> struct DirectSel<R, BK, false, NW> { typedef Di
 
 template <int N> __device__ __forceinline__ void wait_vmcnt() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 
+// ---- bf16 epilogue through LDS --------------------------------------------------------------------
+// The accumulator layout gives every lane 8 bytes in each of many rows; written to global memory directly
+// that is 32 partial lines per store instruction.  Instead the block's tile is assembled in LDS (the
+// stages are free after the main loop) and leaves as whole rows, 16 bytes per lane; a residual operand
+// comes in the same way.  The arithmetic is unchanged: acc + bias + residual in fp32, one rounding.
+// Position of 16-byte chunk c of tile row `row`: XOR with low row bits, so that the 8-byte accesses of 32
+// consecutive rows spread over all banks.
+template <int CPR> __device__ __forceinline__ int epi_place(int c, int row) {
+  if (c < (CPR & ~15)) return (c & ~15) | ((c ^ row) & 15);
+  return (c & ~7) | ((c ^ row) & 7);
+}
+template <int BM, int BN, int NW, int TM, int TN>
+__device__ __forceinline__ void epilogue_lds(const MfmaGemmParams &p, const f32x16 (&acc)[TM][TN], char *lds, int m0,
+                                             int n0, int wrow, int wcol, int lane) {
+  constexpr int CPR = BN / 8, ROWB = BN * 2, NT = 64 * NW, CHUNKS = BM * CPR;
+  static_assert(CHUNKS % NT == 0, "whole passes");
+  const int l32 = lane & 31, hh = lane >> 5, tid = threadIdx.x;
+  const rsrc_t rc = make_rsrc(p.C, p.c_bytes);
+  if (p.residual) {
+    const rsrc_t rres = make_rsrc(p.residual, p.c_bytes);
+#pragma unroll
+    for (int it = 0; it < CHUNKS / NT; ++it) {
+      const int idx = it * NT + tid, row = idx / CPR, c = idx % CPR;
+      const int gcol = n0 + c * 8;
+      const uint32_t off = gcol < p.N ? (uint32_t)(((int64_t)(m0 + row) * p.ldc + gcol) * 2) : 0xfffffff0u;
+      const u32x4 v = buf_load16(rres, off, 0);
+      *reinterpret_cast<u32x4 *>(lds + row * ROWB + (epi_place<CPR>(c, row) << 4)) = v;
+    }
+    __syncthreads();
+  }
+  const rsrc_t rbias = make_rsrc(p.bias ? (const void *)p.bias : p.C, (uint32_t)p.N * 2u);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int tcol = wcol + j * 32 + 8 * q + 4 * hh;  // column inside the tile
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (p.bias) {
+        const int col = n0 + tcol;
+        const u32x2 braw = __builtin_bit_cast(
+            u32x2, __builtin_amdgcn_raw_buffer_load_b64(rbias, col < p.N ? (uint32_t)col * 2u : 0xfffffff0u, 0, 0));
+        bv[0] = __builtin_bit_cast(float, braw[0] << 16);
+        bv[1] = __builtin_bit_cast(float, braw[0] & 0xffff0000u);
+        bv[2] = __builtin_bit_cast(float, braw[1] << 16);
+        bv[3] = __builtin_bit_cast(float, braw[1] & 0xffff0000u);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = wrow + i * 32 + l32;
+        char *at = lds + row * ROWB + (epi_place<CPR>(tcol >> 3, row) << 4) + ((tcol & 4) << 1);
+        float r[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = acc[i][j][4 * q + e] + bv[e];
+        if (p.residual) {
+          const u32x2 rr = *reinterpret_cast<const u32x2 *>(at);
+          r[0] += __builtin_bit_cast(float, rr[0] << 16);
+          r[1] += __builtin_bit_cast(float, rr[0] & 0xffff0000u);
+          r[2] += __builtin_bit_cast(float, rr[1] << 16);
+          r[3] += __builtin_bit_cast(float, rr[1] & 0xffff0000u);
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)r[e];
+        *reinterpret_cast<bf16x4 *>(at) = o;
+      }
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < CHUNKS / NT; ++it) {
+    const int idx = it * NT + tid, row = idx / CPR, c = idx % CPR;
+    const int gcol = n0 + c * 8;
+    const uint32_t off = gcol < p.N ? (uint32_t)(((int64_t)(m0 + row) * p.ldc + gcol) * 2) : 0xfffffff0u;
+    const u32x4 v = *reinterpret_cast<const u32x4 *>(lds + row * ROWB + (epi_place<CPR>(c, row) << 4));
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u32, v), rc, off, 0, 0);
+  }
+}
+
 // =================================================================================================
 // pipelined kernel: WGM x WGN waves, two LDS stages, the barrier sits before the LAST reduction slice
 // =================================================================================================
@@ -400,7 +480,13 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
     sched_last<MF, DSN, LOADS, 0>();
   }
   wait_vmcnt<0>();  // drain the look-ahead loads before the block may exit
-  epilogue<TM, TN, EPI>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
+  if constexpr (EPI == 0) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();  // every wave's loads have landed and its LDS reads are done: the stages are free
+    epilogue_lds<BM, BN, NW, TM, TN>(p, acc, lds, m0, n0, wm * WM, wn * WN, lane);
+  } else {
+    epilogue<TM, TN, EPI>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
+  }
 }
 
 // =================================================================================================
