@@ -33,6 +33,15 @@ int tm_op_linear_fwd(int dtype, int64_t T, int64_t N, int64_t K, const void *x, 
 int tm_op_linear_dgrad(int dtype, int64_t T, int64_t N, int64_t K, const void *dy, const void *w,
                        void *dx, void *stream);
 
+/* The same product with scratch: where the output has few tiles and the reduction is long (the
+ * out-projection's input gradient at a tensor-parallel shard) the reduction is split into parts that fill
+ * the chip, their fp32 results are added in part order and rounded once.  Whether it splits depends on
+ * the shape only (tm_op_linear_dgrad_scratch_bytes > 0); with less scratch than that, or NULL, this is
+ * tm_op_linear_dgrad.  The two differ by fp32 summation order where it splits. */
+int64_t tm_op_linear_dgrad_scratch_bytes(int dtype, int64_t T, int64_t N, int64_t K);
+int tm_op_linear_dgrad_ws(int dtype, int64_t T, int64_t N, int64_t K, const void *dy, const void *w,
+                          void *dx, void *scratch, int64_t scratch_bytes, void *stream);
+
 /* Weight gradient in fp32: dw[N,K] += dy[T,N]^T x[T,K] when accumulate != 0, dw = ... otherwise
  * (the old contents are then not read). */
 int tm_op_linear_wgrad(int dtype, int64_t T, int64_t N, int64_t K, const void *dy, const void *x,

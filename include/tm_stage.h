@@ -89,6 +89,8 @@ typedef struct {
  *   exp_avg, exp_avg_sq   n fp32 Adam moments
  *   workspace   tm_stage_workspace_bytes() bytes: activation stash written by fwd and read by bwd,
  *               plus scratch.  Contents are private to the library between fwd and bwd.
+ *   workspace_bytes   the size of that allocation; tm_stage_init refuses (TM_ESIZE) one that is smaller
+ *               than tm_stage_workspace_bytes() of the same library build
  */
 typedef struct {
   void *params;
@@ -97,6 +99,7 @@ typedef struct {
   float *exp_avg;
   float *exp_avg_sq;
   void *workspace;
+  int64_t workspace_bytes;
 } tm_stage_buffers_t;
 
 typedef struct {

@@ -37,7 +37,8 @@ class tm_stage_config_t(C.Structure):
 
 
 class tm_stage_buffers_t(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("params", "master", "grads", "exp_avg", "exp_avg_sq", "workspace")]
+    _fields_ = [(n, C.c_void_p) for n in ("params", "master", "grads", "exp_avg", "exp_avg_sq", "workspace")] + \
+               [("workspace_bytes", C.c_int64)]
 
 
 class tm_profile_entry_t(C.Structure):
@@ -71,6 +72,8 @@ EXPORTS = {
     "tm_last_error": (C.c_char_p, []),
     "tm_op_linear_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 6),
     "tm_op_linear_dgrad": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 4),
+    "tm_op_linear_dgrad_scratch_bytes": (C.c_int64, [C.c_int] + [C.c_int64] * 3),
+    "tm_op_linear_dgrad_ws": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 4 + [C.c_int64, C.c_void_p]),
     "tm_op_linear_wgrad": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 3 + [C.c_int, C.c_void_p]),
     "tm_op_reduce_scratch_bytes": (C.c_int64, [C.c_int64, C.c_int64]),
     "tm_op_bias_grad": (C.c_int, [C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 3 + [C.c_int, C.c_void_p]),
@@ -155,9 +158,15 @@ def tm_stage_param_layout(cfg) -> List[Tuple[str, int, Tuple[int, int]]]:
     return out
 
 
-def tm_stage_init(cfg, params, master, grads, exp_avg, exp_avg_sq, workspace) -> int:
-    """Returns the opaque handle (an integer address)."""
-    b = tm_stage_buffers_t(_ptr(params), _ptr(master), _ptr(grads), _ptr(exp_avg), _ptr(exp_avg_sq), _ptr(workspace))
+def tm_stage_init(cfg, params, master, grads, exp_avg, exp_avg_sq, workspace, workspace_bytes: Optional[int] = None) -> int:
+    """Returns the opaque handle (an integer address).  workspace_bytes: the size of the workspace
+    allocation; taken from the tensor when one is passed."""
+    if workspace_bytes is None:
+        if not hasattr(workspace, "numel"):
+            raise ValueError("tm_stage_init: workspace_bytes is required when the workspace is a bare address")
+        workspace_bytes = int(workspace.numel()) * int(workspace.element_size())
+    b = tm_stage_buffers_t(_ptr(params), _ptr(master), _ptr(grads), _ptr(exp_avg), _ptr(exp_avg_sq), _ptr(workspace),
+                           workspace_bytes)
     h = C.c_void_p()
     _check(lib().tm_stage_init(C.byref(make_config(cfg)), C.byref(b), C.byref(h)))
     return h.value
@@ -218,6 +227,14 @@ def tm_op_linear_fwd(dtype, T, N, K, x, w, bias, residual, y, stream=0):
 
 def tm_op_linear_dgrad(dtype, T, N, K, dy, w, dx, stream=0):
     _check(lib().tm_op_linear_dgrad(dtype, T, N, K, _ptr(dy), _ptr(w), _ptr(dx), stream))
+
+
+def tm_op_linear_dgrad_scratch_bytes(dtype, T, N, K) -> int:
+    return _check(lib().tm_op_linear_dgrad_scratch_bytes(dtype, T, N, K))
+
+
+def tm_op_linear_dgrad_ws(dtype, T, N, K, dy, w, dx, scratch, scratch_bytes, stream=0):
+    _check(lib().tm_op_linear_dgrad_ws(dtype, T, N, K, _ptr(dy), _ptr(w), _ptr(dx), _ptr(scratch), scratch_bytes, stream))
 
 
 def tm_op_linear_wgrad(dtype, T, N, K, dy, x, dw, accumulate=1, stream=0):

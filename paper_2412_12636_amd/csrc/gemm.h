@@ -19,6 +19,13 @@ struct GemmArgs {
   const void *bias;
   const void *residual;
   int c_mode;
+  // Split reduction (dx = dy W with few output tiles).  Caller side: scratch for the fp32 partial results;
+  // gemm_mfma() decides from the shape whether to use it (gemm_mfma_splitk_bytes says how much it wants).
+  void *splitk_scratch = nullptr;
+  int64_t splitk_bytes = 0;
+  // Kernel side: block row y of the grid reduces over the y-th of k_splits equal parts of K and writes the
+  // y-th of k_splits results [M, ldc] behind C (c_mode 2).
+  int k_splits = 1;
 };
 
 int gemm_generic(int dtype, const GemmArgs &g, hipStream_t s);
@@ -28,6 +35,8 @@ int gemm_generic(int dtype, const GemmArgs &g, hipStream_t s);
 // 16-byte aligned base pointers.
 bool gemm_mfma_supported(const GemmArgs &g);
 int gemm_mfma(const GemmArgs &g, hipStream_t s);
+// Bytes of scratch with which gemm_mfma() would split this product's reduction (0: it would not).
+int64_t gemm_mfma_splitk_bytes(const GemmArgs &g);
 // Measures the tile configurations for one layout and shape, on n instances of the product that live
 // in different memory (the launches cycle through them), and makes later gemm_mfma() calls of that layout
 // and shape use the fastest.  Overwrites every C; waits for the stream.  Without it a cost model picks.

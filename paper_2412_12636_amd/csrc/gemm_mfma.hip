@@ -15,6 +15,7 @@ namespace tmk {
 int gemm_mfma_nt(const GemmArgs &g, int config, hipStream_t s);  // y = x W^T       (both reduction axes contiguous)
 int gemm_mfma_nn(const GemmArgs &g, int config, hipStream_t s);  // dx = dy W       (W read along its strided axis)
 int gemm_mfma_tn(const GemmArgs &g, int config, hipStream_t s);  // dW (+)= dy^T x  (both strided, fp32 result)
+int gemm_mfma_nn_partial(const GemmArgs &g, hipStream_t s);      // dx = dy W in k_splits fp32 parts, 128x192 tiles
 
 bool gemm_mfma_supported(const GemmArgs &g) {
   auto operand_ok = [&](const void *ptr, int64_t rs, int64_t cs, int64_t rows) {
@@ -104,7 +105,65 @@ static int launch_config(const GemmArgs &g, int config, hipStream_t s) {
   return fail(TM_EINVAL, "gemm_mfma: operand layout not instantiated");
 }
 
-int gemm_mfma(const GemmArgs &g, hipStream_t s) { return launch_config(g, pick_config(g), s); }
+// ---- split reduction --------------------------------------------------------------------------------
+// dx = dy W with a long reduction and few output tiles (the out-projection's input gradient: 2048 x 1536
+// over 12288) fills a fraction of the chip.  With scratch from the caller the reduction is cut into parts
+// whose 128x192 tiles make one pass of 512 blocks; the fp32 parts are added in part order and rounded once.
+// The choice depends on the shape only, so results stay reproducible.
+static int splitk_parts(const GemmArgs &g) {
+  if (g.c_mode != 0 || g.bias || g.residual || !(g.a_cs == 1 && g.b_cs != 1)) return 1;
+  const int64_t tiles = ceil_div(g.M, 128) * ceil_div(g.N, 192);
+  if (tiles > 256 || g.K < 4096) return 1;
+  int parts = (int)(512 / tiles);
+  if (parts > 8) parts = 8;
+  while (parts > 1 && g.K % (64 * parts) != 0) --parts;
+  return parts;
+}
+
+int64_t gemm_mfma_splitk_bytes(const GemmArgs &g) {
+  const int parts = splitk_parts(g);
+  return parts > 1 ? (int64_t)parts * g.M * g.N * 4 : 0;
+}
+
+// out[m, n] (bf16, row stride ldc) = sum over parts of part[p][m][n], eight columns per thread
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int parts, int64_t M, int64_t N,
+                                                            bf16 *__restrict__ out, int64_t ldc) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  typedef bf16 bf16x8 __attribute__((ext_vector_type(8)));
+  const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x, per_row = N / 8;
+  if (idx >= M * per_row) return;
+  const int64_t m = idx / per_row, n = (idx % per_row) * 8;
+  f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = lo;
+  for (int q = 0; q < parts; ++q) {
+    const float *src = part + ((int64_t)q * M + m) * N + n;
+    const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src));
+    const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(src) + 1);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) lo[e] += a[e], hi[e] += b[e];
+  }
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) o[e] = (bf16)lo[e], o[4 + e] = (bf16)hi[e];
+  *reinterpret_cast<bf16x8 *>(out + m * ldc + n) = o;
+}
+
+int gemm_mfma(const GemmArgs &g, hipStream_t s) {
+  const int parts = splitk_parts(g);
+  if (parts > 1 && g.splitk_scratch && g.splitk_bytes >= (int64_t)parts * g.M * g.N * 4 &&
+      (((uintptr_t)g.splitk_scratch) & 15) == 0 && g.M * g.N * 4 < (1LL << 31) && forced_config() < 0) {
+    GemmArgs p = g;
+    p.C = g.splitk_scratch;
+    p.ldc = g.N;
+    p.c_mode = 2;
+    p.k_splits = parts;
+    if (int e = gemm_mfma_nn_partial(p, s)) return e;
+    const int64_t groups = g.M * (g.N / 8);
+    splitk_reduce_kernel<<<(unsigned)ceil_div(groups, (int64_t)256), 256, 0, s>>>((const float *)g.splitk_scratch, parts, g.M, g.N,
+                                                                              (bf16 *)g.C, g.ldc);
+    return check_launch("splitk_reduce");
+  }
+  return launch_config(g, pick_config(g), s);
+}
 
 // Times every configuration and remembers the fastest for this layout and shape.  `variants` are n
 // instances of the same product on different memory (say, the weights of different layers): the

@@ -36,6 +36,23 @@ extern "C" int tm_op_linear_dgrad(int dtype, int64_t T, int64_t N, int64_t K, co
   return run(dtype, g, (hipStream_t)stream);
 }
 
+extern "C" int64_t tm_op_linear_dgrad_scratch_bytes(int dtype, int64_t T, int64_t N, int64_t K) {
+  if (int e = check_linear("linear_dgrad_scratch_bytes", dtype, T, N, K)) return e;
+  if (dtype != TM_DTYPE_BF16) return 0;
+  GemmArgs g{T, K, N, nullptr, N, 1, nullptr, 1, K, nullptr, K, nullptr, nullptr, 0};
+  return gemm_mfma_splitk_bytes(g);
+}
+
+extern "C" int tm_op_linear_dgrad_ws(int dtype, int64_t T, int64_t N, int64_t K, const void *dy, const void *w,
+                                     void *dx, void *scratch, int64_t scratch_bytes, void *stream) {
+  if (int e = check_linear("linear_dgrad", dtype, T, N, K)) return e;
+  if (!dy || !w || !dx) return fail(TM_EINVAL, "linear_dgrad: NULL pointer");
+  GemmArgs g{T, K, N, dy, N, 1, w, 1, K, dx, K, nullptr, nullptr, 0};
+  g.splitk_scratch = scratch;
+  g.splitk_bytes = scratch ? scratch_bytes : 0;
+  return run(dtype, g, (hipStream_t)stream);
+}
+
 extern "C" int tm_op_linear_wgrad(int dtype, int64_t T, int64_t N, int64_t K, const void *dy, const void *x, float *dw,
                                   int accumulate, void *stream) {
   if (int e = check_linear("linear_wgrad", dtype, T, N, K)) return e;

@@ -142,6 +142,8 @@ struct Plan {
   int64_t dqkv;        // [T, Nqkv]
   int64_t dvec;        // scratch of the attention backward pass
   int64_t reduce;      // scratch of the column reductions
+  int64_t splitk;      // fp32 partial results of an input-gradient product whose reduction is split
+  int64_t splitk_bytes;
   int64_t total;
 };
 
@@ -185,6 +187,11 @@ static Plan make_plan(const tm_stage_config_t *c) {
   p.dvec = take(tm_op_attn_bwd_scratch_bytes(c->dtype, c->seq, c->micro_batch, c->n_q_heads, c->n_kv_heads, c->head_dim));
   const int64_t widest = std::max(std::max(2 * h, f1), std::max(nqkv, h));
   p.reduce = take(tm_op_reduce_scratch_bytes(T, widest));
+  p.splitk_bytes = 0;
+  const int64_t lin[4][2] = {{nqkv, h}, {h, A}, {f1, h}, {h, f}};  // (N, K) of the four linear maps
+  for (const auto &nk : lin)
+    p.splitk_bytes = std::max(p.splitk_bytes, std::max<int64_t>(0, tm_op_linear_dgrad_scratch_bytes(c->dtype, T, nk[0], nk[1])));
+  p.splitk = take(p.splitk_bytes);
   p.total = at;
   return p;
 }
@@ -300,11 +307,15 @@ extern "C" int tm_stage_init(const tm_stage_config_t *cfg, const tm_stage_buffer
   }
   if (strncmp(prop.gcnArchName, "gfx950", 6) != 0)
     return fail(TM_EARCH, "stage_init: device is %s, this library is built for gfx950", prop.gcnArchName);
+  const Plan plan = make_plan(cfg);
+  if (b->workspace_bytes < plan.total)
+    return fail(TM_ESIZE, "stage_init: workspace of %lld bytes, %lld needed", (long long)b->workspace_bytes,
+                (long long)plan.total);
   tm_stage *st = new tm_stage();
   st->cfg = *cfg;
   st->buf = *b;
   st->lo = layer_offsets(cfg);
-  st->plan = make_plan(cfg);
+  st->plan = plan;
   st->n_params = st->lo.total * cfg->n_layers;
   st->have_fwd = false;
   *out = st;
@@ -585,7 +596,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
 
     // y = x1 + g W2^T + b2
     void *dg = (c.act == TM_ACT_SWIGLU) ? (void *)(ws + pl.dmid) : (void *)(ws + pl.dwide);
-    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_dgrad(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, s));
+    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_dgrad_ws(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
     TM_STEP(mm(d.h, d.f), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), acc, sw));
     if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, acc, s));
@@ -594,7 +605,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     TM_STEP(0, es * d.T * (d.f + 2 * d.f1), tm_op_act_bwd(dt, c.act, d.T, d.f, dg, ws + k.u, du, s));
     // u = c W1^T + b1
     void *dc = ws + pl.dnorm;
-    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_dgrad(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, s));
+    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_dgrad_ws(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
     TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), acc, sw));
     if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, acc, s));
@@ -605,7 +616,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
                            (const float *)(ws + k.rstd2), P(o.norm2_gain), dy, dx1, G(o.norm2_gain),
                            G(o.norm2_offset), red, acc, s));
     // x1 = x + ctx Wout^T + bout
-    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_dgrad(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, s));
+    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_dgrad_ws(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
     TM_STEP(mm(d.h, d.A), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), acc, sw));
     if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, acc, s));
@@ -619,7 +630,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
                            ws + pl.dqkv, s));
     // qkv = a Wqkv^T + b
     void *da = ws + pl.dnorm;
-    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_dgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, s));
+    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_dgrad_ws(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
     TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), acc, sw));
     if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, acc, s));

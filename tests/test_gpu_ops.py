@@ -71,6 +71,32 @@ def test_linear_fwd_dgrad_wgrad(env, dtype, T, N, K):
     assert rel_err(to_host(dw), ref) <= 1e-5
 
 
+def test_input_gradient_with_split_reduction(env):
+    """dx = dy W with few output tiles and a long reduction: with scratch the reduction is split (the size
+    query says so), the result meets the same tolerance against the definition and is reproducible; without
+    scratch the call is the plain product."""
+    torch, tm = env
+    T, N, K = 300, 4096, 264                     # reduction over N = 4096, output 300 x 264: six tiles
+    rng = np.random.default_rng(21)
+    dy, w = rand(rng, (T, N), 0.1, BF16), rand(rng, (N, K), 0.05, BF16)
+    dyd, wd = to_dev(torch, dy, BF16), to_dev(torch, w, BF16)
+    s = stream_ptr(torch)
+    need = tm.tm_op_linear_dgrad_scratch_bytes(BF16, T, N, K)
+    assert need == 8 * T * K * 4                 # eight parts of 512
+    assert tm.tm_op_linear_dgrad_scratch_bytes(BF16, 2048, 4608, 12288) == 0   # enough tiles: no split
+    scratch = torch.empty(need, dtype=torch.uint8, device="cuda")
+    new = lambda: torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+    a, b, c, d = new(), new(), new(), new()
+    tm.tm_op_linear_dgrad_ws(BF16, T, N, K, dyd, wd, a, scratch, need, s)
+    tm.tm_op_linear_dgrad_ws(BF16, T, N, K, dyd, wd, b, scratch, need, s)
+    tm.tm_op_linear_dgrad_ws(BF16, T, N, K, dyd, wd, c, None, 0, s)
+    tm.tm_op_linear_dgrad(BF16, T, N, K, dyd, wd, d, s)
+    torch.cuda.synchronize()
+    ref = dy.astype(np.float64) @ w.astype(np.float64)
+    assert rel_err(to_host(a), ref) <= TOL_BF16 and rel_err(to_host(d), ref) <= TOL_BF16
+    assert torch.equal(a, b) and torch.equal(c, d)
+
+
 def test_gradient_overwrite_mode_ignores_old_contents(env):
     torch, tm = env
     rng = np.random.default_rng(4)

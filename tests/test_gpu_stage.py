@@ -232,3 +232,6 @@ def test_init_rejects_bad_buffers_and_shapes(env):
     with pytest.raises(tm.TmError) as e:
         tm.tm_stage_init(cfg.replace(n_q_heads=3), buf, buf, buf, buf, buf, ws)
     assert e.value.code == tm.TM_ESIZE
+    with pytest.raises(tm.TmError) as e:                               # a workspace one byte short
+        tm.tm_stage_init(cfg, buf, buf, buf, buf, buf, ws, workspace_bytes=ws.numel() - 1)
+    assert e.value.code == tm.TM_ESIZE
