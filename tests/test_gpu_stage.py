@@ -179,6 +179,27 @@ def test_backward_with_overlapped_optimizer_equals_the_two_calls(env):
     b.close()
 
 
+def test_backward_on_one_stream_equals_backward_on_two(env, monkeypatch):
+    """The weight-gradient products on the internal second stream (default) against everything on the
+    caller's stream (TM_BWD_ONE_STREAM): same bits."""
+    torch, tm = env
+    cfg = SMALL_GPT.replace(n_layers=3)
+    flat = si.make_flat_params(cfg)
+    x, dy = to_dev(torch, si.make_x(cfg), cfg.dtype), to_dev(torch, si.make_dy(cfg), cfg.dtype)
+    a, b = GpuStage(torch, tm, cfg, flat), GpuStage(torch, tm, cfg, flat)
+    a.fwd(x)
+    a.bwd(dy)
+    torch.cuda.synchronize()
+    monkeypatch.setenv("TM_BWD_ONE_STREAM", "1")
+    b.fwd(x)
+    b.bwd(dy)
+    torch.cuda.synchronize()
+    monkeypatch.delenv("TM_BWD_ONE_STREAM")
+    assert torch.equal(a.grads, b.grads) and torch.equal(a.dx, b.dx)
+    a.close()
+    b.close()
+
+
 def test_two_runs_are_bit_identical(env):
     torch, tm = env
     cfg = SMALL_LLAMA
