@@ -13,9 +13,11 @@
 //     [k][rows], i.e. the global layout; MFMA fragments come from the transposing LDS read
 //     ds_read_b64_tr_b16, which hands each lane four consecutive k of one row.  No transposed copies
 //     in HBM, no register shuffles.
-// Loads run one step ahead; one barrier per step, placed before the LAST 16-wide slice of the step so
-// that the LDS reads and the global loads that follow it overlap that slice's MFMAs; the waits on the
-// loads are explicit (s_waitcnt vmcnt), since the compiler does not track the LDS side of these loads.
+// The loads of step k+2 are issued during step k; one barrier per step, placed before the LAST 16-wide
+// slice of the step so that the LDS reads and the global loads that follow it overlap that slice's MFMAs;
+// the waits on the loads are explicit (s_waitcnt vmcnt), since the compiler does not track the LDS side of
+// these loads.  With a grid of several block rows the kernel splits the reduction: block row y takes
+// the y-th part of K and writes the y-th fp32 result (added up by the caller).
 // What bounds the kernel is the path from L2 into LDS (about 50 bytes per clock and compute unit, and
 // only whole 128-byte lines count: hence 64-element steps) together with the LDS reads, so the tile
 // shapes trade traffic per flop against how evenly the tiles fill the 256 compute units.
@@ -32,7 +34,8 @@
 // Epilogue.  bf16 results: the MFMA operands are passed swapped, so an accumulator tile is C^T and every
 // lane owns four consecutive output columns of one row; the block's tile is assembled in LDS and leaves
 // as whole rows (16 bytes per lane), a residual operand arrives the same way.  fp32 results: natural
-// orientation, a store instruction writes two whole 128-byte lines, streamed past the caches.
+// orientation, a store instruction writes two whole 128-byte lines, streamed past the caches.  (The staged
+// kernel stores its bf16 results straight from the accumulators.)
 //
 // Block index -> tile mapping: consecutive hardware block ids land on different XCDs (8 per chip,
 // each with its own L2); ids are re-numbered so that every XCD works on a contiguous range of
