@@ -33,8 +33,10 @@ Pins (tests/test_oracle_pins.py): central finite differences for every
 gradient, an independent pure-loop evaluation on tiny shapes, softmax row sums
 and causal zeros, closed-form attention cases, tensor-parallel re-assembly
 into the unsharded layer, closed-form Adam steps, hand-picked bf16 rounding
-patterns.  End-to-end values at the large presets have no external pin beyond
-those (the paper prints no numbers for this path).
+patterns; for the multi-micro-batch iteration: additivity of the gradients,
+hand-computed clipping factors, the slices tiling the state exactly once.
+End-to-end values at the large presets have no external pin beyond those (the
+paper prints no numbers for this path).
 """
 from __future__ import annotations
 
@@ -340,6 +342,66 @@ def adam_step(p, g, m, v, step: int, lr: float, beta1: float, beta2: float, eps:
     vhat = v / (1.0 - beta2 ** step)
     p = p - lr * (mhat / (np.sqrt(vhat) + eps) + weight_decay * p)
     return p, m, v
+
+
+# ----------------------------------------------------------------------------
+# A whole iteration as the paper's default profiles run it (section 8.1): several
+# micro-batches whose gradients add up, gradient-norm clipping, and the optimizer
+# step on this data-parallel rank's share of the state (distributed optimizer)
+# ----------------------------------------------------------------------------
+def grad_sq_sum(flat_grads: np.ndarray) -> float:
+    """Sum of squares of a gradient vector (this rank's contribution to the squared global norm; the
+    sum over ranks that would follow is served locally, i.e. it is the identity here)."""
+    g = np.asarray(flat_grads, F64)
+    return float(np.dot(g, g))
+
+
+def clip_scale(sq_sum: float, max_norm: float, eps: float = 1e-6) -> float:
+    """Factor that brings a gradient of squared norm sq_sum down to norm max_norm: min(1, c / (|g| + eps)).
+    (Clipping by global norm; the paper does not restate the rule, this is the usual one with the small
+    constant in the denominator.)  max_norm <= 0 switches clipping off."""
+    if max_norm <= 0.0:
+        return 1.0
+    return min(1.0, max_norm / (float(np.sqrt(sq_sum)) + eps))
+
+
+def optimizer_slice(n: int, dp: int, rank: int):
+    """[first, first+count) of the flat state that data-parallel rank `rank` of `dp` updates: equal
+    contiguous shares of ceil(n / dp) rounded up to 8 elements, the last one short."""
+    share = -(-n // dp)
+    share = -(-share // 8) * 8
+    first = min(n, rank * share)
+    return first, min(n, first + share) - first
+
+
+def accumulate_micro_batches(cfg, layers, xs, dys):
+    """Forward and backward over every micro-batch (xs[i], dys[i]); the parameter gradients add up.
+    Returns (list of y, list of dx, per-layer gradient dicts)."""
+    ys, dxs, total = [], [], None
+    for x, dy in zip(xs, dys):
+        y, stashes = stage_fwd(cfg, layers, x)
+        dx, grads = stage_bwd(cfg, layers, stashes, dy)
+        ys.append(y)
+        dxs.append(dx)
+        if total is None:
+            total = grads
+        else:
+            total = [{k: total[l][k] + grads[l][k] for k in grads[l]} for l in range(len(grads))]
+    return ys, dxs, total
+
+
+def iteration_update(p, g, m, v, step: int, hp: Dict[str, float], max_norm: float, n_micro: int, dp: int, rank: int):
+    """Optimizer part of the iteration on flat fp64 vectors: the accumulated gradient g is averaged over
+    the n_micro micro-batches and clipped by its global norm (both as ONE factor handed to Adam), and only
+    this rank's slice of p, m, v changes.  Returns (p, m, v, factor, first, count)."""
+    p, g, m, v = (np.array(t, F64) for t in (p, g, m, v))
+    avg = 1.0 / n_micro
+    factor = avg * clip_scale(grad_sq_sum(g) * avg * avg, max_norm)
+    first, count = optimizer_slice(p.size, dp, rank)
+    sl = slice(first, first + count)
+    p[sl], m[sl], v[sl] = adam_step(p[sl], g[sl], m[sl], v[sl], step, hp["lr"], hp["beta1"], hp["beta2"], hp["eps"],
+                                    hp.get("weight_decay", 0.0), factor)
+    return p, m, v, factor, first, count
 
 
 def bf16_round_nearest_even(a: np.ndarray) -> np.ndarray:

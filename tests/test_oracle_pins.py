@@ -401,3 +401,60 @@ def test_input_recipe_is_seeded_and_matches_inventory():
     assert (si.from_bf16_bits(si.bf16_bits(bf["w_qkv"])) == bf["w_qkv"]).all()
     x = si.make_x(cfg)
     assert x.shape == (128, 2, 256) and abs(float(x.std()) - 1.0) < 0.01
+
+
+# ----------------------------------------------------------------------------- whole iteration (section 8.1 profiles)
+def test_micro_batch_gradients_add_and_equal_one_concatenated_batch():
+    """Two micro-batches of one entry each give the same parameter gradients as one micro-batch holding both
+    entries (entries are independent and gradients are sums over tokens), and the same outputs per entry."""
+    cfg = si.PRESETS["tiny"].replace(n_layers=1, seq=6, hidden=16, n_q_heads=2, n_kv_heads=2, head_dim=8, ffn=24,
+                                     micro_batch=1)
+    layers = [si.make_layer_params(cfg, 0)]
+    xs = [si.make_x(cfg, seed=s) for s in (5, 6)]
+    dys = [si.make_dy(cfg, seed=s) for s in (5, 6)]
+    ys, dxs, total = so.accumulate_micro_batches(cfg, layers, xs, dys)
+    both = cfg.replace(micro_batch=2)
+    xb = np.concatenate(xs, axis=1)
+    dyb = np.concatenate(dys, axis=1)
+    y, st = so.stage_fwd(both, layers, xb)
+    dx, grads = so.stage_bwd(both, layers, st, dyb)
+    assert np.allclose(np.concatenate(ys, axis=1), y, rtol=0, atol=1e-12)
+    assert np.allclose(np.concatenate(dxs, axis=1), dx, rtol=0, atol=1e-12)
+    for k in grads[0]:
+        assert np.allclose(total[0][k], grads[0][k], rtol=1e-12, atol=1e-15), k
+
+
+def test_clipping_factor_by_hand():
+    assert so.grad_sq_sum(np.array([3.0, -4.0])) == 25.0
+    assert so.clip_scale(25.0, 10.0) == 1.0                      # norm 5 under the limit
+    assert abs(so.clip_scale(25.0, 1.0) - 1.0 / (5.0 + 1e-6)) < 1e-15
+    assert so.clip_scale(25.0, 0.0) == 1.0                       # switched off
+    g = np.array([3.0, -4.0]) * so.clip_scale(25.0, 1.0)
+    assert abs(np.sqrt(so.grad_sq_sum(g)) - 1.0) < 1e-6          # the clipped gradient has the limit as its norm
+
+
+def test_optimizer_slices_tile_the_state_once():
+    for n, dp in ((100, 3), (96, 3), (7, 8), (1 << 20, 7), (2718922752, 3)):
+        covered = 0
+        for r in range(dp):
+            first, count = so.optimizer_slice(n, dp, r)
+            assert first == covered or count == 0
+            assert count == 0 or first % 8 == 0
+            covered += count
+        assert covered == n
+
+
+def test_iteration_update_touches_only_its_slice_and_folds_both_factors():
+    rng = np.random.default_rng(3)
+    n = 50
+    p, g, m = rng.standard_normal(n), rng.standard_normal(n), rng.standard_normal(n) * 0.1
+    v = rng.random(n) * 0.01
+    hp = dict(lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8)
+    p2, m2, v2, factor, first, count = so.iteration_update(p, g, m, v, 4, hp, max_norm=0.5, n_micro=2, dp=3, rank=1)
+    assert (first, count) == (24, 24)
+    norm_avg = np.sqrt(np.sum((g / 2) ** 2))
+    assert abs(factor - 0.5 * 0.5 / (norm_avg + 1e-6)) < 1e-15   # 1/n_micro times c / (norm of the average + eps)
+    keep = np.r_[0:24, 48:50]
+    assert np.array_equal(p2[keep], p[keep]) and np.array_equal(m2[keep], m[keep]) and np.array_equal(v2[keep], v[keep])
+    pe, me, ve = so.adam_step(p[24:48], g[24:48] * factor, m[24:48], v[24:48], 4, **hp)
+    assert np.allclose(p2[24:48], pe, rtol=0, atol=1e-15) and np.allclose(m2[24:48], me) and np.allclose(v2[24:48], ve)
