@@ -17,6 +17,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -108,6 +109,11 @@ def main() -> int:
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 4 GiB device copy before the timed region (reference reading "
                          "for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
+    ap.add_argument("--micro-batches", type=int, default=0,
+                    help="also time a whole iteration of this many micro-batches (gradient accumulation, squared "
+                         "gradient norm, clipping factor on the host, Adam on one data-parallel rank's slice)")
+    ap.add_argument("--dp", type=int, default=1, help="data-parallel size for --micro-batches (Adam updates 1/dp)")
+    ap.add_argument("--clip", type=float, default=1.0, help="gradient-norm limit for --micro-batches (0: off)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's stage shard; this build has no multi-GPU path "
@@ -304,6 +310,37 @@ def main() -> int:
         "profiled_ms_per_step": round(prof_ms_step, 4),
         "roofline": roofline, "roofline_mfma": roofline_mfma, "kernels": kernels[:14],
     }
+    if args.micro_batches > 0:
+        # the iteration of the paper's default profiles (section 8.1): n micro-batches, one optimizer step on 1/dp
+        nmb, dp = args.micro_batches, max(1, args.dp)
+        share = -(-(-(-n // dp)) // 8) * 8
+        first, count = 0, min(n, share)
+        sq = torch.zeros(1, dtype=torch.float64, device="cuda")
+
+        def iteration():
+            step_no[0] += 1
+            for i in range(nmb):
+                tm.tm_stage_grad_mode(h, i == 0)
+                tm.tm_stage_fwd(h, x, y, stream)
+                tm.tm_stage_bwd(h, dy, dx, stream)
+            tm.tm_stage_grad_sq_sum(h, sq, stream)
+            norm = math.sqrt(float(sq.item())) / nmb          # the host waits here, as a training loop does
+            factor = (1.0 / nmb) * (min(1.0, args.clip / (norm + 1e-6)) if args.clip > 0 else 1.0)
+            tm.tm_adam_step_range(h, first, count, tm.make_hparams(**{**si.ADAM_DEFAULTS, "grad_scale": factor}),
+                                  step_no[0], stream)
+
+        iteration()
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for _ in range(max(1, args.steps // 2)):
+            iteration()
+        torch.cuda.synchronize()
+        it_ms = (time.time() - t0) * 1e3 / max(1, args.steps // 2)
+        out["iteration"] = {"micro_batches": nmb, "dp": dp, "clip": args.clip, "ms": round(it_ms, 3),
+                            "tokens_per_s": round(nmb * tokens / (it_ms * 1e-3), 1),
+                            "tflops_whole_iteration": round(nmb * flops / (it_ms * 1e-3) / 1e12, 1),
+                            "note": "host wall clock; gradient accumulation from the second micro-batch on"}
+        tm.tm_stage_grad_mode(h, True)
     tm.tm_stage_destroy(h)
     if not args.no_cpu_baseline:
         del master, params, grads, m, v, ws

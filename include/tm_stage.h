@@ -200,6 +200,33 @@ int tm_stage_bwd_adam(tm_stage_t *st, const void *dy, void *dx, const tm_adam_hp
                       int64_t step, void *stream);
 
 /*
+ * Pieces of a whole iteration as the paper's default profiles run it (section
+ * 8.1: several micro-batches per iteration, distributed optimizer): after the
+ * micro-batches' backward passes have added up in buffers.grads,
+ *   tm_stage_grad_sq_sum  writes the sum of squares of all gradients of this
+ *       rank (its contribution to the squared global norm; the sum over ranks
+ *       is served locally) to out[0], a DEVICE double; fixed summation order;
+ *       uses the workspace's scratch, so not between a forward pass and its
+ *       backward pass's use of that scratch: call it after tm_stage_bwd;
+ *   the caller forms hp->grad_scale from it (1/micro-batches times the clipping
+ *       factor min(1, c / (norm + 1e-6)));
+ *   tm_adam_step_range  updates elements [first, first+count) of the flat
+ *       state only: this data-parallel rank's share under a distributed
+ *       optimizer (first a multiple of 8; TM_EINVAL outside the state).
+ */
+int tm_stage_grad_sq_sum(tm_stage_t *st, double *out, void *stream);
+int tm_adam_step_range(tm_stage_t *st, int64_t first, int64_t count, const tm_adam_hparams_t *hp,
+                       int64_t step, void *stream);
+
+/*
+ * Sum of squares of n fp32 values (16-byte aligned) into out[0] (device
+ * double), two passes in a fixed order; scratch: tm_sq_sum_scratch_bytes(n)
+ * bytes, 8-byte aligned.
+ */
+int64_t tm_sq_sum_scratch_bytes(int64_t n);
+int tm_sq_sum(int64_t n, const float *g, void *scratch, double *out, void *stream);
+
+/*
  * The same update on bare flat device arrays of n elements (p, m, v updated in
  * place; g read, and cleared if hp->zero_grads; p_bf16 may be NULL).  This is
  * what a distributed-optimizer rank would call on its slice.  Pointers must be

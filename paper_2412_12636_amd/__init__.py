@@ -61,6 +61,10 @@ EXPORTS = {
     "tm_stage_fwd": (C.c_int, [C.c_void_p] * 4),
     "tm_stage_bwd": (C.c_int, [C.c_void_p] * 4),
     "tm_adam_step": (C.c_int, [C.c_void_p, C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
+    "tm_stage_grad_sq_sum": (C.c_int, [C.c_void_p] * 3),
+    "tm_adam_step_range": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
+    "tm_sq_sum_scratch_bytes": (C.c_int64, [C.c_int64]),
+    "tm_sq_sum": (C.c_int, [C.c_int64] + [C.c_void_p] * 4),
     "tm_stage_bwd_adam": (C.c_int, [C.c_void_p] * 3 + [C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
     "tm_adam_step_flat": (C.c_int, [C.c_int64] + [C.c_void_p] * 5 + [C.POINTER(tm_adam_hparams_t), C.c_int64,
                                                                        C.c_void_p]),
@@ -182,6 +186,22 @@ def tm_stage_bwd(handle: int, dy_in, dx_out, stream: int = 0) -> None:
 
 def tm_stage_bwd_adam(handle: int, dy_in, dx_out, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:
     _check(lib().tm_stage_bwd_adam(handle, _ptr(dy_in), _ptr(dx_out), C.byref(hp), step, stream))
+
+
+def tm_stage_grad_sq_sum(handle: int, out, stream: int = 0) -> None:
+    _check(lib().tm_stage_grad_sq_sum(handle, _ptr(out), stream))
+
+
+def tm_adam_step_range(handle: int, first: int, count: int, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:
+    _check(lib().tm_adam_step_range(handle, first, count, C.byref(hp), step, stream))
+
+
+def tm_sq_sum_scratch_bytes(n: int) -> int:
+    return _check(lib().tm_sq_sum_scratch_bytes(n))
+
+
+def tm_sq_sum(n: int, g, scratch, out, stream: int = 0) -> None:
+    _check(lib().tm_sq_sum(n, _ptr(g), _ptr(scratch), _ptr(out), stream))
 
 
 def tm_adam_step(handle: int, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:

@@ -282,6 +282,71 @@ extern "C" int tm_op_rotary(int dtype, int64_t seq, int64_t batch, int64_t n_hea
   return check_launch("rotary");
 }
 
+// ---- squared norm of a gradient vector ------------------------------------------------------------
+// Two passes in a fixed order (reproducible): a block squares and adds 4096 consecutive elements (fp32 per
+// thread over its 16, fp64 from there on) and writes one partial; one block adds the partials.
+namespace tmk {
+constexpr int kSqBlockElems = 4096;
+
+__device__ __forceinline__ double block_sum_f64(double x, double *red) {  // 256 or 1024 threads; result in thread 0
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, kWave);
+  const int w = threadIdx.x / kWave, l = threadIdx.x % kWave, nw = blockDim.x / kWave;
+  if (l == 0) red[w] = x;
+  __syncthreads();
+  double s = 0.0;
+  if (threadIdx.x == 0)
+    for (int i = 0; i < nw; ++i) s += red[i];
+  return s;
+}
+
+__global__ __launch_bounds__(256) void sq_sum_partial_kernel(const float *__restrict__ g, int64_t n, double *__restrict__ part) {
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+  __shared__ double red[4];
+  const int64_t base = (int64_t)blockIdx.x * kSqBlockElems;
+  float acc = 0.f;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const int64_t i = base + (u * 256 + threadIdx.x) * 4;
+    if (i + 4 <= n) {
+      const f32x4 v = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g + i));
+      acc += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+    } else {
+      for (int64_t j = i; j < n; ++j) acc += g[j] * g[j];
+    }
+  }
+  const double s = block_sum_f64((double)acc, red);
+  if (threadIdx.x == 0) part[blockIdx.x] = s;
+}
+
+__global__ __launch_bounds__(1024) void sq_sum_final_kernel(const double *__restrict__ part, int64_t nparts, double *__restrict__ out) {
+  __shared__ double red[16];
+  double acc = 0.0;
+  for (int64_t i = threadIdx.x; i < nparts; i += 1024) acc += part[i];
+  const double s = block_sum_f64(acc, red);
+  if (threadIdx.x == 0) out[0] = s;
+}
+}  // namespace tmk
+
+extern "C" int64_t tm_sq_sum_scratch_bytes(int64_t n) {
+  if (n < 0) return TM_EINVAL;
+  return ceil_div(n > 0 ? n : 1, (int64_t)kSqBlockElems) * (int64_t)sizeof(double);
+}
+
+extern "C" int tm_sq_sum(int64_t n, const float *g, void *scratch, double *out, void *stream) {
+  if (n < 0) return fail(TM_EINVAL, "sq_sum: negative length");
+  if (!g || !scratch || !out) return fail(TM_EINVAL, "sq_sum: NULL pointer");
+  if ((((uintptr_t)g) & 15) || (((uintptr_t)scratch) & 7) || (((uintptr_t)out) & 7))
+    return fail(TM_EALIGN, "sq_sum: g must be 16-byte, scratch and out 8-byte aligned");
+  const int64_t blocks = ceil_div(n > 0 ? n : 1, (int64_t)kSqBlockElems);
+  if (blocks > 0x7fffffffLL) return fail(TM_ESIZE, "sq_sum: vector too long");
+  hipStream_t s = (hipStream_t)stream;
+  g_last_kernel = "sq_sum_partial_kernel";
+  sq_sum_partial_kernel<<<(unsigned)blocks, 256, 0, s>>>(g, n, (double *)scratch);
+  sq_sum_final_kernel<<<1, 1024, 0, s>>>((const double *)scratch, blocks, out);
+  return check_launch("sq_sum");
+}
+
 extern "C" int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float *v, void *p_bf16,
                                  const tm_adam_hparams_t *hp, int64_t step, void *stream) {
   if (!hp || !p || !g || !m || !v) return fail(TM_EINVAL, "adam: NULL pointer");

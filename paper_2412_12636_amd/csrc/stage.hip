@@ -186,7 +186,8 @@ static Plan make_plan(const tm_stage_config_t *c) {
   p.dqkv = take(T * nqkv * es);
   p.dvec = take(tm_op_attn_bwd_scratch_bytes(c->dtype, c->seq, c->micro_batch, c->n_q_heads, c->n_kv_heads, c->head_dim));
   const int64_t widest = std::max(std::max(2 * h, f1), std::max(nqkv, h));
-  p.reduce = take(tm_op_reduce_scratch_bytes(T, widest));
+  const int64_t n_params = layer_offsets(c).total * c->n_layers;
+  p.reduce = take(std::max(tm_op_reduce_scratch_bytes(T, widest), tm_sq_sum_scratch_bytes(n_params)));
   p.splitk_bytes = 0;
   const int64_t lin[4][2] = {{nqkv, h}, {h, A}, {f1, h}, {h, f}};  // (N, K) of the four linear maps
   for (const auto &nk : lin)
@@ -671,6 +672,27 @@ extern "C" int tm_stage_bwd_adam(tm_stage_t *st, const void *dy_in, void *dx_out
                                  int64_t step, void *stream) {
   if (!hp) return fail(TM_EINVAL, "stage_bwd_adam: NULL hyper-parameters");
   return stage_bwd(st, dy_in, dx_out, stream, hp, step);
+}
+
+extern "C" int tm_stage_grad_sq_sum(tm_stage_t *st, double *out, void *stream) {
+  if (!st || !out) return fail(TM_EINVAL, "grad_sq_sum: NULL argument");
+  hipStream_t s = (hipStream_t)stream;
+  TM_STEP(0, 4.0 * (double)st->n_params,
+          tm_sq_sum(st->n_params, st->buf.grads, (char *)st->buf.workspace + st->plan.reduce, out, stream));
+  return TM_OK;
+}
+
+extern "C" int tm_adam_step_range(tm_stage_t *st, int64_t first, int64_t count, const tm_adam_hparams_t *hp,
+                                  int64_t step, void *stream) {
+  if (!st || !hp) return fail(TM_EINVAL, "adam_step_range: NULL argument");
+  if (first < 0 || count < 0 || first + count > st->n_params)
+    return fail(TM_EINVAL, "adam_step_range: [%lld, %lld) is outside the %lld parameters", (long long)first,
+                (long long)(first + count), (long long)st->n_params);
+  if (first % 8) return fail(TM_EALIGN, "adam_step_range: the first element must be a multiple of 8");
+  hipStream_t s = (hipStream_t)stream;
+  const double per_param = 28.0 + (st->cfg.dtype == TM_DTYPE_BF16 ? 2.0 : 0.0) + (hp->zero_grads ? 4.0 : 0.0);
+  TM_STEP(0, per_param * (double)count, adam_slice(st, first, count, hp, step, s));
+  return TM_OK;
 }
 
 extern "C" int tm_adam_step(tm_stage_t *st, const tm_adam_hparams_t *hp, int64_t step, void *stream) {

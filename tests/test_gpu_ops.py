@@ -351,6 +351,22 @@ def test_adam_first_step_closed_form(env):
 
 
 # ------------------------------------------------------------------ argument errors
+@pytest.mark.parametrize("n", [1, 7, 4096, 4097, 1_000_003])
+def test_sum_of_squares(env, n):
+    torch, tm = env
+    rng = np.random.default_rng(n)
+    g = (rng.standard_normal(n) * 1e-2).astype(np.float32)
+    gd = f32_dev(torch, g)
+    scratch = torch.empty(tm.tm_sq_sum_scratch_bytes(n), dtype=torch.uint8, device="cuda")
+    out = torch.zeros(2, dtype=torch.float64, device="cuda")
+    tm.tm_sq_sum(n, gd, scratch, out, stream_ptr(torch))
+    tm.tm_sq_sum(n, gd, scratch, out[1:], stream_ptr(torch))
+    torch.cuda.synchronize()
+    ref = so.grad_sq_sum(g)
+    assert abs(float(out[0]) - ref) <= 1e-6 * ref
+    assert float(out[0]) == float(out[1])               # fixed summation order
+
+
 def test_bad_arguments_are_reported_not_launched(env):
     torch, tm = env
     t = torch.zeros(64, dtype=torch.float32, device="cuda")

@@ -200,6 +200,67 @@ def test_backward_on_one_stream_equals_backward_on_two(env, monkeypatch):
     b.close()
 
 
+@pytest.mark.parametrize("cfg", [SMALL_GPT, SMALL_LLAMA], ids=["small_gpt", "small_llama"])
+def test_whole_iteration_of_several_micro_batches(env, cfg):
+    """Three micro-batches (first stored, the others accumulated), the squared gradient norm, the clipping
+    factor and the Adam update of one data-parallel rank's slice, against the checker's whole iteration
+    (section 8.1 profiles: several micro-batches per iteration, distributed optimizer)."""
+    torch, tm = env
+    n_micro, dp, rank, max_norm = 3, 3, 1, 0.05
+    flat = si.make_flat_params(cfg)
+    layers = si.split_flat(cfg, flat)
+    xs = [si.make_x(cfg, seed=100 + i) for i in range(n_micro)]
+    dys = [si.make_dy(cfg, seed=100 + i) for i in range(n_micro)]
+    st = GpuStage(torch, tm, cfg, flat)
+    st.grads.fill_(float("nan"))                         # the first micro-batch must not read it
+    for i in range(n_micro):
+        tm.tm_stage_grad_mode(st.handle, i == 0)
+        st.fwd(to_dev(torch, xs[i], cfg.dtype))
+        st.bwd(to_dev(torch, dys[i], cfg.dtype))
+    sq = torch.zeros(1, dtype=torch.float64, device="cuda")
+    tm.tm_stage_grad_sq_sum(st.handle, sq, stream_ptr(torch))
+    torch.cuda.synchronize()
+    gpu_grads = st.grads.cpu().numpy().astype(np.float64)
+    _, _, rgrads = so.accumulate_micro_batches(cfg, layers, xs, dys)
+    ref_grads = flatten_grads(cfg, rgrads)
+    off = 0
+    for l in range(cfg.n_layers):
+        for name, shape in si.layer_inventory(cfg):
+            n = int(np.prod(shape))
+            assert rel_err(gpu_grads[off:off + n], ref_grads[off:off + n]) <= TOL_BF16, (l, name)
+            off += n
+    # the squared norm: tight against the GPU's own gradients, bf16-loose against the checker's
+    assert abs(float(sq.item()) - so.grad_sq_sum(gpu_grads)) <= 1e-6 * so.grad_sq_sum(gpu_grads)
+    assert abs(float(sq.item()) - so.grad_sq_sum(ref_grads)) <= 2 * TOL_BF16 * so.grad_sq_sum(ref_grads)
+    # the host forms the factor as the checker does; it clips in this set-up
+    factor = (1.0 / n_micro) * so.clip_scale(float(sq.item()) / n_micro ** 2, max_norm)
+    assert factor < 1.0 / n_micro
+    first, count = so.optimizer_slice(st.n, dp, rank)
+    hp_kw = {**si.ADAM_DEFAULTS, "grad_scale": factor}
+    before = {k: getattr(st, k).clone() for k in ("master", "m", "v", "params")}
+    tm.tm_adam_step_range(st.handle, first, count, tm.make_hparams(**hp_kw), 1, stream_ptr(torch))
+    torch.cuda.synchronize()
+    hp = {k: si.ADAM_DEFAULTS[k] for k in ("lr", "beta1", "beta2", "eps", "weight_decay")}
+    z = np.zeros(st.n)
+    rp, rm, rv, rfactor, rfirst, rcount = so.iteration_update(flat.astype(np.float64), gpu_grads, z, z, 1, hp, max_norm,
+                                                              n_micro, dp, rank)
+    assert (rfirst, rcount) == (first, count) and abs(rfactor - factor) <= 1e-9 * factor
+    assert rel_err(to_host(st.master), rp) <= TOL_ADAM
+    assert rel_err(to_host(st.m), rm) <= TOL_ADAM and rel_err(to_host(st.v), rv) <= TOL_ADAM
+    outside = torch.ones(st.n, dtype=torch.bool, device="cuda")
+    outside[first:first + count] = False
+    for k, old in before.items():                        # nothing outside the slice moved
+        assert torch.equal(getattr(st, k)[outside], old[outside]), k
+    assert not torch.equal(st.master[first:first + count], before["master"][first:first + count])
+    with pytest.raises(tm.TmError) as e:
+        tm.tm_adam_step_range(st.handle, 4, 8, tm.make_hparams(**hp_kw), 1, stream_ptr(torch))
+    assert e.value.code == tm.TM_EALIGN
+    with pytest.raises(tm.TmError) as e:
+        tm.tm_adam_step_range(st.handle, 0, st.n + 8, tm.make_hparams(**hp_kw), 1, stream_ptr(torch))
+    assert e.value.code == tm.TM_EINVAL
+    st.close()
+
+
 def test_two_runs_are_bit_identical(env):
     torch, tm = env
     cfg = SMALL_LLAMA
