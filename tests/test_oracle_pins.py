@@ -458,3 +458,115 @@ def test_iteration_update_touches_only_its_slice_and_folds_both_factors():
     assert np.array_equal(p2[keep], p[keep]) and np.array_equal(m2[keep], m[keep]) and np.array_equal(v2[keep], v[keep])
     pe, me, ve = so.adam_step(p[24:48], g[24:48] * factor, m[24:48], v[24:48], 4, **hp)
     assert np.allclose(p2[24:48], pe, rtol=0, atol=1e-15) and np.allclose(m2[24:48], me) and np.allclose(v2[24:48], ve)
+
+
+# ----------------------------------------------------------------------------- first / last stage layers (section 6.1)
+from oracle import roles_oracle as ro  # noqa: E402
+
+
+def _fd(f, a, eps=1e-6):
+    """Central finite-difference gradient of the scalar function f with respect to array a."""
+    g = np.zeros_like(a)
+    it = np.nditer(a, flags=["multi_index"])
+    for _ in it:
+        i = it.multi_index
+        old = a[i]
+        a[i] = old + eps
+        fp = f()
+        a[i] = old - eps
+        fm = f()
+        a[i] = old
+        g[i] = (fp - fm) / (2 * eps)
+    return g
+
+
+def test_embedding_is_a_row_lookup_and_its_gradient_a_one_hot_product():
+    rng = np.random.default_rng(1)
+    s, b, h, v_local, v0, n_pos = 5, 3, 4, 6, 10, 8
+    w, pos = rng.standard_normal((v_local, h)), rng.standard_normal((n_pos, h))
+    tokens = rng.integers(8, 18, size=(s, b))            # ids 8..17: some below, some inside 10..15, some above
+    assert ((tokens < v0).any() and (tokens >= v0 + v_local).any() and ((tokens >= v0) & (tokens < v0 + v_local)).any())
+    x0 = ro.embedding_fwd(tokens, w, v0, pos)
+    for i in range(s):
+        for n in range(b):
+            row = w[tokens[i, n] - v0] if v0 <= tokens[i, n] < v0 + v_local else 0.0
+            assert np.array_equal(x0[i, n], row + pos[i])
+    assert np.allclose(ro.embedding_fwd(tokens, w, v0, None), x0 - pos[:s, None, :], rtol=0, atol=1e-15)
+    dx0 = rng.standard_normal((s, b, h))
+    dw, dp = ro.embedding_bwd(dx0, tokens, v_local, v0, n_pos)
+    onehot = (tokens.reshape(-1, 1) - v0 == np.arange(v_local)[None, :]).astype(np.float64)   # [T, V_local]
+    assert np.allclose(dw, onehot.T @ dx0.reshape(-1, h), rtol=0, atol=1e-14)
+    assert np.allclose(dp[:s], dx0.sum(axis=1)) and not dp[s:].any()
+    assert ro.embedding_bwd(dx0, tokens, v_local, v0, 0)[1] is None
+    # gradient of a scalar function of x0 by finite differences
+    c = rng.standard_normal((s, b, h))
+    gw = _fd(lambda: float((ro.embedding_fwd(tokens, w, v0, pos) * c).sum()), w)
+    gp = _fd(lambda: float((ro.embedding_fwd(tokens, w, v0, pos) * c).sum()), pos)
+    dw2, dp2 = ro.embedding_bwd(c, tokens, v_local, v0, n_pos)
+    assert np.allclose(gw, dw2, atol=1e-8) and np.allclose(gp, dp2, atol=1e-8)
+
+
+def test_cross_entropy_closed_forms():
+    T, v_local, v0 = 4, 8, 16
+    targets = np.array([16, 23, 3, 40])                   # two inside the shard, one below, one above
+    const = np.full((T, v_local), 1.5)
+    loss_t, probs = ro.xent_fwd(const, targets, v0)
+    assert np.allclose(loss_t, [np.log(8), np.log(8), 1.5 + np.log(8), 1.5 + np.log(8)], rtol=0, atol=1e-14)
+    assert np.allclose(probs, 1.0 / 8)
+    big = np.zeros((T, v_local))
+    big[np.arange(T), [0, 7, 2, 5]] = 10.0                # one dominant logit per row; rows 0, 1 hit their target
+    loss_t, probs = ro.xent_fwd(big, targets, v0)
+    tail = np.log1p(7 * np.exp(-10.0))
+    assert np.allclose(loss_t[:2], tail, rtol=1e-9, atol=0) and np.allclose(loss_t[2:], 10.0 + tail, rtol=0, atol=1e-12)
+    assert np.allclose(probs.sum(axis=1), 1.0)
+    d = ro.xent_bwd(probs, targets, v0, np.ones(T))
+    assert np.allclose(d.sum(axis=1), [0.0, 0.0, 1.0, 1.0], atol=1e-14)   # rows with a local target sum to zero
+    shifted, _ = ro.xent_fwd(big + 123.0, targets, v0)    # a shift moves only the rows whose target is elsewhere
+    assert np.allclose(shifted[:2], loss_t[:2], atol=1e-9) and np.allclose(shifted[2:], loss_t[2:] + 123.0)
+
+
+def test_head_gradients_by_finite_differences():
+    rng = np.random.default_rng(2)
+    s, b, h, v_local, v0 = 3, 2, 6, 5, 7
+    for kind in (so.NORM_LAYERNORM, so.NORM_RMSNORM):
+        y = rng.standard_normal((s, b, h))
+        gain, offset = 1.0 + 0.1 * rng.standard_normal(h), 0.1 * rng.standard_normal(h)
+        off = offset if kind == so.NORM_LAYERNORM else None
+        w = 0.5 * rng.standard_normal((v_local, h))
+        targets = rng.integers(5, 14, size=(s, b))        # ids 5..13 against the shard 7..11
+        loss, st = ro.head_fwd(kind, 1e-5, y, gain, off, w, targets, v0)
+        dy, dgain, doffset, dw = ro.head_bwd(kind, st, gain, w, targets, v0)
+        f = lambda: ro.head_fwd(kind, 1e-5, y, gain, off, w, targets, v0)[0]
+        assert np.allclose(_fd(f, y), dy, atol=1e-8)
+        assert np.allclose(_fd(f, gain), dgain, atol=1e-8)
+        assert np.allclose(_fd(f, w), dw, atol=1e-8)
+        if kind == so.NORM_LAYERNORM:
+            assert np.allclose(_fd(f, offset), doffset, atol=1e-8)
+        else:
+            assert doffset is None
+        # a loss gradient of 2 doubles everything
+        dy2, _, _, dw2 = ro.head_bwd(kind, st, gain, w, targets, v0, dloss=2.0)
+        assert np.allclose(dy2, 2 * dy) and np.allclose(dw2, 2 * dw)
+
+
+def test_vocabulary_shards_reassemble_the_full_embedding_and_the_full_softmax_pieces():
+    """Summing the ranks' embedding outputs gives the full-table lookup; the ranks' sum-exp and target-logit
+    pieces add up to the full cross-entropy (what the served-locally all-reduces would have combined)."""
+    rng = np.random.default_rng(4)
+    s, b, h, V, tp = 4, 2, 3, 12, 3
+    table = rng.standard_normal((V, h))
+    tokens = rng.integers(0, V, size=(s, b))
+    full = ro.embedding_fwd(tokens, table, 0, None)
+    parts = sum(ro.embedding_fwd(tokens, table[r * 4:(r + 1) * 4], r * 4, None) for r in range(tp))
+    assert np.array_equal(full, parts)
+    logits = rng.standard_normal((s * b, V))
+    targets = rng.integers(0, V, size=s * b)
+    full_loss, _ = ro.xent_fwd(logits, targets, 0)
+    sumexp, picked = np.zeros(s * b), np.zeros(s * b)
+    for r in range(tp):
+        lt, _ = ro.xent_fwd(logits[:, r * 4:(r + 1) * 4], targets, r * 4)
+        inside = (targets >= r * 4) & (targets < r * 4 + 4)
+        lse_r = lt + np.where(inside, logits[np.arange(s * b), targets], 0.0)
+        sumexp += np.exp(lse_r)
+        picked += np.where(inside, logits[np.arange(s * b), targets], 0.0)
+    assert np.allclose(np.log(sumexp) - picked, full_loss, atol=1e-12)
