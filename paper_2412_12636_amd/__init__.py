@@ -86,6 +86,12 @@ EXPORTS = {
     "tm_op_act_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 3),
     "tm_op_act_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 4),
     "tm_op_rotary": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_double, C.c_int, C.c_void_p, C.c_void_p]),
+    "tm_op_embed_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 5),
+    "tm_op_embed_bwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 4 + [C.c_int64, C.c_int, C.c_void_p]),
+    "tm_op_xent": (C.c_int, [C.c_int] + [C.c_int64] * 3 + [C.c_void_p] * 2 + [C.c_double] + [C.c_void_p] * 3),
+    "tm_head_workspace_bytes": (C.c_int64, [C.c_int] + [C.c_int64] * 4),
+    "tm_head_fwd_bwd": (C.c_int, [C.c_int, C.c_int, C.c_double] + [C.c_int64] * 5 + [C.c_void_p] * 5 + [C.c_double, C.c_void_p,
+                                 C.c_int64] + [C.c_void_p] * 5 + [C.c_int, C.c_void_p]),
     "tm_op_attn_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 4),
     "tm_op_attn_bwd_scratch_bytes": (C.c_int64, [C.c_int] + [C.c_int64] * 5),
     "tm_op_attn_bwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 7),
@@ -304,3 +310,29 @@ def tm_op_attn_bwd_scratch_bytes(dtype, seq, batch, nq, nkv, d) -> int:
 def tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, qkv, ctx, dctx, lse, scratch, dqkv, stream=0):
     _check(lib().tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, _ptr(qkv), _ptr(ctx), _ptr(dctx), _ptr(lse),
                                 _ptr(scratch), _ptr(dqkv), stream))
+
+
+def tm_op_embed_fwd(dtype, seq, batch, h, v_local, v0, tokens, w, pos_emb, x0, stream=0):
+    _check(lib().tm_op_embed_fwd(dtype, seq, batch, h, v_local, v0, _ptr(tokens), _ptr(w), _ptr(pos_emb), _ptr(x0), stream))
+
+
+def tm_op_embed_bwd(dtype, seq, batch, h, v_local, v0, tokens, dx0, dw, dpos, n_pos, accumulate=1, stream=0):
+    _check(lib().tm_op_embed_bwd(dtype, seq, batch, h, v_local, v0, _ptr(tokens), _ptr(dx0), _ptr(dw), _ptr(dpos), n_pos,
+                                 accumulate, stream))
+
+
+def tm_op_xent(dtype, T, v_local, v0, logits, targets, dloss, loss_t, loss, stream=0):
+    _check(lib().tm_op_xent(dtype, T, v_local, v0, _ptr(logits), _ptr(targets), dloss, _ptr(loss_t), _ptr(loss), stream))
+
+
+def tm_head_workspace_bytes(dtype, seq, batch, h, v_local) -> int:
+    return _check(lib().tm_head_workspace_bytes(dtype, seq, batch, h, v_local))
+
+
+def tm_head_fwd_bwd(dtype, norm, eps, seq, batch, h, v_local, v0, y, targets, gain, offset, w, dloss, workspace, loss, dy,
+                    dgain, doffset, dw, accumulate=1, stream=0, workspace_bytes=None):
+    if workspace_bytes is None:
+        workspace_bytes = int(workspace.numel()) * int(workspace.element_size())
+    _check(lib().tm_head_fwd_bwd(dtype, norm, eps, seq, batch, h, v_local, v0, _ptr(y), _ptr(targets), _ptr(gain), _ptr(offset),
+                                 _ptr(w), dloss, _ptr(workspace), workspace_bytes, _ptr(loss), _ptr(dy), _ptr(dgain),
+                                 _ptr(doffset), _ptr(dw), accumulate, stream))

@@ -22,7 +22,9 @@ def tm():
 
 def declared_symbols():
     names = set()
-    for hdr in ("tm_stage.h", "tm_ops.h"):
+    for hdr in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if not hdr.endswith(".h"):
+            continue
         text = open(os.path.join(ROOT, "include", hdr)).read()
         text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
         names |= set(re.findall(r"\b(tm_[a-z0-9_]+)\s*\(", text))
