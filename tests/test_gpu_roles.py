@@ -136,3 +136,67 @@ def test_last_stage_forward_and_backward(env, dtype, norm, seq, batch, h, v_loca
     with pytest.raises(tm.TmError) as e:
         tm.tm_head_fwd_bwd(*args, accumulate=0, stream=s, workspace_bytes=ws.numel() - 1)
     assert e.value.code == tm.TM_ESIZE
+
+
+def test_last_stage_at_the_175b_shard_width(env):
+    """hidden 12288, 2048 tokens, 6400 vocabulary rows per rank (51200 / 8): loss, sampled rows of dy and of
+    dW, and the norm-gain gradient, against the checker (which forms the full logits once)."""
+    torch, tm = env
+    seq, batch, h, v_local, v0 = 2048, 1, 12288, 6400, 12800
+    T = seq * batch
+    print(f"last stage full width: T={T} h={h} v_local={v_local}", flush=True)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+
+    def draw(shape, std, mean=0.0):
+        return torch.empty(shape, dtype=torch.float32, device="cuda").normal_(mean, std, generator=gen).to(torch.bfloat16)
+
+    y, gain, offset, w = draw((seq, batch, h), 1.0), draw((h,), 0.02, 1.0), draw((h,), 0.02), draw((v_local, h), 0.02)
+    targets = torch.randint(0, 51200, (T,), generator=gen, device="cuda", dtype=torch.int32)
+    targets[:T // 2] = torch.randint(v0, v0 + v_local, (T // 2,), generator=gen, device="cuda", dtype=torch.int32)
+    s = stream_ptr(torch)
+    ws = torch.empty(tm.tm_head_workspace_bytes(BF16, seq, batch, h, v_local), dtype=torch.uint8, device="cuda")
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    dy = torch.empty_like(y)
+    dgain = torch.empty(h, dtype=torch.float32, device="cuda")
+    doffset = torch.empty(h, dtype=torch.float32, device="cuda")
+    dw = torch.empty((v_local, h), dtype=torch.float32, device="cuda")
+    tm.tm_head_fwd_bwd(BF16, so.NORM_LAYERNORM, 1e-5, seq, batch, h, v_local, v0, y, targets, gain, offset, w, 1.0, ws, loss,
+                       dy, dgain, doffset, dw, accumulate=0, stream=s)
+    torch.cuda.synchronize()
+    yh, gh, oh, wh = (to_host(t) for t in (y, gain, offset, w))
+    th = targets.cpu().numpy().reshape(seq, batch)
+    rloss, st = ro.head_fwd(so.NORM_LAYERNORM, 1e-5, yh, gh, oh, wh, th, v0)
+    rdy, rdgain, rdoffset, rdw = ro.head_bwd(so.NORM_LAYERNORM, st, gh, wh, th, v0)
+    print(f"  loss gpu {float(loss):.6f} checker {rloss:.6f}", flush=True)
+    assert abs(float(loss) - rloss) <= 2e-3 * abs(rloss)
+    rows = np.random.default_rng(5).choice(T, 48, replace=False)
+    vrows = np.random.default_rng(6).choice(v_local, 48, replace=False)
+    dyh = to_host(dy).reshape(T, h)
+    assert rel_err(dyh[rows], rdy.reshape(T, h)[rows]) <= TOL_BF16
+    assert rel_err(to_host(dw[torch.from_numpy(vrows).cuda()]), rdw[vrows]) <= TOL_BF16
+    assert rel_err(to_host(dgain), rdgain) <= TOL_BF16 and rel_err(to_host(doffset), rdoffset) <= TOL_BF16
+    assert bool(torch.isfinite(dy.float()).all()) and bool(torch.isfinite(dw).all())
+
+
+def test_embedding_at_the_175b_shard_width(env):
+    torch, tm = env
+    seq, batch, h, v_local, v0 = 2048, 1, 12288, 6400, 12800
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(78)
+    w = torch.empty((v_local, h), dtype=torch.float32, device="cuda").normal_(0, 0.02, generator=gen).to(torch.bfloat16)
+    pos = torch.empty((seq, h), dtype=torch.float32, device="cuda").normal_(0, 0.02, generator=gen).to(torch.bfloat16)
+    dx0 = torch.empty((seq, batch, h), dtype=torch.float32, device="cuda").normal_(0, 0.01, generator=gen).to(torch.bfloat16)
+    tokens = torch.randint(v0 - 100, v0 + v_local + 100, (seq * batch,), generator=gen, device="cuda", dtype=torch.int32)
+    tokens[:64] = v0 + 5                                   # one row collects many tokens
+    s = stream_ptr(torch)
+    x0 = torch.empty((seq, batch, h), dtype=torch.bfloat16, device="cuda")
+    dw = torch.empty((v_local, h), dtype=torch.float32, device="cuda")
+    dp = torch.empty((seq, h), dtype=torch.float32, device="cuda")
+    tm.tm_op_embed_fwd(BF16, seq, batch, h, v_local, v0, tokens, w, pos, x0, s)
+    tm.tm_op_embed_bwd(BF16, seq, batch, h, v_local, v0, tokens, dx0, dw, dp, seq, 0, s)
+    torch.cuda.synchronize()
+    th = tokens.cpu().numpy().reshape(seq, batch)
+    assert rel_err(to_host(x0), ro.embedding_fwd(th, to_host(w), v0, to_host(pos))) <= TOL_BF16
+    rdw, rdp = ro.embedding_bwd(to_host(dx0), th, v_local, v0, seq)
+    assert rel_err(to_host(dw), rdw) <= 1e-5 and rel_err(to_host(dp), rdp) <= 1e-5
