@@ -97,6 +97,53 @@ def cpu_baseline(si, cfg, budget_s: float):
     }
 
 
+def time_roles(torch, tm, cfg, v_local: int, gen, stream: int, reps: int):
+    """The layers only the first and the last pipeline stage have, at the preset's width: embedding lookup and its
+    scatter-add backward; final norm + output layer + cross-entropy over the shard, forward and backward in one call."""
+    seq, batch, h = cfg.seq, cfg.micro_batch, cfg.hidden
+    T, v0 = seq * batch, 2 * v_local
+    td = torch.bfloat16
+
+    def draw(shape, std, mean=0.0):
+        return torch.empty(shape, dtype=torch.float32, device="cuda").normal_(mean, std, generator=gen).to(td)
+
+    w, pos, y, dx0 = draw((v_local, h), 0.02), draw((seq, h), 0.02), draw((seq, batch, h), 1.0), draw((seq, batch, h), 0.01)
+    gain, offset = draw((h,), 0.02, 1.0), draw((h,), 0.02)
+    tokens = torch.randint(0, 8 * v_local, (T,), generator=gen, device="cuda", dtype=torch.int32)
+    tokens[:T // 2] = torch.randint(v0, v0 + v_local, (T // 2,), generator=gen, device="cuda", dtype=torch.int32)
+    x0, dy = torch.empty_like(y), torch.empty_like(y)
+    dw = torch.empty((v_local, h), dtype=torch.float32, device="cuda")
+    dpos = torch.empty((seq, h), dtype=torch.float32, device="cuda")
+    dgain, doffset = (torch.empty(h, dtype=torch.float32, device="cuda") for _ in range(2))
+    loss = torch.empty(1, dtype=torch.float32, device="cuda")
+    ws = torch.empty(tm.tm_head_workspace_bytes(1, seq, batch, h, v_local), dtype=torch.uint8, device="cuda")
+    ln = cfg.norm == 0
+
+    def timed(fn):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_ef = timed(lambda: tm.tm_op_embed_fwd(1, seq, batch, h, v_local, v0, tokens, w, pos, x0, stream))
+    t_eb = timed(lambda: tm.tm_op_embed_bwd(1, seq, batch, h, v_local, v0, tokens, dx0, dw, dpos, seq, 0, stream))
+    t_head = timed(lambda: tm.tm_head_fwd_bwd(1, cfg.norm, cfg.norm_eps, seq, batch, h, v_local, v0, y, tokens, gain,
+                                              offset if ln else None, w, 1.0, ws, loss, dy, dgain, doffset if ln else None,
+                                              dw, 0, stream))
+    head_flops = 3 * 2.0 * T * v_local * h
+    return {"v_local": v_local, "tokens": T, "hidden": h,
+            "embed_fwd_ms": round(t_ef, 4), "embed_fwd_gbps": round((T * h * 2 * 3) / (t_ef * 1e-3) / 1e9, 1),
+            "embed_bwd_ms": round(t_eb, 4), "embed_bwd_gbps": round((T * h * 2 + (v_local + seq) * h * 4) / (t_eb * 1e-3) / 1e9, 1),
+            "head_fwd_bwd_ms": round(t_head, 4), "head_tflops": round(head_flops / (t_head * 1e-3) / 1e12, 1),
+            "note": "bytes: embedding forward reads a table row and a position row and writes x0 per token; backward reads "
+                    "dx0 once and writes both fp32 gradients once; head flops = 3 products of 2*T*v_local*h"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +161,9 @@ def main() -> int:
                          "gradient norm, clipping factor on the host, Adam on one data-parallel rank's slice)")
     ap.add_argument("--dp", type=int, default=1, help="data-parallel size for --micro-batches (Adam updates 1/dp)")
     ap.add_argument("--clip", type=float, default=1.0, help="gradient-norm limit for --micro-batches (0: off)")
+    ap.add_argument("--roles", type=int, default=0, metavar="V_LOCAL",
+                    help="also time the first- and last-stage layers at the preset's width with this many vocabulary "
+                         "rows per rank (e.g. 6400 = 51200 / 8)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU's stage shard; this build has no multi-GPU path "
@@ -341,6 +391,8 @@ def main() -> int:
                             "tflops_whole_iteration": round(nmb * flops / (it_ms * 1e-3) / 1e12, 1),
                             "note": "host wall clock; gradient accumulation from the second micro-batch on"}
         tm.tm_stage_grad_mode(h, True)
+    if args.roles > 0:
+        out["roles"] = time_roles(torch, tm, cfg, args.roles, gen, stream, max(3, args.steps))
     tm.tm_stage_destroy(h)
     if not args.no_cpu_baseline:
         del master, params, grads, m, v, ws

@@ -570,3 +570,117 @@ def test_vocabulary_shards_reassemble_the_full_embedding_and_the_full_softmax_pi
         sumexp += np.exp(lse_r)
         picked += np.where(inside, logits[np.arange(s * b), targets], 0.0)
     assert np.allclose(np.log(sumexp) - picked, full_loss, atol=1e-12)
+
+
+# ------------------------------------------------------------------ record / replay layer of the sandbox (section 4.2)
+from oracle import sandbox_oracle as sb  # noqa: E402
+
+
+@pytest.mark.parametrize("cfg", [TINY_GPT, TINY_LLAMA])
+def test_hooked_layer_with_no_peers_is_the_plain_layer(cfg):
+    cfg2 = cfg.replace(n_layers=2)
+    layers = [_params(cfg2), _params(cfg2)]
+    x = RNG.standard_normal((cfg.seq, cfg.micro_batch, cfg.hidden))
+    dy = RNG.standard_normal(x.shape)
+    y0, st0 = so.stage_fwd(cfg2, layers, x)
+    dx0, g0 = so.stage_bwd(cfg2, layers, st0, dy)
+    y1, st1 = sb.stage_fwd(cfg2, layers, x, sb.PassThrough())
+    dx1, g1 = sb.stage_bwd(cfg2, layers, st1, dy, sb.PassThrough())
+    assert np.abs(y0 - y1).max() <= 1e-13 and np.abs(dx0 - dx1).max() <= 1e-13
+    for a, b in zip(g0, g1):
+        for k in a:
+            assert np.abs(a[k] - b[k]).max() <= 1e-13, k
+
+
+def _tp_shards(full, p, n_ranks):
+    """Megatron split of one layer: heads / ffn columns over the ranks; norm parameters and the biases of the
+    row-parallel maps replicated (those biases are added once, after the all-reduce)."""
+    d, A = full.head_dim, full.attn_width
+    hpr, fpr = full.n_q_heads // n_ranks, full.ffn // n_ranks
+    out = []
+    for r in range(n_ranks):
+        heads = np.arange(r * hpr * d, (r + 1) * hpr * d)
+        rows = np.r_[heads, A + heads, 2 * A + heads]
+        cols = slice(r * fpr, (r + 1) * fpr)
+        ps = dict(p)
+        ps["w_qkv"], ps["b_qkv"] = p["w_qkv"][rows], p["b_qkv"][rows]
+        ps["w_out"] = p["w_out"][:, heads]
+        ps["w_fc1"], ps["b_fc1"] = p["w_fc1"][cols], p["b_fc1"][cols]
+        ps["w_fc2"] = p["w_fc2"][:, cols]
+        out.append(ps)
+    return out
+
+
+def test_replay_reproduces_a_rank_of_a_real_tensor_parallel_group():
+    """Two ranks run the hooked stage as a REAL group (their partial sums are added), rank 0 records every
+    scope.  The group's result is the unsharded layer's; rank 0 replaying ALONE gets its own outputs and
+    gradients of the group run bit for bit; with only the pipeline scope on the boundary and the tensor
+    scope left to its (absent) peers, it does not."""
+    import threading
+    full = si.StageConfig(2, 16, 4, 4, 4, 24, 6, 2, dtype=si.DTYPE_FP32)
+    shard = full.replace(n_q_heads=2, n_kv_heads=2, ffn=12)
+    layers_full = [_params(full), _params(full)]
+    per_rank = list(zip(*[_tp_shards(full, p, 2) for p in layers_full]))   # [rank][layer]
+    x = RNG.standard_normal((full.seq, full.micro_batch, full.hidden))
+    dy = RNG.standard_normal(x.shape)
+    group = sb.ThreadGroup(2)
+    rec = sb.Recorder(group.member(0), sb.SCOPE_TP | sb.SCOPE_PP)
+    comms = [rec, group.member(1)]
+    res = [None, None]
+
+    def run(r):
+        y, st = sb.stage_fwd(shard, per_rank[r], x, comms[r])
+        dx, gr = sb.stage_bwd(shard, per_rank[r], st, dy, comms[r])
+        res[r] = (y, dx, gr)
+
+    th = [threading.Thread(target=run, args=(r,)) for r in range(2)]
+    [t.start() for t in th]
+    [t.join(60) for t in th]
+    assert res[0] is not None and res[1] is not None
+    # the real group computes the unsharded stage
+    y_full, st_full = so.stage_fwd(full, layers_full, x)
+    dx_full, g_full = so.stage_bwd(full, layers_full, st_full, dy)
+    for r in range(2):
+        assert np.abs(res[r][0] - y_full).max() <= 1e-12 and np.abs(res[r][1] - dx_full).max() <= 1e-12
+    heads0 = np.arange(0, 2 * full.head_dim)
+    assert np.abs(res[0][2][1]["w_out"] - g_full[1]["w_out"][:, heads0]).max() <= 1e-12
+    assert np.abs(res[0][2][0]["w_fc1"] - g_full[0]["w_fc1"][:12]).max() <= 1e-12
+    # tape: recv x, 2 all-reduces per layer forward, recv dy, 2 per layer backward
+    kinds = [(e[0], e[2]) for e in rec.tape]
+    assert kinds == [(sb.RECV, sb.SITE_X)] + [(sb.ALL_REDUCE, sb.SITE_ATTN_OUT), (sb.ALL_REDUCE, sb.SITE_MLP_OUT)] * 2 + \
+        [(sb.RECV, sb.SITE_DY)] + [(sb.ALL_REDUCE, sb.SITE_D_MLP_IN), (sb.ALL_REDUCE, sb.SITE_D_ATTN_IN)] * 2
+    # rank 0 alone, every recorded scope on the boundary; the arguments are NOT the real x / dy: the tape supplies them
+    rp = sb.Replayer(rec.tape, sb.SCOPE_TP | sb.SCOPE_PP)
+    junk = np.zeros_like(x)
+    y, st = sb.stage_fwd(shard, per_rank[0], junk, rp)
+    dx, gr = sb.stage_bwd(shard, per_rank[0], st, junk, rp)
+    assert (y == res[0][0]).all() and (dx == res[0][1]).all()
+    for l in range(2):
+        for k in gr[l]:
+            assert (gr[l][k] == res[0][2][l][k]).all(), k
+    assert rp.at == len(rec.tape) and rp.skipped == 2          # both sends skipped
+    # boundary = pipeline scope only: the tensor-parallel sums lack rank 1's share
+    rp2 = sb.Replayer(rec.tape, sb.SCOPE_PP)
+    y2, _ = sb.stage_fwd(shard, per_rank[0], junk, rp2)
+    assert np.abs(y2 - y_full).max() > 1e-3 and rp2.at == 1
+
+
+def test_replay_refuses_a_different_call_sequence_and_skips_barriers():
+    cfg = TINY_GPT
+    layers = [_params(cfg)]
+    x = RNG.standard_normal((cfg.seq, cfg.micro_batch, cfg.hidden))
+    rec = sb.Recorder(sb.PassThrough(), sb.SCOPE_PP | sb.SCOPE_DP)
+    y, st = sb.stage_fwd(cfg, layers, x, rec)
+    g = RNG.standard_normal(50)
+    out = sb.grad_sync(g, rec)
+    assert (out == g).all() and len(rec.tape) == 2                    # recv x and the gradient all-reduce; no barrier, no send
+    rp = sb.Replayer(rec.tape, sb.SCOPE_PP | sb.SCOPE_DP)
+    with pytest.raises(sb.ReplayMismatch):
+        sb.stage_bwd(cfg, layers, st, x, rp)                           # asks for dy where the tape holds x
+    rp = sb.Replayer(rec.tape, sb.SCOPE_DP)
+    assert (sb.grad_sync(np.zeros(50), rp) == g).all() and rp.skipped == 1
+    with pytest.raises(sb.ReplayMismatch):
+        sb.grad_sync(np.zeros(50), rp)                                 # tape exhausted
+    rp = sb.Replayer(rec.tape, sb.SCOPE_DP)
+    with pytest.raises(sb.ReplayMismatch):
+        sb.grad_sync(np.zeros(51), rp)                                 # other shape
