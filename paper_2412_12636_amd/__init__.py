@@ -1,7 +1,7 @@
 """Python binding of libtm_stage.so: argument marshalling only.
 
 Every function has the name and argument order of its C counterpart in
-include/tm_stage.h and include/tm_ops.h.  Device tensors are passed either as
+include/tm_stage.h, tm_ops.h, tm_roles.h and tm_sandbox.h.  Device tensors are passed either as
 integer addresses or as objects with a ``data_ptr()`` method (torch tensors);
 this module itself does not import torch.  A non-zero status raises TmError
 with the library's message.  There is no fallback: if the shared library is
@@ -21,6 +21,11 @@ TM_DTYPE_FP32, TM_DTYPE_BF16 = 0, 1
 TM_NORM_LAYERNORM, TM_NORM_RMSNORM = 0, 1
 TM_ACT_GELU_TANH, TM_ACT_GELU_ERF, TM_ACT_SWIGLU = 0, 1, 2
 TM_POS_NONE, TM_POS_ROTARY = 0, 1
+TM_COMM_PASS, TM_COMM_RECORD, TM_COMM_REPLAY = 0, 1, 2
+TM_SCOPE_TP, TM_SCOPE_PP, TM_SCOPE_DP = 1, 2, 4
+TM_COLL_ALL_REDUCE, TM_COLL_RECV, TM_COLL_SEND, TM_COLL_BARRIER = 0, 1, 2, 3
+(TM_SITE_X, TM_SITE_Y, TM_SITE_DY, TM_SITE_DX, TM_SITE_ATTN_OUT, TM_SITE_MLP_OUT, TM_SITE_D_MLP_IN, TM_SITE_D_ATTN_IN,
+ TM_SITE_GRADS, TM_SITE_STEP_END) = range(10)
 
 
 class TmError(RuntimeError):
@@ -49,6 +54,10 @@ class tm_profile_entry_t(C.Structure):
 class tm_adam_hparams_t(C.Structure):
     _fields_ = [(n, C.c_double) for n in ("lr", "beta1", "beta2", "eps", "weight_decay", "grad_scale")] + \
                [("zero_grads", C.c_int32)]
+
+
+class tm_comm_stats_t(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("calls", "stored", "stored_bytes", "skipped", "native", "tape_entries", "tape_bytes")]
 
 
 EXPORTS = {
@@ -92,6 +101,14 @@ EXPORTS = {
     "tm_head_workspace_bytes": (C.c_int64, [C.c_int] + [C.c_int64] * 4),
     "tm_head_fwd_bwd": (C.c_int, [C.c_int, C.c_int, C.c_double] + [C.c_int64] * 5 + [C.c_void_p] * 5 + [C.c_double, C.c_void_p,
                                  C.c_int64] + [C.c_void_p] * 5 + [C.c_int, C.c_void_p]),
+    "tm_comm_open": (C.c_int, [C.c_char_p, C.c_int, C.c_int, C.POINTER(C.c_void_p)]),
+    "tm_comm_call": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]),
+    "tm_comm_rewind": (C.c_int, [C.c_void_p]),
+    "tm_comm_stats": (C.c_int, [C.c_void_p, C.POINTER(tm_comm_stats_t)]),
+    "tm_comm_close": (C.c_int, [C.c_void_p]),
+    "tm_stage_attach_comm": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "tm_stage_grad_sync": (C.c_int, [C.c_void_p, C.c_void_p]),
+    "tm_op_bias_residual_add": (C.c_int, [C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 5),
     "tm_op_attn_fwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 4),
     "tm_op_attn_bwd_scratch_bytes": (C.c_int64, [C.c_int] + [C.c_int64] * 5),
     "tm_op_attn_bwd": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_void_p] * 7),
@@ -336,3 +353,39 @@ def tm_head_fwd_bwd(dtype, norm, eps, seq, batch, h, v_local, v0, y, targets, ga
     _check(lib().tm_head_fwd_bwd(dtype, norm, eps, seq, batch, h, v_local, v0, _ptr(y), _ptr(targets), _ptr(gain), _ptr(offset),
                                  _ptr(w), dloss, _ptr(workspace), workspace_bytes, _ptr(loss), _ptr(dy), _ptr(dgain),
                                  _ptr(doffset), _ptr(dw), accumulate, stream))
+
+
+def tm_comm_open(path: Optional[str], mode: int, scopes: int) -> int:
+    out = C.c_void_p()
+    _check(lib().tm_comm_open(None if path is None else os.fsencode(path), mode, scopes, C.byref(out)))
+    return int(out.value)
+
+
+def tm_comm_call(comm: int, kind: int, scope: int, site: int, dtype: int, buf, nbytes: int, stream: int = 0) -> None:
+    _check(lib().tm_comm_call(comm, kind, scope, site, dtype, _ptr(buf), nbytes, stream))
+
+
+def tm_comm_rewind(comm: int) -> None:
+    _check(lib().tm_comm_rewind(comm))
+
+
+def tm_comm_stats(comm: int) -> dict:
+    st = tm_comm_stats_t()
+    _check(lib().tm_comm_stats(comm, C.byref(st)))
+    return {n: int(getattr(st, n)) for n, _ in tm_comm_stats_t._fields_}
+
+
+def tm_comm_close(comm: int) -> None:
+    _check(lib().tm_comm_close(comm))
+
+
+def tm_stage_attach_comm(handle: int, comm: Optional[int]) -> None:
+    _check(lib().tm_stage_attach_comm(handle, comm))
+
+
+def tm_stage_grad_sync(handle: int, stream: int = 0) -> None:
+    _check(lib().tm_stage_grad_sync(handle, stream))
+
+
+def tm_op_bias_residual_add(dtype, T, h, part, bias, residual, out, stream=0):
+    _check(lib().tm_op_bias_residual_add(dtype, T, h, _ptr(part), _ptr(bias), _ptr(residual), _ptr(out), stream))

@@ -11,7 +11,9 @@
 
 #include "common.h"
 #include "gemm.h"
+#include "sandbox.h"
 #include "../../include/tm_ops.h"
+#include "../../include/tm_sandbox.h"
 
 namespace tmk {
 
@@ -244,6 +246,8 @@ struct tm_stage {
   // ... and, in tm_stage_bwd_adam, each layer's optimizer update on a third
   hipStream_t opt = nullptr;
   hipEvent_t ev_opt[3] = {nullptr, nullptr, nullptr};
+  // record / replay hook called at every collective call site (not owned)
+  tm_comm_t *comm = nullptr;
 };
 
 static std::deque<std::string> &name_pool() {  // deque: growing it never moves the strings
@@ -476,6 +480,12 @@ extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void 
   st->have_fwd = false;
   const double es = (double)d.es, Th = (double)d.T * d.h;
   const double attn_flops = 2.0 * c.micro_batch * c.n_q_heads * (double)c.seq * c.seq * c.head_dim;  // causal half
+  tm_comm_t *cm = st->comm;
+  // with the tensor-parallel scope stored or served from the tape, a row-parallel map's partial product must
+  // exist on its own: the product runs without its fused epilogue and bias / residual are added after the hook
+  const bool tp_cut = comm_intercepts(cm, TM_SCOPE_TP);
+  const int64_t act_bytes = d.T * d.h * d.es;
+  void *part = ws + st->plan.dx1;  // scratch of the backward pass, free during the forward pass
 
   for (int l = 0; l < c.n_layers; ++l) {
     const LayerStash &k = st->plan.layer[l];
@@ -489,6 +499,7 @@ extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void 
               hipMemcpyAsync(x, x_in, d.T * d.h * d.es, hipMemcpyDeviceToDevice, s) == hipSuccess
                   ? TM_OK
                   : fail(TM_ELAUNCH, "stage_fwd: copy of the stage input failed"));
+      if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_RECV, TM_SCOPE_PP, TM_SITE_X, dt, x, act_bytes, s));
     }
     void *y = (l + 1 < c.n_layers) ? (void *)(ws + st->plan.layer[l + 1].x) : y_out;
     // a = Norm(x)
@@ -506,8 +517,15 @@ extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void 
             tm_op_attn_fwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
                            (float *)(ws + k.lse), s));
     // x1 = x + ctx Wout^T + b   (row-parallel projection; its all-reduce is the identity here)
-    TM_STEP(2.0 * d.T * d.h * d.A, 0,
-            tm_op_linear_fwd(dt, d.T, d.h, d.A, ws + k.ctx, P(o.w_out), P(o.b_out), x, ws + k.x1, s));
+    if (!tp_cut) {
+      TM_STEP(2.0 * d.T * d.h * d.A, 0,
+              tm_op_linear_fwd(dt, d.T, d.h, d.A, ws + k.ctx, P(o.w_out), P(o.b_out), x, ws + k.x1, s));
+      if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_ATTN_OUT, dt, ws + k.x1, act_bytes, s));
+    } else {
+      TM_STEP(2.0 * d.T * d.h * d.A, 0, tm_op_linear_fwd(dt, d.T, d.h, d.A, ws + k.ctx, P(o.w_out), nullptr, nullptr, part, s));
+      TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_ATTN_OUT, dt, part, act_bytes, s));
+      TM_STEP(0, 3 * es * Th, tm_op_bias_residual_add(dt, d.T, d.h, part, P(o.b_out), x, ws + k.x1, s));
+    }
     // c = Norm(x1)
     TM_STEP(0, 2 * es * Th,
             tm_op_norm_fwd(dt, c.norm, d.T, d.h, c.norm_eps, ws + k.x1, P(o.norm2_gain), P(o.norm2_offset), ws + k.c,
@@ -517,9 +535,17 @@ extern "C" int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void 
             tm_op_linear_fwd(dt, d.T, d.f1, d.h, ws + k.c, P(o.w_fc1), P(o.b_fc1), nullptr, ws + k.u, s));
     TM_STEP(0, es * d.T * (d.f1 + d.f), tm_op_act_fwd(dt, c.act, d.T, d.f, ws + k.u, ws + k.g, s));
     // y = x1 + g W2^T + b
-    TM_STEP(2.0 * d.T * d.h * d.f, 0,
-            tm_op_linear_fwd(dt, d.T, d.h, d.f, ws + k.g, P(o.w_fc2), P(o.b_fc2), ws + k.x1, y, s));
+    if (!tp_cut) {
+      TM_STEP(2.0 * d.T * d.h * d.f, 0,
+              tm_op_linear_fwd(dt, d.T, d.h, d.f, ws + k.g, P(o.w_fc2), P(o.b_fc2), ws + k.x1, y, s));
+      if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_MLP_OUT, dt, y, act_bytes, s));
+    } else {
+      TM_STEP(2.0 * d.T * d.h * d.f, 0, tm_op_linear_fwd(dt, d.T, d.h, d.f, ws + k.g, P(o.w_fc2), nullptr, nullptr, part, s));
+      TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_MLP_OUT, dt, part, act_bytes, s));
+      TM_STEP(0, 3 * es * Th, tm_op_bias_residual_add(dt, d.T, d.h, part, P(o.b_fc2), ws + k.x1, y, s));
+    }
   }
+  if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_SEND, TM_SCOPE_PP, TM_SITE_Y, dt, y_out, act_bytes, s));
   st->have_fwd = true;
   return TM_OK;
 }
@@ -585,7 +611,23 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     return TM_OK;
   };
 
+  tm_comm_t *cm = st->comm;
+  if (hp && comm_intercepts(cm, TM_SCOPE_DP))
+    return fail(TM_ESTATE, "stage_bwd_adam: the attached hook intercepts the data-parallel scope; the update must follow tm_stage_grad_sync");
+  const int64_t act_bytes = d.T * d.h * d.es;
   const void *dy = dy_in;
+  if (cm) {
+    void *at = const_cast<void *>(dy_in);
+    if (comm_intercepts(cm, TM_SCOPE_PP)) {
+      // the received gradient may be replaced: it needs a buffer of the library's own (the one the pattern of
+      // alternating gradient streams leaves free for the top layer's input)
+      at = ws + pl.dstream[c.n_layers & 1];
+      if (hipMemcpyAsync(at, dy_in, (size_t)act_bytes, hipMemcpyDeviceToDevice, s) != hipSuccess)
+        return fail(TM_ELAUNCH, "stage_bwd: copy of the incoming gradient failed");
+      dy = at;
+    }
+    TM_TRY(tm_comm_call(cm, TM_COLL_RECV, TM_SCOPE_PP, TM_SITE_DY, dt, at, act_bytes, s));
+  }
   for (int l = c.n_layers - 1; l >= 0; --l) {
     TM_TRY(join());  // the layer above is done with the scratch buffers
     const LayerStash &k = pl.layer[l];
@@ -607,6 +649,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     // u = c W1^T + b1
     void *dc = ws + pl.dnorm;
     TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_dgrad_ws(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, ws + pl.splitk, pl.splitk_bytes, s));
+    if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_D_MLP_IN, dt, dc, act_bytes, s));
     TM_TRY(fork());
     TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), acc, sw));
     if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, acc, s));
@@ -632,6 +675,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     // qkv = a Wqkv^T + b
     void *da = ws + pl.dnorm;
     TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_dgrad_ws(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, ws + pl.splitk, pl.splitk_bytes, s));
+    if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_D_ATTN_IN, dt, da, act_bytes, s));
     TM_TRY(fork());
     TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), acc, sw));
     if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, acc, s));
@@ -661,7 +705,22 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     if (hipEventRecord(st->ev_opt[2], st->opt) != hipSuccess || hipStreamWaitEvent(s, st->ev_opt[2], 0) != hipSuccess)
       return fail(TM_ELAUNCH, "stage_bwd: optimizer join failed");
   }
-  return join();
+  TM_TRY(join());
+  if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_SEND, TM_SCOPE_PP, TM_SITE_DX, dt, dx_out, act_bytes, s));
+  return TM_OK;
+}
+
+extern "C" int tm_stage_attach_comm(tm_stage_t *st, tm_comm_t *c) {
+  if (!st) return fail(TM_EINVAL, "attach_comm: NULL handle");
+  st->comm = c;
+  return TM_OK;
+}
+
+extern "C" int tm_stage_grad_sync(tm_stage_t *st, void *stream) {
+  if (!st) return fail(TM_EINVAL, "grad_sync: NULL handle");
+  if (!st->comm) return TM_OK;  // no peers: the local gradient is the reduced one
+  TM_TRY(tm_comm_call(st->comm, TM_COLL_ALL_REDUCE, TM_SCOPE_DP, TM_SITE_GRADS, TM_DTYPE_FP32, st->buf.grads, st->n_params * 4, stream));
+  return tm_comm_call(st->comm, TM_COLL_BARRIER, TM_SCOPE_DP, TM_SITE_STEP_END, TM_DTYPE_FP32, nullptr, 0, stream);
 }
 
 extern "C" int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stream) {
