@@ -97,6 +97,56 @@ def cpu_baseline(si, cfg, budget_s: float):
     }
 
 
+def time_sandbox(torch, tm, h, x, y, dy, dx, stream: int, folder: str, reps: int):
+    """Forward + backward of one micro-batch with the hook attached: a recording run (synchronous by design: every stored
+    tensor is complete before it goes to the tape), the tape's load into pinned host memory, and replaying runs."""
+    os.makedirs(folder, exist_ok=True)
+
+    def fwd_bwd():
+        tm.tm_stage_fwd(h, x, y, stream)
+        tm.tm_stage_bwd(h, dy, dx, stream)
+
+    def wall(fn, n):
+        torch.cuda.synchronize()
+        t0 = time.time()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.time() - t0) * 1e3 / n
+
+    fwd_bwd()
+    res = {"plain_ms": round(wall(fwd_bwd, reps), 3)}
+    for label, scopes in (("pp", tm.TM_SCOPE_PP), ("pp_tp", tm.TM_SCOPE_PP | tm.TM_SCOPE_TP)):
+        path = os.path.join(folder, f"bench_{label}.tape")
+        c = tm.tm_comm_open(path, tm.TM_COMM_RECORD, scopes)
+        tm.tm_stage_attach_comm(h, c)
+        rec_ms = wall(fwd_bwd, 1)
+        st = tm.tm_comm_stats(c)
+        tm.tm_stage_attach_comm(h, None)
+        tm.tm_comm_close(c)
+        t0 = time.time()
+        c = tm.tm_comm_open(path, tm.TM_COMM_REPLAY, scopes)
+        load_s = time.time() - t0
+        tm.tm_stage_attach_comm(h, c)
+
+        def replay():
+            tm.tm_comm_rewind(c)
+            fwd_bwd()
+
+        replay()
+        rep_ms = wall(replay, reps)
+        tm.tm_stage_attach_comm(h, None)
+        torch.cuda.synchronize()
+        tm.tm_comm_close(c)
+        os.remove(path)
+        res[label] = {"tape_entries": st["stored"], "tape_bytes": st["stored_bytes"], "record_ms": round(rec_ms, 3),
+                      "tape_load_s": round(load_s, 3), "tape_load_gbps": round(st["stored_bytes"] / max(load_s, 1e-9) / 1e9, 2),
+                      "replay_ms": round(rep_ms, 3)}
+    res["note"] = ("host wall clock per forward + backward; replay enqueues one host-to-device copy per boundary tensor; with "
+                   "the tensor scope intercepted the two row-parallel products run without their fused bias/residual epilogue")
+    return res
+
+
 def time_roles(torch, tm, cfg, v_local: int, gen, stream: int, reps: int):
     """The layers only the first and the last pipeline stage have, at the preset's width: embedding lookup and its
     scatter-add backward; final norm + output layer + cross-entropy over the shard, forward and backward in one call."""
@@ -161,6 +211,9 @@ def main() -> int:
                          "gradient norm, clipping factor on the host, Adam on one data-parallel rank's slice)")
     ap.add_argument("--dp", type=int, default=1, help="data-parallel size for --micro-batches (Adam updates 1/dp)")
     ap.add_argument("--clip", type=float, default=1.0, help="gradient-norm limit for --micro-batches (0: off)")
+    ap.add_argument("--sandbox", default="", metavar="DIR",
+                    help="also time the shadow iteration (forward + backward, one micro-batch) under the record / replay "
+                         "hook, tapes written to DIR: recording and replaying the pipeline scope, and pipeline + tensor scope")
     ap.add_argument("--roles", type=int, default=0, metavar="V_LOCAL",
                     help="also time the first- and last-stage layers at the preset's width with this many vocabulary "
                          "rows per rank (e.g. 6400 = 51200 / 8)")
@@ -391,6 +444,8 @@ def main() -> int:
                             "tflops_whole_iteration": round(nmb * flops / (it_ms * 1e-3) / 1e12, 1),
                             "note": "host wall clock; gradient accumulation from the second micro-batch on"}
         tm.tm_stage_grad_mode(h, True)
+    if args.sandbox:
+        out["sandbox"] = time_sandbox(torch, tm, h, x, y, dy, dx, stream, args.sandbox, max(3, args.steps))
     if args.roles > 0:
         out["roles"] = time_roles(torch, tm, cfg, args.roles, gen, stream, max(3, args.steps))
     tm.tm_stage_destroy(h)
