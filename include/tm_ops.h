@@ -23,6 +23,14 @@
 extern "C" {
 #endif
 
+/* The bf16 products choose among tm_gemm_config_count() tile configurations (by a cost model, or by measurement after
+ * tm_stage_tune); every configuration adds the terms of an output element in the same order, so the choice changes
+ * speed only.  tm_gemm_force_config(i) makes every later product of the process use configuration i (products whose
+ * reduction length is not a multiple of 64 keep their own kernel); -1 restores the automatic choice.  A testing and
+ * tuning aid; not thread-safe. */
+int tm_gemm_config_count(void);
+int tm_gemm_force_config(int index);
+
 /* y[T,N] = x[T,K] w[N,K]^T (+ bias[N]) (+ residual[T,N]).  bias, residual may be NULL;
  * residual may alias y.  (Linear maps of the block; the residual form is the row-parallel
  * projection whose all-reduce is the identity.) */

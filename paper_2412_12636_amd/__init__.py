@@ -101,6 +101,8 @@ EXPORTS = {
     "tm_head_workspace_bytes": (C.c_int64, [C.c_int] + [C.c_int64] * 4),
     "tm_head_fwd_bwd": (C.c_int, [C.c_int, C.c_int, C.c_double] + [C.c_int64] * 5 + [C.c_void_p] * 5 + [C.c_double, C.c_void_p,
                                  C.c_int64] + [C.c_void_p] * 5 + [C.c_int, C.c_void_p]),
+    "tm_gemm_config_count": (C.c_int, []),
+    "tm_gemm_force_config": (C.c_int, [C.c_int]),
     "tm_comm_open": (C.c_int, [C.c_char_p, C.c_int, C.c_int, C.POINTER(C.c_void_p)]),
     "tm_comm_call": (C.c_int, [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_void_p]),
     "tm_comm_rewind": (C.c_int, [C.c_void_p]),
@@ -389,3 +391,11 @@ def tm_stage_grad_sync(handle: int, stream: int = 0) -> None:
 
 def tm_op_bias_residual_add(dtype, T, h, part, bias, residual, out, stream=0):
     _check(lib().tm_op_bias_residual_add(dtype, T, h, _ptr(part), _ptr(bias), _ptr(residual), _ptr(out), stream))
+
+
+def tm_gemm_config_count() -> int:
+    return _check(lib().tm_gemm_config_count())
+
+
+def tm_gemm_force_config(index: int) -> None:
+    _check(lib().tm_gemm_force_config(index))

@@ -41,5 +41,8 @@ int64_t gemm_mfma_splitk_bytes(const GemmArgs &g);
 // in different memory (the launches cycle through them), and makes later gemm_mfma() calls of that layout
 // and shape use the fastest.  Overwrites every C; waits for the stream.  Without it a cost model picks.
 int gemm_mfma_tune(const GemmArgs *variants, int n, hipStream_t s);
+// Number of tile configurations, and a process-wide override (index, or -1 for the automatic choice).
+int gemm_mfma_config_count();
+int gemm_mfma_force_config(int index);
 
 }  // namespace tmk

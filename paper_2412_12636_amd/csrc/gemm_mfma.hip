@@ -46,6 +46,7 @@ struct TileConfig {
 static const TileConfig kConfigs[] = {
     {128, 192, 2, 2, 2, 1.00}, {128, 128, 2, 2, 2, 0.92}, {192, 128, 2, 2, 2, 0.90}, {256, 192, 4, 2, 1, 1.08},
     {192, 256, 2, 4, 1, 1.00}, {256, 256, 2, 4, 1, 1.04}, {256, 256, 4, 2, 1, 1.04}, {256, 128, 4, 2, 1, 0.85},
+    {256, 192, 2, 2, 1, 1.10},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 
@@ -67,7 +68,9 @@ static int heuristic_config(const GemmArgs &g) {
 }
 
 // TM_GEMM_TILE=<BM>x<BN>x<WGM>x<WGN> in the environment forces one configuration (tuning aid).
+static int g_override_config = -1;  // tm_gemm_force_config
 static int forced_config() {
+  if (g_override_config >= 0) return g_override_config;
   static int forced = -2;
   if (forced == -2) {
     forced = -1;
@@ -79,6 +82,13 @@ static int forced_config() {
     }
   }
   return forced;
+}
+
+int gemm_mfma_config_count() { return kNumConfigs; }
+int gemm_mfma_force_config(int index) {
+  if (index < -1 || index >= kNumConfigs) return fail(TM_EINVAL, "gemm_force_config: no configuration %d", index);
+  g_override_config = index;
+  return TM_OK;
 }
 
 // Configurations found by gemm_mfma_tune(), keyed by (layout, M, N, K).

@@ -1,7 +1,8 @@
 // bf16 GEMM on the CDNA4 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
 //
 // A block of WGM x WGN wavefronts (four or eight) owns a BM x BN output tile and walks the reduction
-// axis 64 elements at a time through two LDS stages.
+// axis 64 elements at a time through two LDS stages.  (Four waves on a 256x192 tile own 128x96 each: fewer
+// LDS bytes per MFMA, one wave per SIMD, accumulators in the upper half of the 512-register file.)
 //
 // Main kernel (gemm_pipe_kernel).  Operand tiles go from global memory STRAIGHT into LDS
 // (buffer_load ... lds, 16 bytes per lane): no staging registers, no LDS store instructions.  A
@@ -708,7 +709,7 @@ template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs
 // occupancy and measured relative speed, in the same order.
 #define TM_GEMM_CONFIGS(X) \
   X(128, 192, 2, 2) X(128, 128, 2, 2) X(192, 128, 2, 2) X(256, 192, 4, 2) X(192, 256, 2, 4) X(256, 256, 2, 4) \
-  X(256, 256, 4, 2) X(256, 128, 4, 2)
+  X(256, 256, 4, 2) X(256, 128, 4, 2) X(256, 192, 2, 2)
 
 // The variants the host side launches are instantiated explicitly (an implicit instantiation from inside
 // the launcher templates leaves the host-side kernel handle undefined with this compiler).
@@ -722,7 +723,8 @@ template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs
   TM_GEMM_INSTANTIATE_ONE(192, 256, 2, 4, AKC, BKC, EPI)    \
   TM_GEMM_INSTANTIATE_ONE(256, 256, 2, 4, AKC, BKC, EPI)    \
   TM_GEMM_INSTANTIATE_ONE(256, 256, 4, 2, AKC, BKC, EPI)    \
-  TM_GEMM_INSTANTIATE_ONE(256, 128, 4, 2, AKC, BKC, EPI)
+  TM_GEMM_INSTANTIATE_ONE(256, 128, 4, 2, AKC, BKC, EPI)    \
+  TM_GEMM_INSTANTIATE_ONE(256, 192, 2, 2, AKC, BKC, EPI)
 
 // config: index into the list above, as chosen by gemm_mfma_config()
 template <bool A_KC, bool B_KC, int EPI> static int launch_layout(const GemmArgs &g, int config, hipStream_t s) {

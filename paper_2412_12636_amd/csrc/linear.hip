@@ -61,3 +61,6 @@ extern "C" int tm_op_linear_wgrad(int dtype, int64_t T, int64_t N, int64_t K, co
   GemmArgs g{N, K, T, dy, 1, N, x, 1, K, dw, K, nullptr, nullptr, accumulate ? 1 : 2};
   return run(dtype, g, (hipStream_t)stream);
 }
+
+extern "C" int tm_gemm_config_count(void) { return gemm_mfma_config_count(); }
+extern "C" int tm_gemm_force_config(int index) { return gemm_mfma_force_config(index); }

@@ -71,6 +71,47 @@ def test_linear_fwd_dgrad_wgrad(env, dtype, T, N, K):
     assert rel_err(to_host(dw), ref) <= 1e-5
 
 
+def test_every_tile_configuration_gives_the_same_bits_and_matches_the_checker(env):
+    """Each tile configuration in turn is forced on the three products of a linear map (ragged edges, several tiles of
+    the largest shape, all dimensions multiples of 64 so that the pipelined kernel runs): results equal the checker's
+    within tolerance and equal the first configuration's bit for bit."""
+    torch, tm = env
+    T, N, K = 712, 584, 448
+    rng = np.random.default_rng(11)
+    x, w = rand(rng, (T, K), 1.0, BF16), rand(rng, (N, K), 0.05, BF16)
+    bias, res, dy = rand(rng, (N,), 0.5, BF16), rand(rng, (T, N), 1.0, BF16), rand(rng, (T, N), 0.1, BF16)
+    xd, wd, bd, rd, dyd = (to_dev(torch, a, BF16) for a in (x, w, bias, res, dy))
+    dy64 = dy.astype(np.float64)
+    s = stream_ptr(torch)
+    ref_y = x.astype(np.float64) @ w.astype(np.float64).T + bias + res
+    first = None
+    n = tm.tm_gemm_config_count()
+    assert n >= 9
+    try:
+        for c in range(n):
+            print(f"tile configuration {c}", flush=True)
+            tm.tm_gemm_force_config(c)
+            y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+            dx = torch.empty((T, K), dtype=torch.bfloat16, device="cuda")
+            dw = torch.empty((N, K), dtype=torch.float32, device="cuda")
+            tm.tm_op_linear_fwd(BF16, T, N, K, xd, wd, bd, rd, y, s)
+            tm.tm_op_linear_dgrad(BF16, T, N, K, dyd, wd, dx, s)
+            tm.tm_op_linear_wgrad(BF16, T, N, K, dyd, xd, dw, 0, s)
+            tm.tm_op_linear_wgrad(BF16, T, N, K, dyd, xd, dw, 1, s)      # adds the same product again
+            torch.cuda.synchronize()
+            assert rel_err(to_host(y), ref_y) <= TOL_BF16
+            assert rel_err(to_host(dx), dy64 @ w.astype(np.float64)) <= TOL_BF16
+            assert rel_err(to_host(dw), 2.0 * (dy64.T @ x.astype(np.float64))) <= 1e-5
+            if first is None:
+                first = (y, dx, dw)
+            else:
+                assert torch.equal(y, first[0]) and torch.equal(dx, first[1]) and torch.equal(dw, first[2]), c
+    finally:
+        tm.tm_gemm_force_config(-1)
+    with pytest.raises(tm.TmError):
+        tm.tm_gemm_force_config(n)
+
+
 def test_input_gradient_with_split_reduction(env):
     """dx = dy W with few output tiles and a long reduction: with scratch the reduction is split (the size
     query says so), the result meets the same tolerance against the definition and is reproducible; without
