@@ -684,3 +684,112 @@ def test_replay_refuses_a_different_call_sequence_and_skips_barriers():
     rp = sb.Replayer(rec.tape, sb.SCOPE_DP)
     with pytest.raises(sb.ReplayMismatch):
         sb.grad_sync(np.zeros(51), rp)                                 # other shape
+
+
+# ------------------------------------------------------------------ mixture-of-experts MLP shard
+from oracle import moe_oracle as mo  # noqa: E402
+
+
+def _moe_params(h, f, E, ep, bias=True, scale=0.3):
+    p = {"w_router": RNG.standard_normal((E, h)) * scale}
+    for j in range(E // ep):
+        p[f"w_fc1.{j}"] = RNG.standard_normal((f, h)) * scale
+        p[f"w_fc2.{j}"] = RNG.standard_normal((h, f)) * scale
+        if bias:
+            p[f"b_fc1.{j}"] = RNG.standard_normal(f) * scale
+            p[f"b_fc2.{j}"] = RNG.standard_normal(h) * scale
+    return p
+
+
+@pytest.mark.parametrize("E,ep,k,cap,bias", [(4, 1, 2, 5, True), (6, 3, 2, 3, False), (4, 2, 1, 4, True), (3, 1, 3, 9, True)])
+def test_moe_backward_matches_central_differences(E, ep, k, cap, bias):
+    T, h, f = 9, 6, 8
+    p = _moe_params(h, f, E, ep, bias)
+    c = RNG.standard_normal((T, h))
+    dout = RNG.standard_normal((T, h))
+    out, st = mo.moe_fwd(c, p, E, ep, k, cap, so.ACT_GELU_TANH)
+    assert mo.min_decision_margin(st["logits"], min(k, E - 1)) > 2e-5      # the routing is constant around this point
+    dc, gr = mo.moe_bwd(dout, p, st, E, ep, k, cap, so.ACT_GELU_TANH)
+    loss = lambda cc, pp: float((mo.moe_fwd(cc, pp, E, ep, k, cap, so.ACT_GELU_TANH)[0] * dout).sum())
+    eps = 1e-6
+    for _ in range(12):
+        t, j = RNG.integers(T), RNG.integers(h)
+        cp, cm = c.copy(), c.copy()
+        cp[t, j] += eps
+        cm[t, j] -= eps
+        fd = (loss(cp, p) - loss(cm, p)) / (2 * eps)
+        assert abs(fd - dc[t, j]) <= 1e-6 * max(1.0, abs(fd)), ("dc", t, j)
+    for name in p:
+        for _ in range(6):
+            pos = tuple(RNG.integers(n) for n in p[name].shape)
+            pp, pm = {k_: v.copy() for k_, v in p.items()}, {k_: v.copy() for k_, v in p.items()}
+            pp[name][pos] += eps
+            pm[name][pos] -= eps
+            fd = (loss(c, pp) - loss(c, pm)) / (2 * eps)
+            assert abs(fd - gr[name][pos]) <= 1e-6 * max(1.0, abs(fd)), (name, pos)
+
+
+def test_moe_with_one_expert_is_the_dense_mlp():
+    T, h, f = 7, 6, 10
+    p = _moe_params(h, f, 1, 1)
+    c = RNG.standard_normal((T, h))
+    out, st = mo.moe_fwd(c, p, 1, 1, 1, T, so.ACT_GELU_ERF)
+    dense = so.gelu_fwd(c @ p["w_fc1.0"].T + p["b_fc1.0"], so.ACT_GELU_ERF) @ p["w_fc2.0"].T + p["b_fc2.0"]
+    assert np.abs(out - dense).max() <= 1e-13 and (st["gates"] == 1.0).all()
+    dout = RNG.standard_normal((T, h))
+    dc, gr = mo.moe_bwd(dout, p, st, 1, 1, 1, T, so.ACT_GELU_ERF)
+    du = so.gelu_bwd(dout @ p["w_fc2.0"], c @ p["w_fc1.0"].T + p["b_fc1.0"], so.ACT_GELU_ERF)
+    assert np.abs(dc - du @ p["w_fc1.0"]).max() <= 1e-13
+    assert np.abs(gr["w_fc1.0"] - du.T @ c).max() <= 1e-13 and np.abs(gr["w_router"]).max() == 0.0
+
+
+def test_moe_choosing_every_expert_is_the_softmax_mixture():
+    T, h, f, E = 6, 5, 7, 4
+    p = _moe_params(h, f, E, 1)
+    c = RNG.standard_normal((T, h))
+    out, st = mo.moe_fwd(c, p, E, 1, E, T, so.ACT_GELU_TANH)
+    lg = c @ p["w_router"].T
+    sm = np.exp(lg) / np.exp(lg).sum(axis=1, keepdims=True)
+    want = np.zeros((T, h))
+    for e in range(E):
+        want += sm[:, e:e + 1] * (so.gelu_fwd(c @ p[f"w_fc1.{e}"].T + p[f"b_fc1.{e}"], so.ACT_GELU_TANH) @ p[f"w_fc2.{e}"].T
+                                  + p[f"b_fc2.{e}"])
+    assert np.abs(out - want).max() <= 1e-12
+    assert np.abs(st["gates"].sum(axis=1) - 1.0).max() <= 1e-15
+    assert (np.diff(np.take_along_axis(lg, st["idx"], axis=1), axis=1) <= 0).all()      # decreasing logit
+
+
+def test_moe_full_buffer_drops_later_tokens_and_ties_go_to_the_lower_index():
+    T, h, f, E, C = 6, 4, 5, 3, 2
+    p = _moe_params(h, f, E, 1)
+    p["w_router"] = np.zeros((E, h))
+    p["w_router"][1, 0] = 5.0                       # expert 1 wins wherever c[:, 0] > 0; experts 0 and 2 tie at 0
+    c = np.abs(RNG.standard_normal((T, h))) + 0.1
+    out, st = mo.moe_fwd(c, p, E, 1, 2, C, so.ACT_GELU_TANH)
+    assert (st["idx"] == np.array([1, 0])).all()    # the tie between experts 0 and 2 goes to 0
+    assert (st["row"][:C, 0] == C * 1 + np.arange(C)).all() and (st["row"][C:] == -1).all()
+    assert (out[C:] == 0).all() and np.abs(out[:C]).min() > 0
+    assert (st["buf"][2 * C:] == 0).all()           # expert 2's buffer stays empty
+    dout = RNG.standard_normal((T, h))
+    dc, gr = mo.moe_bwd(dout, p, st, E, 1, 2, C, so.ACT_GELU_TANH)
+    assert (dc[C:] == 0).all() and (gr["w_fc1.2"] == 0).all()
+    assert np.abs(gr["b_fc2.1"] - (st["gates"][:C, :1] * dout[:C]).sum(axis=0)).max() <= 1e-14
+
+
+def test_moe_expert_parallel_groups_share_the_local_weights():
+    T, h, f, E, ep, k, C = 10, 6, 8, 6, 3, 2, 3
+    p = _moe_params(h, f, E, ep)
+    c, dout = RNG.standard_normal((T, h)), RNG.standard_normal((T, h))
+    out, st = mo.moe_fwd(c, p, E, ep, k, C, so.ACT_GELU_TANH)
+    dc, gr = mo.moe_bwd(dout, p, st, E, ep, k, C, so.ACT_GELU_TANH)
+    wide = {"w_router": p["w_router"]}
+    for e in range(E):
+        for name in ("w_fc1", "b_fc1", "w_fc2", "b_fc2"):
+            wide[f"{name}.{e}"] = p[f"{name}.{e % (E // ep)}"]
+    out2, st2 = mo.moe_fwd(c, wide, E, 1, k, C, so.ACT_GELU_TANH)
+    dc2, gr2 = mo.moe_bwd(dout, wide, st2, E, 1, k, C, so.ACT_GELU_TANH)
+    assert np.abs(out - out2).max() <= 1e-13 and np.abs(dc - dc2).max() <= 1e-13
+    for j in range(E // ep):
+        for name in ("w_fc1", "b_fc1", "w_fc2", "b_fc2"):
+            total = sum(gr2[f"{name}.{e}"] for e in range(E) if e % (E // ep) == j)
+            assert np.abs(gr[f"{name}.{j}"] - total).max() <= 1e-12
