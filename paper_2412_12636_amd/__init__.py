@@ -1,7 +1,7 @@
 """Python binding of libtm_stage.so: argument marshalling only.
 
 Every function has the name and argument order of its C counterpart in
-include/tm_stage.h, tm_ops.h, tm_roles.h and tm_sandbox.h.  Device tensors are passed either as
+include/tm_stage.h, tm_ops.h, tm_roles.h, tm_sandbox.h and tm_moe.h.  Device tensors are passed either as
 integer addresses or as objects with a ``data_ptr()`` method (torch tensors);
 this module itself does not import torch.  A non-zero status raises TmError
 with the library's message.  There is no fallback: if the shared library is
@@ -56,6 +56,14 @@ class tm_adam_hparams_t(C.Structure):
                [("zero_grads", C.c_int32)]
 
 
+class tm_moe_config_t(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("tokens", "hidden", "ffn", "n_experts", "ep", "top_k", "capacity", "dtype", "act",
+                                         "has_bias")]
+
+
+TM_MOE_WS_LOGITS, TM_MOE_WS_TOP_IDX, TM_MOE_WS_GATES, TM_MOE_WS_SLOT_ROW = 0, 1, 2, 3
+
+
 class tm_comm_stats_t(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("calls", "stored", "stored_bytes", "skipped", "native", "tape_entries", "tape_bytes")]
 
@@ -101,6 +109,13 @@ EXPORTS = {
     "tm_head_workspace_bytes": (C.c_int64, [C.c_int] + [C.c_int64] * 4),
     "tm_head_fwd_bwd": (C.c_int, [C.c_int, C.c_int, C.c_double] + [C.c_int64] * 5 + [C.c_void_p] * 5 + [C.c_double, C.c_void_p,
                                  C.c_int64] + [C.c_void_p] * 5 + [C.c_int, C.c_void_p]),
+    "tm_moe_param_count": (C.c_int64, [C.POINTER(tm_moe_config_t)]),
+    "tm_moe_param_layout": (C.c_int, [C.POINTER(tm_moe_config_t), C.c_int, C.POINTER(C.c_char_p), C.POINTER(C.c_int64),
+                                      C.POINTER(C.c_int64)]),
+    "tm_moe_workspace_bytes": (C.c_int64, [C.POINTER(tm_moe_config_t)]),
+    "tm_moe_workspace_offset": (C.c_int64, [C.POINTER(tm_moe_config_t), C.c_int, C.POINTER(C.c_int64)]),
+    "tm_moe_fwd": (C.c_int, [C.POINTER(tm_moe_config_t)] + [C.c_void_p] * 4 + [C.c_int64, C.c_void_p]),
+    "tm_moe_bwd": (C.c_int, [C.POINTER(tm_moe_config_t)] + [C.c_void_p] * 5 + [C.c_int, C.c_void_p, C.c_int64, C.c_void_p]),
     "tm_gemm_config_count": (C.c_int, []),
     "tm_gemm_force_config": (C.c_int, [C.c_int]),
     "tm_comm_open": (C.c_int, [C.c_char_p, C.c_int, C.c_int, C.POINTER(C.c_void_p)]),
@@ -399,3 +414,48 @@ def tm_gemm_config_count() -> int:
 
 def tm_gemm_force_config(index: int) -> None:
     _check(lib().tm_gemm_force_config(index))
+
+
+def make_moe_config(cfg: Any) -> tm_moe_config_t:
+    """From any object with the attribute names of tm_moe_config_t."""
+    if isinstance(cfg, tm_moe_config_t):
+        return cfg
+    return tm_moe_config_t(*[int(getattr(cfg, n)) for n, _ in tm_moe_config_t._fields_])
+
+
+def tm_moe_param_count(cfg) -> int:
+    return _check(lib().tm_moe_param_count(C.byref(make_moe_config(cfg))))
+
+
+def tm_moe_param_layout(cfg) -> List[Tuple[str, int, Tuple[int, int]]]:
+    c = make_moe_config(cfg)
+    n = _check(lib().tm_moe_param_layout(C.byref(c), -1, None, None, None))
+    out = []
+    for i in range(n):
+        name, off, shape = C.c_char_p(), C.c_int64(), (C.c_int64 * 2)()
+        _check(lib().tm_moe_param_layout(C.byref(c), i, C.byref(name), C.byref(off), shape))
+        out.append((name.value.decode(), int(off.value), (int(shape[0]), int(shape[1]))))
+    return out
+
+
+def tm_moe_workspace_bytes(cfg) -> int:
+    return _check(lib().tm_moe_workspace_bytes(C.byref(make_moe_config(cfg))))
+
+
+def tm_moe_workspace_offset(cfg, region: int) -> Tuple[int, int]:
+    nbytes = C.c_int64()
+    off = _check(lib().tm_moe_workspace_offset(C.byref(make_moe_config(cfg)), region, C.byref(nbytes)))
+    return off, int(nbytes.value)
+
+
+def tm_moe_fwd(cfg, params, c, out, workspace, stream: int = 0, workspace_bytes: Optional[int] = None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = int(workspace.numel()) * int(workspace.element_size())
+    _check(lib().tm_moe_fwd(C.byref(make_moe_config(cfg)), _ptr(params), _ptr(c), _ptr(out), _ptr(workspace), workspace_bytes, stream))
+
+
+def tm_moe_bwd(cfg, params, c, dout, dc, grads, accumulate, workspace, stream: int = 0, workspace_bytes: Optional[int] = None) -> None:
+    if workspace_bytes is None:
+        workspace_bytes = int(workspace.numel()) * int(workspace.element_size())
+    _check(lib().tm_moe_bwd(C.byref(make_moe_config(cfg)), _ptr(params), _ptr(c), _ptr(dout), _ptr(dc), _ptr(grads), accumulate,
+                            _ptr(workspace), workspace_bytes, stream))

@@ -12,7 +12,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libtm_stage.so")
 
 SOURCES = ["stage.hip", "norm.hip", "elementwise.hip", "gemm_generic.hip", "gemm_mfma.hip", "gemm_mfma_nt.hip", "gemm_mfma_nn.hip", "gemm_mfma_tn.hip", "linear.hip",
-           "attn_generic.hip", "attn_mfma.hip", "attn.hip", "roles.hip", "sandbox.hip"]
+           "attn_generic.hip", "attn_mfma.hip", "attn.hip", "roles.hip", "sandbox.hip", "moe.hip"]
 
 # packed fp32 VALU forms are switched off on purpose: the compiler must not form them from plain float code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",

@@ -224,3 +224,62 @@ def make_adam_state(n: int, seed: int = BASE_SEED, chunk: int = 1 << 24):
         z = normal(seed, c, "adam_z", (hi - lo,), 1e-3)
         v[lo:hi] = np.float32(1e-3) * z * z
     return p, g, m, v
+
+
+# ---- mixture-of-experts MLP shard ------------------------------------------------------------------
+@dataclasses.dataclass(frozen=True)
+class MoeConfig:
+    """One rank's expert shard; sizes local to the rank except n_experts (global) and ep."""
+    tokens: int
+    hidden: int
+    ffn: int
+    n_experts: int
+    ep: int
+    top_k: int
+    capacity: int
+    dtype: int = DTYPE_BF16
+    act: int = ACT_GELU_TANH
+    has_bias: int = 1
+
+    def replace(self, **kw) -> "MoeConfig":
+        return dataclasses.replace(self, **kw)
+
+
+def moe_capacity(tokens: int, top_k: int, n_experts: int, factor: float = 1.0) -> int:
+    return max(1, -(-int(round(factor * tokens * top_k * 1000)) // (1000 * n_experts)))
+
+
+# Shaped like the paper's largest workload (Table 3: 5.12T parameters, TP 8, PP 8, EP 16): 96 layers of 16 experts with
+# 8 h^2 parameters each give 5.15e12 at hidden 20480; one rank holds one expert's tensor-parallel slice (4h / 8 = 10240
+# columns) and sees one micro-batch of 2048 tokens; top-2 routing with capacity factor 1 (the paper states neither).
+MOE_PRESETS = {
+    "moe5t": MoeConfig(2048, 20480, 10240, 16, 16, 2, moe_capacity(2048, 2, 16)),
+}
+
+
+def moe_inventory(cfg: MoeConfig) -> List[Tuple[str, Tuple[int, ...]]]:
+    inv: List[Tuple[str, Tuple[int, ...]]] = [("w_router", (cfg.n_experts, cfg.hidden))]
+    for j in range(cfg.n_experts // cfg.ep):
+        inv.append((f"w_fc1.{j}", (cfg.ffn, cfg.hidden)))
+        if cfg.has_bias:
+            inv.append((f"b_fc1.{j}", (cfg.ffn,)))
+        inv.append((f"w_fc2.{j}", (cfg.hidden, cfg.ffn)))
+        if cfg.has_bias:
+            inv.append((f"b_fc2.{j}", (cfg.hidden,)))
+    return inv
+
+
+def make_moe_params(cfg: MoeConfig, seed: int = BASE_SEED, router_std: float = 0.02) -> Dict[str, np.ndarray]:
+    """N(0, 0.02^2) everywhere (the router too unless told otherwise), snapped to the bf16 grid for bf16 shards."""
+    out: Dict[str, np.ndarray] = {}
+    for name, shape in moe_inventory(cfg):
+        a = normal(seed, 0x4D6F, name, shape, router_std if name == "w_router" else 0.02)
+        out[name] = snap_to_bf16_grid(a) if cfg.dtype == DTYPE_BF16 else a
+    return out
+
+
+def make_moe_io(cfg: MoeConfig, seed: int = BASE_SEED):
+    """Layer input c ~ N(0, 1) (a normalised residual stream) and output gradient ~ N(0, 1e-4), [tokens, hidden]."""
+    fin = (lambda a: snap_to_bf16_grid(a)) if cfg.dtype == DTYPE_BF16 else (lambda a: a)
+    return (fin(normal(seed, 0x4D6F, "moe_c", (cfg.tokens, cfg.hidden), 1.0)),
+            fin(normal(seed, 0x4D6F, "moe_dout", (cfg.tokens, cfg.hidden), 1e-2)))
