@@ -147,6 +147,46 @@ def time_sandbox(torch, tm, h, x, y, dy, dx, stream: int, folder: str, reps: int
     return res
 
 
+def time_moe(torch, tm, si, gen, stream: int, reps: int):
+    """tm_moe_fwd, tm_moe_bwd (gradients stored, not added) and the flat Adam sweep over the shard's parameters."""
+    cfg = si.MOE_PRESETS["moe5t"]
+    n = tm.tm_moe_param_count(cfg)
+    master = torch.empty(n, dtype=torch.float32, device="cuda").normal_(0, 0.02, generator=gen)
+    params = master.to(torch.bfloat16)
+    master.copy_(params)
+    grads, m, v = (torch.zeros(n, dtype=torch.float32, device="cuda") for _ in range(3))
+    c = torch.empty((cfg.tokens, cfg.hidden), dtype=torch.float32, device="cuda").normal_(0, 1, generator=gen).to(torch.bfloat16)
+    dout = torch.empty((cfg.tokens, cfg.hidden), dtype=torch.float32, device="cuda").normal_(0, 1e-2, generator=gen).to(torch.bfloat16)
+    out, dc = torch.empty_like(c), torch.empty_like(c)
+    ws = torch.empty(tm.tm_moe_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+    hp = tm.make_hparams(**si.ADAM_DEFAULTS)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    tot = [0.0, 0.0, 0.0]
+    for it in range(reps + 2):
+        ev[0].record()
+        tm.tm_moe_fwd(cfg, params, c, out, ws, stream)
+        ev[1].record()
+        tm.tm_moe_bwd(cfg, params, c, dout, dc, grads, 0, ws, stream)
+        ev[2].record()
+        tm.tm_adam_step_flat(n, master, grads, m, v, params, hp, it + 1, stream)
+        ev[3].record()
+        torch.cuda.synchronize()
+        if it >= 2:
+            for i in range(3):
+                tot[i] += ev[i].elapsed_time(ev[i + 1])
+    fwd, bwd, adam = (t / reps for t in tot)
+    rows = cfg.n_experts * cfg.capacity
+    flops = 3 * (2.0 * rows * cfg.hidden * cfg.ffn * 2 + 2.0 * cfg.tokens * cfg.n_experts * cfg.hidden)
+    return {"workload": f"moe5t: {cfg.tokens} tokens, hidden {cfg.hidden}, expert width {cfg.ffn}, {cfg.n_experts} experts over "
+                        f"ep {cfg.ep}, top-{cfg.top_k}, capacity {cfg.capacity} rows per expert buffer, {n} parameters",
+            "fwd_ms": round(fwd, 3), "bwd_ms": round(bwd, 3), "adam_ms": round(adam, 3),
+            "tokens_per_s": round(cfg.tokens / ((fwd + bwd + adam) * 1e-3), 1),
+            "tflops_fwd_bwd": round(flops / ((fwd + bwd) * 1e-3) / 1e12, 1),
+            "mfma_frac_fwd_bwd": round(flops / ((fwd + bwd) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+            "adam_gbps": round(30.0 * n / (adam * 1e-3) / 1e9, 1),
+            "note": "model flops: 3 x (two expert products over all buffer rows + the router product)"}
+
+
 def time_roles(torch, tm, cfg, v_local: int, gen, stream: int, reps: int):
     """The layers only the first and the last pipeline stage have, at the preset's width: embedding lookup and its
     scatter-add backward; final norm + output layer + cross-entropy over the shard, forward and backward in one call."""
@@ -214,6 +254,9 @@ def main() -> int:
     ap.add_argument("--sandbox", default="", metavar="DIR",
                     help="also time the shadow iteration (forward + backward, one micro-batch) under the record / replay "
                          "hook, tapes written to DIR: recording and replaying the pipeline scope, and pipeline + tensor scope")
+    ap.add_argument("--moe", action="store_true",
+                    help="also time forward + backward + Adam of the mixture-of-experts MLP shard shaped like the paper's "
+                         "5.12T-parameter workload (one local expert, 16 experts, top-2, 2048 tokens)")
     ap.add_argument("--roles", type=int, default=0, metavar="V_LOCAL",
                     help="also time the first- and last-stage layers at the preset's width with this many vocabulary "
                          "rows per rank (e.g. 6400 = 51200 / 8)")
@@ -446,6 +489,8 @@ def main() -> int:
         tm.tm_stage_grad_mode(h, True)
     if args.sandbox:
         out["sandbox"] = time_sandbox(torch, tm, h, x, y, dy, dx, stream, args.sandbox, max(3, args.steps))
+    if args.moe:
+        out["moe"] = time_moe(torch, tm, si, gen, stream, max(3, args.steps))
     if args.roles > 0:
         out["roles"] = time_roles(torch, tm, cfg, args.roles, gen, stream, max(3, args.steps))
     tm.tm_stage_destroy(h)

@@ -38,15 +38,17 @@ bool gemm_mfma_supported(const GemmArgs &g) {
 // ---- tile configurations -------------------------------------------------------------------------
 // Same order as TM_GEMM_CONFIGS in gemm_mfma_impl.h.  occ: blocks a compute unit holds at once (LDS: two
 // stages of (BM+BN) x 128 bytes out of 160 KB; four-wave blocks of up to 256x128 outputs leave room for
-// two).  speed: measured rate per busy compute unit relative to 128x192 on the 175B-shard products.
+// two).  speed[layout]: measured rate per busy compute unit relative to 128x192, per operand layout (0: both
+// reduction axes contiguous, 1: B strided, 2: both strided; the transposing LDS reads of the strided layouts
+// favour the small four-wave tiles, the plain reads the large ones), from products of 2048 to 4096 rows.
 struct TileConfig {
   int bm, bn, wgm, wgn, occ;
-  double speed;
+  double speed[3];
 };
 static const TileConfig kConfigs[] = {
-    {128, 192, 2, 2, 2, 1.00}, {128, 128, 2, 2, 2, 0.92}, {192, 128, 2, 2, 2, 0.90}, {256, 192, 4, 2, 1, 1.08},
-    {192, 256, 2, 4, 1, 1.00}, {256, 256, 2, 4, 1, 1.04}, {256, 256, 4, 2, 1, 1.04}, {256, 128, 4, 2, 1, 0.85},
-    {256, 192, 2, 2, 1, 1.10},
+    {128, 192, 2, 2, 2, {1.00, 1.00, 1.00}}, {128, 128, 2, 2, 2, {0.95, 0.86, 0.91}}, {192, 128, 2, 2, 2, {0.98, 0.98, 1.00}},
+    {256, 192, 4, 2, 1, {1.08, 0.90, 0.88}}, {192, 256, 2, 4, 1, {1.00, 0.90, 0.90}}, {256, 256, 2, 4, 1, {1.22, 1.00, 1.00}},
+    {256, 256, 4, 2, 1, {1.20, 0.98, 1.00}}, {256, 128, 4, 2, 1, {0.88, 0.78, 0.80}}, {256, 192, 2, 2, 1, {1.09, 0.80, 0.83}},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 
@@ -57,11 +59,12 @@ static int layout_of(const GemmArgs &g) { return g.c_mode ? 2 : (g.b_cs == 1 ? 0
 static int heuristic_config(const GemmArgs &g) {
   double best = 1e300;
   int pick = 0;
+  const int layout = layout_of(g);
   for (int c = 0; c < kNumConfigs; ++c) {
     const TileConfig &t = kConfigs[c];
     const int64_t nb = ceil_div(g.M, t.bm) * ceil_div(g.N, t.bn);
     const double passes = (double)ceil_div(nb, 256 * t.occ);
-    const double cost = passes * t.occ * t.bm * t.bn / t.speed;
+    const double cost = passes * t.occ * t.bm * t.bn / t.speed[layout];
     if (cost < best) best = cost, pick = c;
   }
   return pick;

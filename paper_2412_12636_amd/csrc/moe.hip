@@ -15,7 +15,10 @@
 
 namespace tmk {
 
-constexpr int kMoeMaxExperts = 64, kMoeMaxTopK = 8, kMoeThreads = 256, kPlanChunk = 4096;
+constexpr int kMoeMaxExperts = 64, kMoeMaxTopK = 8, kMoeThreads = 256;
+static_assert(kMoeMaxExperts <= kWave, "one lane per expert count");
+constexpr int kWgradSegTokens = 128;  // tokens per block of the router weight gradient
+__device__ __forceinline__ int ceil_div_dev(int a, int b) { return (a + b - 1) / b; }
 
 struct MoeDims {
   int64_t T, h, f, E, ep, k, C, El, rows, es;
@@ -73,7 +76,7 @@ static std::vector<MoeTensor> moe_tensors(const tm_moe_config_t *c, int64_t *tot
 
 struct MoePlan {
   int64_t logits, top_idx, gates, slot_row, row_src, buf, u, g, o, d_o, dg, dbuf, dgate, dlog, reduce, total;
-  int64_t reduce_bytes;
+  int64_t reduce_bytes, wr_part, wr_segs;
 };
 static MoePlan moe_plan(const tm_moe_config_t *c) {
   const MoeDims d = moe_dims(c);
@@ -98,6 +101,8 @@ static MoePlan moe_plan(const tm_moe_config_t *c) {
   p.dbuf = take(d.rows * d.h * d.es);
   p.dgate = take(d.T * d.k * 4);
   p.dlog = take(d.T * d.k * 4);
+  p.wr_segs = ceil_div(d.T, kWgradSegTokens);
+  p.wr_part = take(p.wr_segs * d.E * d.h * 4);
   p.reduce_bytes = tm_op_reduce_scratch_bytes(d.ep * d.C, d.h > d.f ? d.h : d.f);
   p.reduce = take(p.reduce_bytes);
   p.total = at;
@@ -159,34 +164,59 @@ __global__ __launch_bounds__(kMoeThreads) void moe_router_kernel(const T *__rest
   }
 }
 
-// ---- dispatch plan: thread e walks all assignments in order and hands out the rows of expert e's buffer ----
-__global__ __launch_bounds__(kMoeMaxExperts) void moe_plan_kernel(const int *__restrict__ top_idx, int *__restrict__ slot_row,
-                                                                  int *__restrict__ row_src, int n_assign, int E, int El,
-                                                                  int ep, int C) {
-  __shared__ int chunk[kPlanChunk];
-  const int e = threadIdx.x;
-  const int base = e < E ? ((e % El) * ep + e / El) * C : 0;
-  int used = 0;
-  for (int a0 = 0; a0 < n_assign; a0 += kPlanChunk) {
-    const int n = n_assign - a0 < kPlanChunk ? n_assign - a0 : kPlanChunk;
-    for (int i = threadIdx.x; i < n; i += kMoeMaxExperts) chunk[i] = top_idx[a0 + i];
-    __syncthreads();
-    if (e < E) {
-      for (int i = 0; i < n; ++i) {
-        if (chunk[i] != e) continue;
-        if (used < C) {
-          slot_row[a0 + i] = base + used;
-          row_src[base + used] = a0 + i;
-          ++used;
-        } else {
-          slot_row[a0 + i] = -1;  // buffer full: dropped
-        }
-      }
+// ---- dispatch plan: position of every assignment inside its expert's buffer, in assignment order ---------
+// One block of 16 waves; wave w owns a contiguous segment of the assignments.  Pass 1 counts the segment's
+// assignments per expert (a ballot per expert over 64 assignments at a time; lane e keeps expert e's count),
+// the counts of the earlier segments give each wave its starting fill levels, and pass 2 hands out the rows:
+// an assignment's position is its expert's fill level plus the number of earlier lanes in the same ballot.
+constexpr int kPlanWaves = 16;
+__global__ __launch_bounds__(kPlanWaves * kWave) void moe_plan_kernel(const int *__restrict__ top_idx, int *__restrict__ slot_row,
+                                                                      int *__restrict__ row_src, int n_assign, int E, int El,
+                                                                      int ep, int C) {
+  __shared__ int counts[kPlanWaves][kMoeMaxExperts];
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int seg = (int)ceil_div_dev(ceil_div_dev(n_assign, kPlanWaves), kWave) * kWave;
+  const int a_begin = wave * seg;
+  const int a_end = a_begin + seg < n_assign ? a_begin + seg : n_assign;
+  int cnt = 0;
+  for (int a0 = a_begin; a0 < a_end; a0 += kWave) {
+    const int mine = a0 + lane < a_end ? top_idx[a0 + lane] : -1;
+    for (int e = 0; e < E; ++e) {
+      const uint64_t mask = __ballot(mine == e);
+      if (lane == e) cnt += __popcll(mask);
     }
-    __syncthreads();
   }
-  if (e < E)
-    for (int r = used; r < C; ++r) row_src[base + r] = -1;
+  counts[wave][lane] = cnt;
+  __syncthreads();
+  int used = 0;  // lane e: rows of expert e's buffer taken by earlier segments (may pass C: the surplus was dropped)
+  for (int w = 0; w < wave; ++w) used += counts[w][lane];
+  const uint64_t below = (1ull << lane) - 1ull;
+  for (int a0 = a_begin; a0 < a_end; a0 += kWave) {
+    const int a = a0 + lane;
+    const int mine = a < a_end ? top_idx[a] : -1;
+    int row = -1;
+    for (int e = 0; e < E; ++e) {
+      const uint64_t mask = __ballot(mine == e);
+      if (mask == 0) continue;  // uniform over the wave
+      const int before = __shfl(used, e, kWave);
+      if (mine == e) {
+        const int pos = before + __popcll(mask & below);
+        if (pos < C) row = ((e % El) * ep + e / El) * C + pos;
+      }
+      if (lane == e) used += __popcll(mask);
+    }
+    if (a < a_end) {
+      slot_row[a] = row;
+      if (row >= 0) row_src[row] = a;
+    }
+  }
+  // rows no assignment took
+  for (int e = wave; e < E; e += kPlanWaves) {
+    int total = 0;
+    for (int w = 0; w < kPlanWaves; ++w) total += counts[w][e];
+    const int base = ((e % El) * ep + e / El) * C;
+    for (int r = (total < C ? total : C) + lane; r < C; r += kWave) row_src[base + r] = -1;
+  }
 }
 
 // ---- buffers: row = the token's input row, or zero ---------------------------------------------------
@@ -320,41 +350,46 @@ __global__ __launch_bounds__(kMoeThreads) void moe_dispatch_bwd_kernel(const T *
 }
 
 // ---- router weights: dWr[e, col] (+)= sum over tokens, in token order, of dlogit[t, e] c[t, col] ------
-// A block owns 256 columns and keeps one fp32 accumulator per (expert, column) in LDS; a token touches
-// the accumulators of its k chosen experts only.
+// A block owns 256 columns and one segment of the tokens and keeps one fp32 accumulator per (expert, column)
+// in LDS; a token touches the accumulators of its k chosen experts only.  The segments' partial sums are
+// added in segment order by a second kernel.
 template <typename T>
 __global__ __launch_bounds__(kMoeThreads) void moe_router_wgrad_kernel(const T *__restrict__ c, const int *__restrict__ top_idx,
-                                                                       const float *__restrict__ dlog, float *__restrict__ dwr,
-                                                                       int n_tok, int h, int E, int k, int accumulate) {
+                                                                       const float *__restrict__ dlog, float *__restrict__ part,
+                                                                       int n_tok, int h, int E, int k) {
   extern __shared__ __align__(16) char smem[];
-  float *acc = reinterpret_cast<float *>(smem);                       // [E][256]
-  int *s_idx = reinterpret_cast<int *>(acc + (size_t)E * kMoeThreads);  // [256 tokens][k]
-  float *s_dl = reinterpret_cast<float *>(s_idx + kMoeThreads * kMoeMaxTopK);
-  const int tid = threadIdx.x, col = blockIdx.x * kMoeThreads + tid;
+  float *acc = reinterpret_cast<float *>(smem);                         // [E][256]
+  int *s_idx = reinterpret_cast<int *>(acc + (size_t)E * kMoeThreads);  // [segment tokens][k]
+  float *s_dl = reinterpret_cast<float *>(s_idx + kWgradSegTokens * kMoeMaxTopK);
+  const int tid = threadIdx.x, col = blockIdx.x * kMoeThreads + tid, seg = blockIdx.y;
   const bool valid = col < h;
+  const int t0 = seg * kWgradSegTokens;
+  const int n = n_tok - t0 < kWgradSegTokens ? n_tok - t0 : kWgradSegTokens;
   for (int e = 0; e < E; ++e) acc[e * kMoeThreads + tid] = 0.f;
-  for (int t0 = 0; t0 < n_tok; t0 += kMoeThreads) {
-    const int n = n_tok - t0 < kMoeThreads ? n_tok - t0 : kMoeThreads;
-    __syncthreads();
-    for (int i = tid; i < n * k; i += kMoeThreads) {
-      s_idx[i] = top_idx[(int64_t)t0 * k + i];
-      s_dl[i] = dlog[(int64_t)t0 * k + i];
-    }
-    __syncthreads();
-#pragma unroll 4
-    for (int tt = 0; tt < n; ++tt) {
-      const float cv = valid ? to_f32(c[(int64_t)(t0 + tt) * h + col]) : 0.f;
-      for (int i = 0; i < k; ++i) {
-        float *a = acc + s_idx[tt * k + i] * kMoeThreads + tid;
-        *a = fmaf(s_dl[tt * k + i], cv, *a);
-      }
+  for (int i = tid; i < n * k; i += kMoeThreads) {
+    s_idx[i] = top_idx[(int64_t)t0 * k + i];
+    s_dl[i] = dlog[(int64_t)t0 * k + i];
+  }
+  __syncthreads();
+#pragma unroll 8
+  for (int tt = 0; tt < n; ++tt) {
+    const float cv = valid ? to_f32(c[(int64_t)(t0 + tt) * h + col]) : 0.f;
+    for (int i = 0; i < k; ++i) {
+      float *a = acc + s_idx[tt * k + i] * kMoeThreads + tid;
+      *a = fmaf(s_dl[tt * k + i], cv, *a);
     }
   }
   if (valid)
-    for (int e = 0; e < E; ++e) {
-      float *dst = dwr + (int64_t)e * h + col;
-      *dst = (accumulate ? *dst : 0.f) + acc[e * kMoeThreads + tid];
-    }
+    for (int e = 0; e < E; ++e) part[((int64_t)seg * E + e) * h + col] = acc[e * kMoeThreads + tid];
+}
+
+__global__ __launch_bounds__(kMoeThreads) void moe_router_wgrad_reduce_kernel(const float *__restrict__ part, float *__restrict__ dwr,
+                                                                              int64_t n, int segs, int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * kMoeThreads + threadIdx.x;
+  if (i >= n) return;
+  float sum = accumulate ? dwr[i] : 0.f;
+  for (int sg = 0; sg < segs; ++sg) sum += part[(int64_t)sg * n + i];
+  dwr[i] = sum;
 }
 
 template <typename K> static int set_lds(K kernel, int bytes, const char *what) {
@@ -462,7 +497,7 @@ extern "C" int tm_moe_fwd(const tm_moe_config_t *cfg, const void *params, const 
     moe_router_kernel<float><<<(unsigned)d.T, kMoeThreads, router_lds, s>>>((const float *)c, (const float *)par, logits, top_idx,
                                                                             gates, (int)d.h, (int)d.E, (int)d.k);
   }
-  moe_plan_kernel<<<1, kMoeMaxExperts, 0, s>>>(top_idx, slot_row, row_src, (int)(d.T * d.k), (int)d.E, (int)d.El, (int)d.ep, (int)d.C);
+  moe_plan_kernel<<<1, kPlanWaves * kWave, 0, s>>>(top_idx, slot_row, row_src, (int)(d.T * d.k), (int)d.E, (int)d.El, (int)d.ep, (int)d.C);
   if (dt == TM_DTYPE_BF16)
     moe_gather_kernel<bf16><<<(unsigned)d.rows, kMoeThreads, 0, s>>>((const bf16 *)c, row_src, (bf16 *)(ws + p.buf), (int)d.h, (int)d.k);
   else
@@ -530,21 +565,24 @@ extern "C" int tm_moe_bwd(const tm_moe_config_t *cfg, const void *params, const 
     TM_TRY(tm_op_linear_wgrad(dt, grows, d.f, d.h, dg, buf, grads + w1.offset, acc, stream));
     if (cfg->has_bias) TM_TRY(tm_op_bias_grad(dt, grows, d.f, dg, grads + tn[1 + j * per + 1].offset, red, acc, stream));
   }
-  const int wg_lds = (int)(d.E * kMoeThreads * 4) + kMoeThreads * kMoeMaxTopK * 8;
-  const unsigned wg_grid = (unsigned)ceil_div(d.h, kMoeThreads);
+  const int wg_lds = (int)(d.E * kMoeThreads * 4) + kWgradSegTokens * kMoeMaxTopK * 8;
+  const dim3 wg_grid((unsigned)ceil_div(d.h, kMoeThreads), (unsigned)p.wr_segs);
+  float *wr_part = (float *)(ws + p.wr_part);
   g_last_kernel = "moe_dispatch_bwd_kernel";
   if (dt == TM_DTYPE_BF16) {
     moe_dispatch_bwd_kernel<bf16><<<(unsigned)d.T, kMoeThreads, 0, s>>>((const bf16 *)(ws + p.dbuf), (const bf16 *)par, slot_row, top_idx,
                                                                         gates, dgate, dlog, (bf16 *)dc, (int)d.h, (int)d.k);
     TM_TRY(set_lds(moe_router_wgrad_kernel<bf16>, wg_lds, "moe_bwd"));
-    moe_router_wgrad_kernel<bf16><<<wg_grid, kMoeThreads, wg_lds, s>>>((const bf16 *)c, top_idx, dlog, grads, (int)d.T, (int)d.h,
-                                                                       (int)d.E, (int)d.k, acc);
+    moe_router_wgrad_kernel<bf16><<<wg_grid, kMoeThreads, wg_lds, s>>>((const bf16 *)c, top_idx, dlog, wr_part, (int)d.T, (int)d.h,
+                                                                       (int)d.E, (int)d.k);
   } else {
     moe_dispatch_bwd_kernel<float><<<(unsigned)d.T, kMoeThreads, 0, s>>>((const float *)(ws + p.dbuf), (const float *)par, slot_row,
                                                                          top_idx, gates, dgate, dlog, (float *)dc, (int)d.h, (int)d.k);
     TM_TRY(set_lds(moe_router_wgrad_kernel<float>, wg_lds, "moe_bwd"));
-    moe_router_wgrad_kernel<float><<<wg_grid, kMoeThreads, wg_lds, s>>>((const float *)c, top_idx, dlog, grads, (int)d.T, (int)d.h,
-                                                                        (int)d.E, (int)d.k, acc);
+    moe_router_wgrad_kernel<float><<<wg_grid, kMoeThreads, wg_lds, s>>>((const float *)c, top_idx, dlog, wr_part, (int)d.T, (int)d.h,
+                                                                        (int)d.E, (int)d.k);
   }
+  moe_router_wgrad_reduce_kernel<<<(unsigned)ceil_div(d.E * d.h, kMoeThreads), kMoeThreads, 0, s>>>(wr_part, grads, d.E * d.h,
+                                                                                                    (int)p.wr_segs, acc);
   return check_launch("moe_bwd router");
 }
