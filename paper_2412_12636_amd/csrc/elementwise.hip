@@ -347,8 +347,9 @@ extern "C" int tm_sq_sum(int64_t n, const float *g, void *scratch, double *out, 
   return check_launch("sq_sum");
 }
 
-extern "C" int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float *v, void *p_bf16,
-                                 const tm_adam_hparams_t *hp, int64_t step, void *stream) {
+namespace tmk {
+int adam_launch(int64_t n, float *p, float *g, float *m, float *v, void *p_bf16, const tm_adam_hparams_t *hp, int64_t step,
+                hipStream_t s) {
   if (!hp || !p || !g || !m || !v) return fail(TM_EINVAL, "adam: NULL pointer");
   if (n < 0) return fail(TM_EINVAL, "adam: negative length");
   if (step < 1) return fail(TM_EINVAL, "adam: step must be >= 1 (got %lld)", (long long)step);
@@ -368,12 +369,11 @@ extern "C" int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float 
   a.grad_scale = (float)hp->grad_scale;
   a.inv_bc1 = (float)(1.0 / (1.0 - pow(hp->beta1, (double)step)));
   a.inv_bc2 = (float)(1.0 / (1.0 - pow(hp->beta2, (double)step)));
-  hipStream_t s = (hipStream_t)stream;
+  const bool lowp = p_bf16 != nullptr, zero = hp->zero_grads != 0;
+  g_last_kernel = "adam_kernel";
   const int64_t nchunk = n / 4 > 0 ? n / 4 : 1;
   if (ceil_div(nchunk, (int64_t)kAdamThreads) > 0x7fffffffLL) return fail(TM_ESIZE, "adam: array too long for one launch");
   const unsigned grid = (unsigned)ceil_div(nchunk, (int64_t)kAdamThreads);
-  const bool lowp = p_bf16 != nullptr, zero = hp->zero_grads != 0;
-  g_last_kernel = "adam_kernel";
   if (lowp && zero)
     adam_kernel<true, true><<<grid, kAdamThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, n, a);
   else if (lowp)
@@ -383,4 +383,10 @@ extern "C" int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float 
   else
     adam_kernel<false, false><<<grid, kAdamThreads, 0, s>>>(p, g, m, v, nullptr, n, a);
   return check_launch("adam");
+}
+}  // namespace tmk
+
+extern "C" int tm_adam_step_flat(int64_t n, float *p, float *g, float *m, float *v, void *p_bf16,
+                                 const tm_adam_hparams_t *hp, int64_t step, void *stream) {
+  return adam_launch(n, p, g, m, v, p_bf16, hp, step, (hipStream_t)stream);
 }

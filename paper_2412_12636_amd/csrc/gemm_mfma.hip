@@ -49,6 +49,10 @@ static const TileConfig kConfigs[] = {
     {128, 192, 2, 2, 2, {1.00, 1.00, 1.00}}, {128, 128, 2, 2, 2, {0.95, 0.86, 0.91}}, {192, 128, 2, 2, 2, {0.98, 0.98, 1.00}},
     {256, 192, 4, 2, 1, {1.08, 0.90, 0.88}}, {192, 256, 2, 4, 1, {1.00, 0.90, 0.90}}, {256, 256, 2, 4, 1, {1.22, 1.00, 1.00}},
     {256, 256, 4, 2, 1, {1.20, 0.98, 1.00}}, {256, 128, 4, 2, 1, {0.88, 0.78, 0.80}}, {256, 192, 2, 2, 1, {1.09, 0.80, 0.83}},
+    // the alternating kernel (gemm_alt_kernel)
+    {256, 256, 2, 4, 1, {1.00, 1.10, 1.06}}, {256, 256, 4, 2, 1, {1.00, 1.10, 1.06}},
+    // the pipelined kernel with three LDS stages
+    {256, 128, 4, 2, 1, {1.05, 0.78, 0.80}}, {128, 256, 2, 4, 1, {1.05, 0.78, 0.80}},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 

@@ -392,9 +392,15 @@ template <int MF, int DSN, int LOADS, int i> __device__ __forceinline__ void sch
   }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 * 128) ? 2 : 1) void gemm_pipe_kernel(
+// NSA, NSB: LDS stages of the A and of the B tiles.  Two each is the base form.  A third stage lets a tile's loads
+// be issued one step earlier (two steps of time to arrive instead of one): what bounds this kernel is the data it
+// can have in flight between L2 and LDS (free LDS space) against the latency of that path (a 64 KB burst of a
+// block takes about 2500 clocks to arrive even from L2), not LDS or MFMA throughput.  A third stage for B alone
+// measured nothing (the A tiles of the same batch are as late); three of both need tiles of at most 53 KB a stage.
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, int NSA = 2, int NSB = 2>
+__global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 * 128 && NSB == 2) ? 2 : 1) void gemm_pipe_kernel(
     const MfmaGemmParams p_in) {
+  static_assert(NSA >= 2 && NSA <= 3 && NSB >= NSA && NSB <= 3, "two or three LDS stages, B at least as many as A");
   extern __shared__ __align__(16) char lds[];
   MfmaGemmParams p = p_in;
   if (gridDim.y > 1) {  // split reduction: this block row takes one part of K and writes its own result
@@ -413,8 +419,10 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
   typedef typename DirectSel<BM, BK, A_KC, NW>::type LA;
   typedef typename DirectSel<BN, BK, B_KC, NW>::type LB;
-  constexpr int STAGE = LA::BYTES + LB::BYTES;
+  constexpr int B_BASE = NSA * LA::BYTES;  // LDS: the A stages, then the B stages
   constexpr int LOADS = LA::NLOAD + LB::NLOAD;
+  // loads that may still be in flight when step kt+1's tiles must have landed: the batches issued later
+  constexpr int PENDING = (NSA - 2) * LA::NLOAD + (NSB - 2) * LB::NLOAD;
   constexpr int KS = BK / 16;
   static_assert(KS % 2 == 0, "fragment buffers alternate");
   constexpr int MF = TM * TN;
@@ -444,24 +452,26 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
   bf16x8 a[2][TM], b[2][TN];
   // prologue: stage 0 in LDS, its slice 0 in registers, stage 1 in flight
   la.issue(ra, lds, 0, p.lda, wave);
-  lb.issue(rb, lds + LA::BYTES, 0, p.ldb, wave);
+  lb.issue(rb, lds + B_BASE, 0, p.ldb, wave);
   wait_vmcnt<0>();
   __builtin_amdgcn_s_barrier();
 #pragma unroll
   for (int i = 0; i < TM; ++i) a[0][i] = LA::frag(lds, wm * WM + i * 32, 0, lane);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) b[0][j] = LB::frag(lds + LA::BYTES, wn * WN + j * 32, 0, lane);
-  {
-    const int k1 = nk > 1 ? BK : 0;  // never past K: a surplus fetch repeats the last step
-    la.issue(ra, lds + STAGE, k1, p.lda, wave);
-    lb.issue(rb, lds + STAGE + LA::BYTES, k1, p.ldb, wave);
+  for (int j = 0; j < TN; ++j) b[0][j] = LB::frag(lds + B_BASE, wn * WN + j * 32, 0, lane);
+#pragma unroll
+  for (int ahead = 1; ahead < NSB; ++ahead) {
+    const int k1 = (ahead < nk ? ahead : nk - 1) * BK;  // never past K: a surplus fetch repeats the last step
+    if (ahead < NSA) la.issue(ra, lds + ahead * LA::BYTES, k1, p.lda, wave);
+    lb.issue(rb, lds + B_BASE + ahead * LB::BYTES, k1, p.ldb, wave);
   }
 
+  int ca = 0, na = 1, cb = 0, nb = 1;  // LDS stages of steps kt and kt+1, per operand
   for (int kt = 0; kt < nk; ++kt) {
-    char *As = lds + (kt & 1) * STAGE;
-    char *Bs = As + LA::BYTES;
-    char *An = lds + ((kt & 1) ^ 1) * STAGE;
-    char *Bn = An + LA::BYTES;
+    char *As = lds + ca * LA::BYTES;
+    char *Bs = lds + B_BASE + cb * LB::BYTES;
+    char *An = lds + na * LA::BYTES;
+    char *Bn = lds + B_BASE + nb * LB::BYTES;
 #pragma unroll
     for (int ks = 0; ks + 1 < KS; ++ks) {
 #pragma unroll
@@ -476,14 +486,15 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
       sched_mid<MF, DSN, 0>();
     }
     __builtin_amdgcn_sched_barrier(0);
-    // all reads of the current stage are complete, and this wave's loads of the next stage have landed
-    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    // all reads of the current stages are complete, and this wave's loads of the next stages have landed (loads
+    // complete in order; a batch is the A loads, then the B loads, so what may still be in flight of a three-deep
+    // operand are the loads issued last)
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(PENDING) : "memory");
     __builtin_amdgcn_s_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    // the current stage is free: fetch step kt+2 into it (at the end the last step again, never consumed)
-    const int kn = (kt + 2 < nk ? kt + 2 : nk - 1) * BK;
-    la.issue(ra, As, kn, p.lda, wave);
-    lb.issue(rb, Bs, kn, p.ldb, wave);
+    // the current stages are free: fetch steps kt+NSA / kt+NSB into them (at the end the last step again, never consumed)
+    la.issue(ra, As, (kt + NSA < nk ? kt + NSA : nk - 1) * BK, p.lda, wave);
+    lb.issue(rb, Bs, (kt + NSB < nk ? kt + NSB : nk - 1) * BK, p.ldb, wave);
 #pragma unroll
     for (int i = 0; i < TM; ++i) a[0][i] = LA::frag(An, wm * WM + i * 32, 0, lane);
 #pragma unroll
@@ -494,6 +505,154 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
       for (int j = 0; j < TN; ++j)
         acc[i][j] = mfma_for<EPI>(a[(KS - 1) & 1][i], b[(KS - 1) & 1][j], acc[i][j]);
     sched_last<MF, DSN, LOADS, 0>();
+    ca = na;
+    na = na + 1 == NSA ? 0 : na + 1;
+    cb = nb;
+    nb = nb + 1 == NSB ? 0 : nb + 1;
+  }
+  wait_vmcnt<0>();  // drain the look-ahead loads before the block may exit
+  if constexpr (EPI == 0) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();  // every wave's loads have landed and its LDS reads are done: the stages are free
+    epilogue_lds<BM, BN, NW, TM, TN>(p, acc, lds, m0, n0, wm * WM, wn * WN, lane);
+  } else {
+    epilogue<TM, TN, EPI>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
+  }
+}
+
+// =================================================================================================
+// alternating kernel: eight waves, the two waves of every SIMD take turns at the matrix core
+// =================================================================================================
+// A block of eight waves puts two waves on each SIMD (waves w and w + 4).  Time is cut into slots; in a slot
+// the waves of one half run nothing but the MFMAs of one whole 64-element step, operands already in
+// registers, while the waves of the other half fetch THEIR operands of a step from LDS; at the slot's end
+// (one barrier) the halves swap.  The matrix core of a SIMD is fed by one wave at a time with no waits inside
+// the run, and all LDS and global traffic of the other wave hides behind it.
+//   slot 2k:    first half computes step k;        second half reads its fragments of step k
+//   slot 2k+1:  first half reads step k+1;         second half computes step k
+// Stage k&1 of LDS is free once the second half has read step k (end of slot 2k): every wave then issues its
+// share of the global loads of step k+2 into it (start of slot 2k+1) and waits for them before the barrier
+// that ends slot 2k+2, two slots later.  A fragment set of a whole step lives in registers (96 of them for a
+// 128x64 wave tile) beside the 128 accumulators.
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(512, 1) void gemm_alt_kernel(const MfmaGemmParams p) {
+  static_assert(WGM * WGN == 8, "two waves per SIMD");
+  extern __shared__ __align__(16) char lds[];
+  constexpr int NW = 8;
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+  typedef typename DirectSel<BM, BK, A_KC, NW>::type LA;
+  typedef typename DirectSel<BN, BK, B_KC, NW>::type LB;
+  constexpr int STAGE = LA::BYTES + LB::BYTES;
+  constexpr int LOADS = LA::NLOAD + LB::NLOAD;
+  constexpr int KS = BK / 16;
+
+  int m0, n0;
+  tile_of_block(p, BM, BN, m0, n0);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int wm = wave / WGN, wn = wave % WGN;
+  const bool second = wave >= 4;  // waves w and w + 4 share a SIMD
+
+  LA la;
+  LB lb;
+  const rsrc_t ra = make_rsrc(p.A, p.a_bytes), rb = make_rsrc(p.B, p.b_bytes);
+  la.init(p.lda, m0, wave, lane);
+  lb.init(p.ldb, n0, wave, lane);
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nk = (p.K + BK - 1) / BK;
+  bf16x8 fa[KS][TM], fb[KS][TN];
+  // this wave's share of the loads of step `step` (never past K: a surplus fetch repeats the last step)
+  auto issue = [&](int step) {
+    const int k0 = (step < nk ? step : nk - 1) * BK;
+    char *st = lds + (step & 1) * STAGE;
+    la.issue(ra, st, k0, p.lda, wave);
+    lb.issue(rb, st + LA::BYTES, k0, p.ldb, wave);
+  };
+  // Fragment addresses of an operand with contiguous reduction axis: row r of the tile, 16-byte chunk
+  // (2 ks + lane/32) ^ swz(r).  swz looks at row bits 0..5 only and 32 rows further on it flips bit 2, so
+  // eight per-lane offsets (slice ks, row-block parity) serve every 32-row block through the instruction's
+  // immediate offset; without this the compiler keeps one address register per (block, slice).
+  uint32_t ka[KS][2], kb[KS][2];
+  {
+    const int l32 = lane & 31, hh = lane >> 5;
+    const int sw = (l32 ^ (l32 >> 3)) & 7;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int par = 0; par < 2; ++par) {
+        const uint32_t o = (uint32_t)(l32 * LA::ROWB + ((((2 * ks + hh) ^ sw ^ (4 * par)) & 7) << 4));
+        ka[ks][par] = o + (uint32_t)(wm * WM * (A_KC ? LA::ROWB : 0));
+        kb[ks][par] = o + (uint32_t)(wn * WN * (B_KC ? LB::ROWB : 0)) + (uint32_t)LA::BYTES;
+      }
+  }
+  auto read_frags = [&](int step) {
+    const char *as = lds + (step & 1) * STAGE, *bs = as + LA::BYTES;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        if constexpr (A_KC) fa[ks][i] = *reinterpret_cast<const bf16x8 *>(as + ka[ks][i & 1] + i * 32 * LA::ROWB);
+        else fa[ks][i] = LA::frag(as, wm * WM + i * 32, ks, lane);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        if constexpr (B_KC) fb[ks][j] = *reinterpret_cast<const bf16x8 *>(as + kb[ks][j & 1] + j * 32 * LB::ROWB);
+        else fb[ks][j] = LB::frag(bs, wn * WN + j * 32, ks, lane);
+      }
+    }
+  };
+  auto compute = [&]() {
+    __builtin_amdgcn_s_setprio(2);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma_for<EPI>(fa[ks][i], fb[ks][j], acc[i][j]);
+    __builtin_amdgcn_s_setprio(0);
+  };
+  auto slot_end = [&]() {
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+
+  issue(0);
+  issue(1);
+  wait_vmcnt<LOADS>();  // this wave's loads of step 0 have landed (loads complete in order)
+  slot_end();
+  if (!second) {
+    read_frags(0);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    slot_end();
+    for (int k = 0; k < nk; ++k) {
+      compute();                                                   // slot 2k
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");            // own loads of step k+1
+      slot_end();
+      issue(k + 2);                                                // slot 2k+1: stage k&1 is free
+      if (k + 1 < nk) read_frags(k + 1);
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      slot_end();
+    }
+  } else {
+    slot_end();
+    for (int k = 0; k < nk; ++k) {
+      read_frags(k);                                               // slot 2k
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");  // fragments here; own loads of step k+1 landed
+      slot_end();
+      issue(k + 2);                                                // slot 2k+1
+      compute();
+      slot_end();
+    }
   }
   wait_vmcnt<0>();  // drain the look-ahead loads before the block may exit
   if constexpr (EPI == 0) {
@@ -673,28 +832,50 @@ static std::string kernel_tag(const char *base, int bm, int bn, int wgm, int wgn
          std::to_string(wgn) + "," + (akc ? "kc" : "ks") + "," + (bkc ? "kc" : "ks") + ",epi" + std::to_string(epi) + ">";
 }
 
-template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI, int NSA = 2, int NSB = 2>
 static int launch_pipe(const GemmArgs &g, hipStream_t s) {
   constexpr int BK = GEMM_BK;
   const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, BM, BN);
-  constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
+  constexpr int lds_bytes = (NSA * BM + NSB * BN) * BK * 2 > BM * BN * 2 ? (NSA * BM + NSB * BN) * BK * 2 : BM * BN * 2;
   static_assert(lds_bytes <= 160 * 1024, "LDS");
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_pipe_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI>),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_pipe_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI, NSA, NSB>),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
       return fail(TM_ELAUNCH, "gemm_mfma: cannot reserve %d bytes of LDS", lds_bytes);
     attr_set = true;
   }
   const int64_t nblk = (int64_t)p.tiles_m * p.tiles_n;
   if (nblk > 0x7fffffff) return fail(TM_ESIZE, "gemm_mfma: too many tiles");
-  static const std::string name = kernel_tag("gemm_pipe_kernel", BM, BN, WGM, WGN, A_KC, B_KC, EPI);
+  static const std::string name = kernel_tag(NSB == 3 ? (NSA == 3 ? "gemm_pipe33_kernel" : "gemm_pipe23_kernel") : "gemm_pipe_kernel", BM, BN, WGM, WGN, A_KC, B_KC, EPI);
   g_last_kernel = name.c_str();
   if (g.k_splits > 1 && (EPI != 2 || g.K % ((int64_t)BK * g.k_splits) != 0))
     return fail(TM_EINVAL, "gemm_mfma: split reduction needs whole steps per part and fp32 results");
-  gemm_pipe_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI>
+  gemm_pipe_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI, NSA, NSB>
       <<<dim3((unsigned)nblk, (unsigned)(g.k_splits > 1 ? g.k_splits : 1)), 64 * WGM * WGN, lds_bytes, s>>>(p);
   return check_launch("gemm_pipe");
+}
+
+template <int BM, int BN, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+static int launch_alt(const GemmArgs &g, hipStream_t s) {
+  constexpr int BK = GEMM_BK;
+  const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, BM, BN);
+  constexpr int lds_bytes = 2 * (BM + BN) * BK * 2;
+  static_assert(lds_bytes <= 160 * 1024, "LDS");
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_alt_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+      return fail(TM_ELAUNCH, "gemm_mfma: cannot reserve %d bytes of LDS", lds_bytes);
+    attr_set = true;
+  }
+  const int64_t nblk = (int64_t)p.tiles_m * p.tiles_n;
+  if (nblk > 0x7fffffff) return fail(TM_ESIZE, "gemm_mfma: too many tiles");
+  if (g.k_splits > 1) return fail(TM_EINVAL, "gemm_mfma: the alternating kernel does not split the reduction");
+  static const std::string name = kernel_tag("gemm_alt_kernel", BM, BN, WGM, WGN, A_KC, B_KC, EPI);
+  g_last_kernel = name.c_str();
+  gemm_alt_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI><<<dim3((unsigned)nblk), 512, lds_bytes, s>>>(p);
+  return check_launch("gemm_alt");
 }
 
 template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs &g, hipStream_t s) {
@@ -707,6 +888,10 @@ template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs
 
 // The tile configurations (BM, BN, wave grid).  gemm_mfma.hip holds the same list with each entry's
 // occupancy and measured relative speed, in the same order.
+// configurations of the alternating kernel follow those of the pipelined one in the numbering
+#define TM_GEMM_ALT_CONFIGS(X) X(256, 256, 2, 4) X(256, 256, 4, 2)
+// ... then the pipelined kernel with three LDS stages of both tiles (tiles whose three stages fit 160 KB)
+#define TM_GEMM_PIPE33_CONFIGS(X) X(256, 128, 4, 2) X(128, 256, 2, 4)
 #define TM_GEMM_CONFIGS(X) \
   X(128, 192, 2, 2) X(128, 128, 2, 2) X(192, 128, 2, 2) X(256, 192, 4, 2) X(192, 256, 2, 4) X(256, 256, 2, 4) \
   X(256, 256, 4, 2) X(256, 128, 4, 2) X(256, 192, 2, 2)
@@ -724,7 +909,11 @@ template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs
   TM_GEMM_INSTANTIATE_ONE(256, 256, 2, 4, AKC, BKC, EPI)    \
   TM_GEMM_INSTANTIATE_ONE(256, 256, 4, 2, AKC, BKC, EPI)    \
   TM_GEMM_INSTANTIATE_ONE(256, 128, 4, 2, AKC, BKC, EPI)    \
-  TM_GEMM_INSTANTIATE_ONE(256, 192, 2, 2, AKC, BKC, EPI)
+  TM_GEMM_INSTANTIATE_ONE(256, 192, 2, 2, AKC, BKC, EPI)    \
+  template __global__ void gemm_alt_kernel<256, 256, GEMM_BK, 2, 4, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_alt_kernel<256, 256, GEMM_BK, 4, 2, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_pipe_kernel<256, 128, GEMM_BK, 4, 2, AKC, BKC, EPI, 3, 3>(const MfmaGemmParams); \
+  template __global__ void gemm_pipe_kernel<128, 256, GEMM_BK, 2, 4, AKC, BKC, EPI, 3, 3>(const MfmaGemmParams);
 
 // config: index into the list above, as chosen by gemm_mfma_config()
 template <bool A_KC, bool B_KC, int EPI> static int launch_layout(const GemmArgs &g, int config, hipStream_t s) {
@@ -733,6 +922,14 @@ template <bool A_KC, bool B_KC, int EPI> static int launch_layout(const GemmArgs
 #define X(BM_, BN_, WGM_, WGN_) \
   if (config == idx++) return launch_pipe<BM_, BN_, WGM_, WGN_, A_KC, B_KC, EPI>(g, s);
   TM_GEMM_CONFIGS(X)
+#undef X
+#define X(BM_, BN_, WGM_, WGN_) \
+  if (config == idx++) return launch_alt<BM_, BN_, WGM_, WGN_, A_KC, B_KC, EPI>(g, s);
+  TM_GEMM_ALT_CONFIGS(X)
+#undef X
+#define X(BM_, BN_, WGM_, WGN_) \
+  if (config == idx++) return launch_pipe<BM_, BN_, WGM_, WGN_, A_KC, B_KC, EPI, 3, 3>(g, s);
+  TM_GEMM_PIPE33_CONFIGS(X)
 #undef X
   return fail(TM_EINVAL, "gemm_mfma: no tile configuration %d", config);
 }

@@ -554,8 +554,8 @@ static int adam_slice(tm_stage *st, int64_t first, int64_t count, const tm_adam_
                       hipStream_t s) {
   const bool lowp = st->cfg.dtype == TM_DTYPE_BF16;
   float *p = lowp ? st->buf.master : (float *)st->buf.params;
-  return tm_adam_step_flat(count, p + first, st->buf.grads + first, st->buf.exp_avg + first,
-                           st->buf.exp_avg_sq + first, lowp ? (char *)st->buf.params + first * 2 : nullptr, hp, step, s);
+  return adam_launch(count, p + first, st->buf.grads + first, st->buf.exp_avg + first, st->buf.exp_avg_sq + first,
+                     lowp ? (char *)st->buf.params + first * 2 : nullptr, hp, step, s);
 }
 
 // hp != NULL: every layer's parameters are updated as soon as its gradients are complete

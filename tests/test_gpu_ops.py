@@ -86,7 +86,7 @@ def test_every_tile_configuration_gives_the_same_bits_and_matches_the_checker(en
     ref_y = x.astype(np.float64) @ w.astype(np.float64).T + bias + res
     first = None
     n = tm.tm_gemm_config_count()
-    assert n >= 9
+    assert n >= 13
     try:
         for c in range(n):
             print(f"tile configuration {c}", flush=True)
