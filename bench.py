@@ -305,8 +305,9 @@ def main() -> int:
     y, dx = torch.empty_like(x), torch.empty_like(x)
     h = tm.tm_stage_init(cfg, params, master if bf16 else None, grads, m, v, ws)
     # one micro-batch per iteration: the backward pass stores the gradients (their old contents are
-    # dead), so nothing has to clear the buffer and Adam only reads it
-    tm.tm_stage_grad_mode(h, True)
+    # dead), so nothing has to clear the buffer and Adam only reads it; in the timed step (backward with the
+    # update) nobody reads the gradients afterwards, so the matrices' gradients may stay in registers
+    tm.tm_stage_grad_mode(h, tm.TM_GRAD_TRANSIENT)
     # once per process: time the GEMM tile configurations on this shard's twelve products
     tm.tm_stage_tune(h, int(torch.cuda.current_stream().cuda_stream))
     hp = tm.make_hparams(**si.ADAM_DEFAULTS)
@@ -445,7 +446,9 @@ def main() -> int:
                                f"{cfg.n_kv_heads}kv heads x {cfg.head_dim}, ffn {cfg.ffn}, seq {cfg.seq}, "
                                f"micro-batch {cfg.micro_batch}, {n} parameters (one rank's TP shard of one PP stage)",
                    "preset": args.preset, "tokens_per_step": tokens},
-        "step": "tm_stage_fwd + tm_stage_bwd_adam (each layer's Adam update beside the backward pass of the layers below)",
+        "step": "tm_stage_fwd + tm_stage_bwd_adam, transient gradients (each weight matrix is updated in the epilogue of its "
+                "weight-gradient product from the accumulators, the vectors by a flat sweep beside the layers below; same "
+                "bits as the three separate calls, which are timed as sequential_*)",
         "phases_ms": {"fwd": round(fwd_ms, 4), "bwd_with_adam": round(bwd_adam_ms, 4)},
         "sequential_ms_per_step": round(seq_ms_step, 4),
         "sequential_phases_ms": {"fwd": round(seq_fwd_ms, 4), "bwd": round(bwd_ms, 4), "adam": round(adam_ms, 4)},
@@ -486,7 +489,7 @@ def main() -> int:
                             "tokens_per_s": round(nmb * tokens / (it_ms * 1e-3), 1),
                             "tflops_whole_iteration": round(nmb * flops / (it_ms * 1e-3) / 1e12, 1),
                             "note": "host wall clock; gradient accumulation from the second micro-batch on"}
-        tm.tm_stage_grad_mode(h, True)
+        tm.tm_stage_grad_mode(h, tm.TM_GRAD_TRANSIENT)
     if args.sandbox:
         out["sandbox"] = time_sandbox(torch, tm, h, x, y, dy, dx, stream, args.sandbox, max(3, args.steps))
     if args.moe:

@@ -166,13 +166,17 @@ int tm_stage_fwd(tm_stage_t *st, const void *x_in, void *y_out, void *stream);
 int tm_stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stream);
 
 /*
- * Gradient-buffer mode of the following tm_stage_bwd calls.  overwrite == 0 (the default): parameter
- * gradients are ADDED into buffers.grads (gradient accumulation over micro-batches).  overwrite != 0:
+ * Gradient-buffer mode of the following tm_stage_bwd calls.  TM_GRAD_ADD (0, the default): parameter
+ * gradients are ADDED into buffers.grads (gradient accumulation over micro-batches).  TM_GRAD_STORE (1):
  * they are STORED, the buffer's old contents are not read - for the first micro-batch of an iteration,
  * when those contents are dead; it saves one read of the fp32 gradient buffer per backward pass and
- * makes clearing the buffer unnecessary.
+ * makes clearing the buffer unnecessary.  TM_GRAD_TRANSIENT (2): as TM_GRAD_STORE, and tm_stage_bwd_adam
+ * may consume a gradient without storing it (where the update rides in a weight-gradient product, see
+ * there): afterwards those entries of buffers.grads are unspecified - for iterations of one micro-batch
+ * whose gradients nobody reads after the update.
  */
-int tm_stage_grad_mode(tm_stage_t *st, int overwrite);
+enum { TM_GRAD_ADD = 0, TM_GRAD_STORE = 1, TM_GRAD_TRANSIENT = 2 };
+int tm_stage_grad_mode(tm_stage_t *st, int mode);
 
 /*
  * Adam with bias correction at step >= 1 on the whole shard:
@@ -191,7 +195,12 @@ int tm_adam_step(tm_stage_t *st, const tm_adam_hparams_t *hp, int64_t step, void
  * it (the update is bound by HBM bandwidth, the backward pass by the matrix
  * cores, so the two share the chip well).  Valid only when nothing global is
  * derived from this pass's gradients before the update: hp->grad_scale must
- * not depend on them (no norm-based clipping).  Uses internal streams that are
+ * not depend on them (no norm-based clipping).  For bf16 stages in TM_GRAD_STORE
+ * or TM_GRAD_TRANSIENT mode with hp->zero_grads == 0 and a token count that is a
+ * multiple of 64, the update of each weight matrix is applied in the epilogue of
+ * its weight-gradient product, from the accumulators (the gradient is not read
+ * back; in TM_GRAD_TRANSIENT mode it is not stored either), and the flat sweep
+ * covers the vectors between the matrices; the results are the same bits.  Uses internal streams that are
  * ordered after everything enqueued on `stream` so far, and `stream` waits for
  * them before the call's work counts as done.  (Shadow iteration, section 4.2:
  * the last steps of the iteration the sandbox replays.)

@@ -21,6 +21,7 @@ TM_DTYPE_FP32, TM_DTYPE_BF16 = 0, 1
 TM_NORM_LAYERNORM, TM_NORM_RMSNORM = 0, 1
 TM_ACT_GELU_TANH, TM_ACT_GELU_ERF, TM_ACT_SWIGLU = 0, 1, 2
 TM_POS_NONE, TM_POS_ROTARY = 0, 1
+TM_GRAD_ADD, TM_GRAD_STORE, TM_GRAD_TRANSIENT = 0, 1, 2
 TM_COMM_PASS, TM_COMM_RECORD, TM_COMM_REPLAY = 0, 1, 2
 TM_SCOPE_TP, TM_SCOPE_PP, TM_SCOPE_DP = 1, 2, 4
 TM_COLL_ALL_REDUCE, TM_COLL_RECV, TM_COLL_SEND, TM_COLL_BARRIER = 0, 1, 2, 3
@@ -256,8 +257,9 @@ def tm_stage_tune(handle: int, stream: int = 0) -> None:
     _check(lib().tm_stage_tune(handle, stream))
 
 
-def tm_stage_grad_mode(handle: int, overwrite: bool) -> None:
-    _check(lib().tm_stage_grad_mode(handle, int(overwrite)))
+def tm_stage_grad_mode(handle: int, mode: int) -> None:
+    """mode: TM_GRAD_ADD (0 / False), TM_GRAD_STORE (1 / True), TM_GRAD_TRANSIENT (2)."""
+    _check(lib().tm_stage_grad_mode(handle, int(mode)))
 
 
 def tm_stage_destroy(handle: int) -> None:

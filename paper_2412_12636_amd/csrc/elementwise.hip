@@ -2,6 +2,7 @@
 // All HBM-bound: 16-byte accesses, fp32 arithmetic.
 #include <math.h>
 
+#include "adam.h"
 #include "common.h"
 #include "../../include/tm_ops.h"
 
@@ -121,19 +122,6 @@ __global__ __launch_bounds__(kEwThreads) void rotary_kernel(T *buf, int64_t rows
     row[hd * d + j] = from_f32<T>(lo * c - hi * s);
     row[hd * d + j + half] = from_f32<T>(hi * c + lo * s);
   }
-}
-
-struct AdamScalars {
-  float lr, beta1, beta2, one_minus_beta1, one_minus_beta2, eps, weight_decay, grad_scale, inv_bc1, inv_bc2;
-};
-
-__device__ __forceinline__ void adam_one(float &p, float g, float &m, float &v, const AdamScalars &a) {
-  g *= a.grad_scale;
-  m = a.beta1 * m + a.one_minus_beta1 * g;
-  v = a.beta2 * v + a.one_minus_beta2 * g * g;
-  const float mhat = m * a.inv_bc1;
-  const float vhat = v * a.inv_bc2;
-  p = p - a.lr * (mhat / (sqrtf(vhat) + a.eps) + a.weight_decay * p);
 }
 
 // One wave per block measured 3 % faster than four on this sweep (finer units for the dispatcher).
@@ -358,17 +346,7 @@ int adam_launch(int64_t n, float *p, float *g, float *m, float *v, void *p_bf16,
   if (((uintptr_t)p | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v) & 15 || ((uintptr_t)p_bf16 & 7))
     return fail(TM_EALIGN, "adam: arrays must be 16-byte aligned");
   if (n == 0) return TM_OK;
-  AdamScalars a;
-  a.lr = (float)hp->lr;
-  a.beta1 = (float)hp->beta1;
-  a.beta2 = (float)hp->beta2;
-  a.one_minus_beta1 = (float)(1.0 - hp->beta1);  // differences taken in double: 1 - 0.999 in fp32 is off by 6e-5
-  a.one_minus_beta2 = (float)(1.0 - hp->beta2);
-  a.eps = (float)hp->eps;
-  a.weight_decay = (float)hp->weight_decay;
-  a.grad_scale = (float)hp->grad_scale;
-  a.inv_bc1 = (float)(1.0 / (1.0 - pow(hp->beta1, (double)step)));
-  a.inv_bc2 = (float)(1.0 / (1.0 - pow(hp->beta2, (double)step)));
+  const AdamScalars a = make_adam_scalars(hp, step);
   const bool lowp = p_bf16 != nullptr, zero = hp->zero_grads != 0;
   g_last_kernel = "adam_kernel";
   const int64_t nchunk = n / 4 > 0 ? n / 4 : 1;

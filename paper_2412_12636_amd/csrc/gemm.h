@@ -1,5 +1,6 @@
 // Internal GEMM interface shared by the plain-ALU and the MFMA kernels.
 #pragma once
+#include "adam.h"
 #include "common.h"
 
 namespace tmk {
@@ -8,6 +9,8 @@ namespace tmk {
 // c_mode 0: C (stage dtype, row stride ldc) = result (+ bias[n]) (+ residual[m*ldc + n])
 // c_mode 1: C is fp32 and the result is added to it (weight gradients, accumulating)
 // c_mode 2: C is fp32 and is overwritten with the result (first micro-batch of an iteration)
+// c_mode 3: as 2, and the epilogue applies the Adam update of `adam` with the result as the gradient (the gradient is
+//           still stored; what is saved is reading it back, and the update overlaps the products of other blocks)
 struct GemmArgs {
   int64_t M, N, K;
   const void *A;
@@ -26,6 +29,7 @@ struct GemmArgs {
   // Kernel side: block row y of the grid reduces over the y-th of k_splits equal parts of K and writes the
   // y-th of k_splits results [M, ldc] behind C (c_mode 2).
   int k_splits = 1;
+  const AdamTarget *adam = nullptr;  // c_mode 3
 };
 
 int gemm_generic(int dtype, const GemmArgs &g, hipStream_t s);
@@ -42,6 +46,11 @@ int64_t gemm_mfma_splitk_bytes(const GemmArgs &g);
 // and shape use the fastest.  Overwrites every C; waits for the stream.  Without it a cost model picks.
 int gemm_mfma_tune(const GemmArgs *variants, int n, hipStream_t s);
 // Number of tile configurations, and a process-wide override (index, or -1 for the automatic choice).
+// dw[N,K] = dy[T,N]^T x[T,K] (bf16 operands) with the Adam update of those N*K parameters in the product's
+// epilogue.  `supported` says whether the shapes and pointers allow it (matrix-core path, T a multiple of 64).
+bool linear_wgrad_adam_supported(int64_t T, int64_t N, int64_t K, const void *dy, const void *x, const float *dw);
+int linear_wgrad_adam(int64_t T, int64_t N, int64_t K, const void *dy, const void *x, float *dw, const AdamTarget &target,
+                      hipStream_t s);
 int gemm_mfma_config_count();
 int gemm_mfma_force_config(int index);
 

@@ -77,6 +77,7 @@ struct MfmaGemmParams {
   const bf16 *residual;
   int tiles_m, tiles_n;
   uint32_t a_bytes, b_bytes, c_bytes;  // extents of the tensors, for the buffer descriptors
+  AdamTarget adam;                     // EPI 3 only
 };
 
 // Block id -> output tile.  Hardware block ids go round-robin over the 8 XCDs; ids are first
@@ -113,6 +114,49 @@ template <int EPI> __device__ __forceinline__ f32x16 mfma_for(bf16x8 a, bf16x8 b
 template <int TM, int TN, int EPI>
 __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (&acc)[TM][TN], int row_base,
                                          int col_base, int l32, int hh) {
+  if constexpr (EPI == 3) {
+    // weight gradient with the Adam update of its parameters: per accumulator register (two whole 128-byte
+    // lines per wave) the three state reads are in flight together; gradient, state and the bf16 copy are
+    // streamed past the caches
+    constexpr int kNonTemporal = 2;
+    const rsrc_t rc = make_rsrc(p.C, p.c_bytes);
+    const rsrc_t rp = make_rsrc(p.adam.master, p.c_bytes), rm = make_rsrc(p.adam.exp_avg, p.c_bytes);
+    const rsrc_t rv = make_rsrc(p.adam.exp_avg_sq, p.c_bytes), rl = make_rsrc(p.adam.lowp, p.c_bytes / 2);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int col = col_base + j * 32 + l32;
+        const bool col_ok = col < p.N;
+        uint32_t off[16];
+        float pw[16], mw[16], vw[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = row_base + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+          off[v] = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          pw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rp, off[v], 0, kNonTemporal));
+          mw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off[v], 0, kNonTemporal));
+          vw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, off[v], 0, kNonTemporal));
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float g = acc[i][j][v];
+          adam_one(pw[v], g, mw[v], vw[v], p.adam.a);
+          if (p.adam.store_grad)
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, g), rc, off[v], 0, kNonTemporal);
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, pw[v]), rp, off[v], 0, kNonTemporal);
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, mw[v]), rm, off[v], 0, kNonTemporal);
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, vw[v]), rv, off[v], 0, kNonTemporal);
+          const bf16 lo = (bf16)pw[v];
+          __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, lo), rl, col_ok ? off[v] >> 1 : 0xfffffff0u, 0,
+                                                kNonTemporal);
+        }
+      }
+    return;
+  }
   if constexpr (EPI != 0) {
     // fp32 results (weight gradients): whole lines, written once and next read by the optimizer: streamed
     // past the caches, which keeps the operands of the following products resident
@@ -824,6 +868,7 @@ template <bool A_KC, bool B_KC, int EPI> static MfmaGemmParams make_params(const
   p.a_bytes = (uint32_t)((A_KC ? g.M * g.a_rs : g.K * g.a_cs) * 2);
   p.b_bytes = (uint32_t)((B_KC ? g.N * g.b_rs : g.K * g.b_cs) * 2);
   p.c_bytes = (uint32_t)(g.M * g.ldc * (EPI == 0 ? 2 : 4));
+  if (EPI == 3 && g.adam) p.adam = *g.adam;
   return p;
 }
 
@@ -849,6 +894,7 @@ static int launch_pipe(const GemmArgs &g, hipStream_t s) {
   if (nblk > 0x7fffffff) return fail(TM_ESIZE, "gemm_mfma: too many tiles");
   static const std::string name = kernel_tag(NSB == 3 ? (NSA == 3 ? "gemm_pipe33_kernel" : "gemm_pipe23_kernel") : "gemm_pipe_kernel", BM, BN, WGM, WGN, A_KC, B_KC, EPI);
   g_last_kernel = name.c_str();
+  if (EPI == 3 && !g.adam) return fail(TM_EINVAL, "gemm_mfma: the fused update needs its target");
   if (g.k_splits > 1 && (EPI != 2 || g.K % ((int64_t)BK * g.k_splits) != 0))
     return fail(TM_EINVAL, "gemm_mfma: split reduction needs whole steps per part and fp32 results");
   gemm_pipe_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, EPI, NSA, NSB>

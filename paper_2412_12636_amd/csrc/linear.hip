@@ -62,5 +62,20 @@ extern "C" int tm_op_linear_wgrad(int dtype, int64_t T, int64_t N, int64_t K, co
   return run(dtype, g, (hipStream_t)stream);
 }
 
+namespace tmk {
+bool linear_wgrad_adam_supported(int64_t T, int64_t N, int64_t K, const void *dy, const void *x, const float *dw) {
+  if (T <= 0 || N <= 0 || K <= 0 || T % 64 != 0) return false;
+  GemmArgs g{N, K, T, dy, 1, N, x, 1, K, const_cast<float *>(dw), K, nullptr, nullptr, 3};
+  return gemm_mfma_supported(g);
+}
+int linear_wgrad_adam(int64_t T, int64_t N, int64_t K, const void *dy, const void *x, float *dw, const AdamTarget &target,
+                      hipStream_t s) {
+  if (!linear_wgrad_adam_supported(T, N, K, dy, x, dw)) return fail(TM_ESIZE, "linear_wgrad_adam: shape not supported");
+  GemmArgs g{N, K, T, dy, 1, N, x, 1, K, dw, K, nullptr, nullptr, 3};
+  g.adam = &target;
+  return gemm_mfma(g, s);
+}
+}  // namespace tmk
+
 extern "C" int tm_gemm_config_count(void) { return gemm_mfma_config_count(); }
 extern "C" int tm_gemm_force_config(int index) { return gemm_mfma_force_config(index); }

@@ -238,7 +238,7 @@ struct tm_stage {
   Plan plan;
   int64_t n_params;
   bool have_fwd;
-  bool grad_overwrite = false;
+  int grad_mode = TM_GRAD_ADD;
   std::vector<TensorInfo> tensors;
   // backward pass: the weight-gradient products run on a second stream beside the chain of input gradients
   hipStream_t side = nullptr;
@@ -340,9 +340,10 @@ extern "C" void tm_stage_destroy(tm_stage_t *st) {
   delete st;
 }
 
-extern "C" int tm_stage_grad_mode(tm_stage_t *st, int overwrite) {
+extern "C" int tm_stage_grad_mode(tm_stage_t *st, int mode) {
   if (!st) return fail(TM_EINVAL, "grad_mode: NULL handle");
-  st->grad_overwrite = overwrite != 0;
+  if (mode < TM_GRAD_ADD || mode > TM_GRAD_TRANSIENT) return fail(TM_EINVAL, "grad_mode: unknown mode %d", mode);
+  st->grad_mode = mode;
   return TM_OK;
 }
 
@@ -574,7 +575,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
   const Plan &pl = st->plan;
   void *red = ws + pl.reduce;
   const bool bias = c.has_bias != 0;
-  const int acc = st->grad_overwrite ? 0 : 1;
+  const int acc = st->grad_mode == TM_GRAD_ADD ? 1 : 0;
   const double es = (double)d.es, Th = (double)d.T * d.h;
   const double attn_flops = 2.0 * c.micro_batch * c.n_q_heads * (double)c.seq * c.seq * c.head_dim;
   auto mm = [&](int64_t n, int64_t kk) { return 2.0 * d.T * n * kk; };
@@ -615,6 +616,29 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
   if (hp && comm_intercepts(cm, TM_SCOPE_DP))
     return fail(TM_ESTATE, "stage_bwd_adam: the attached hook intercepts the data-parallel scope; the update must follow tm_stage_grad_sync");
   const int64_t act_bytes = d.T * d.h * d.es;
+  // tm_stage_bwd_adam with the gradients in overwrite mode: the update of a weight matrix rides in the epilogue of
+  // its weight-gradient product (the gradient is still stored, but never read back, and the state streams while
+  // other blocks of the product still multiply); what is left for the flat sweep are the vectors between the
+  // matrices.  TM_ADAM_UNFUSED=1 keeps the whole update in the flat sweep.
+  const bool fuse = hp && acc == 0 && dt == TM_DTYPE_BF16 && !hp->zero_grads && getenv("TM_ADAM_UNFUSED") == nullptr;
+  const AdamScalars ascal = hp ? make_adam_scalars(hp, step) : AdamScalars{};
+  struct Range { int64_t first, count; };
+  std::vector<Range> fused;  // this layer's matrices already updated, element ranges relative to the layer's block
+  auto wgrad = [&](int64_t pb, int64_t w_off, int64_t N, int64_t K, const void *dyp, const void *xp) -> int {
+    float *dw = grads + pb + w_off;
+    if (fuse && linear_wgrad_adam_supported(d.T, N, K, dyp, xp, dw)) {
+      AdamTarget t;
+      t.master = st->buf.master + pb + w_off;
+      t.exp_avg = st->buf.exp_avg + pb + w_off;
+      t.exp_avg_sq = st->buf.exp_avg_sq + pb + w_off;
+      t.lowp = (bf16 *)st->buf.params + pb + w_off;
+      t.a = ascal;
+      t.store_grad = st->grad_mode != TM_GRAD_TRANSIENT;
+      fused.push_back({w_off, N * K});
+      return linear_wgrad_adam(d.T, N, K, dyp, xp, dw, t, sw);
+    }
+    return tm_op_linear_wgrad(dt, d.T, N, K, dyp, xp, dw, acc, sw);
+  };
   const void *dy = dy_in;
   if (cm) {
     void *at = const_cast<void *>(dy_in);
@@ -641,7 +665,8 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     void *dg = (c.act == TM_ACT_SWIGLU) ? (void *)(ws + pl.dmid) : (void *)(ws + pl.dwide);
     TM_STEP(mm(d.h, d.f), 0, tm_op_linear_dgrad_ws(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
-    TM_STEP(mm(d.h, d.f), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.f, dy, ws + k.g, G(o.w_fc2), acc, sw));
+    fused.clear();
+    TM_STEP(mm(d.h, d.f), 0, wgrad(pb, o.w_fc2, d.h, d.f, dy, ws + k.g));
     if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, acc, s));
     // activation
     void *du = ws + pl.dwide;
@@ -651,7 +676,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_dgrad_ws(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, ws + pl.splitk, pl.splitk_bytes, s));
     if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_D_MLP_IN, dt, dc, act_bytes, s));
     TM_TRY(fork());
-    TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.f1, d.h, du, ws + k.c, G(o.w_fc1), acc, sw));
+    TM_STEP(mm(d.f1, d.h), 0, wgrad(pb, o.w_fc1, d.f1, d.h, du, ws + k.c));
     if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, acc, s));
     // c = Norm(x1): dx1 = dy + norm gradient
     void *dx1 = ws + pl.dx1;
@@ -662,7 +687,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     // x1 = x + ctx Wout^T + bout
     TM_STEP(mm(d.h, d.A), 0, tm_op_linear_dgrad_ws(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
-    TM_STEP(mm(d.h, d.A), 0, tm_op_linear_wgrad(dt, d.T, d.h, d.A, dx1, ws + k.ctx, G(o.w_out), acc, sw));
+    TM_STEP(mm(d.h, d.A), 0, wgrad(pb, o.w_out, d.h, d.A, dx1, ws + k.ctx));
     if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, acc, s));
     // attention, rotary
     TM_STEP(2 * attn_flops, 0,
@@ -677,7 +702,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_dgrad_ws(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, ws + pl.splitk, pl.splitk_bytes, s));
     if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_D_ATTN_IN, dt, da, act_bytes, s));
     TM_TRY(fork());
-    TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_wgrad(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, ws + k.a, G(o.w_qkv), acc, sw));
+    TM_STEP(mm(d.nqkv, d.h), 0, wgrad(pb, o.w_qkv, d.nqkv, d.h, ws + pl.dqkv, ws + k.a));
     if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, acc, s));
     // a = Norm(x): dx = dx1 + norm gradient
     TM_STEP(0, 4 * es * Th,
@@ -697,7 +722,14 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
       const double per_param = 28.0 + (d.es == 2 ? 2.0 : 0.0) + (hp->zero_grads ? 4.0 : 0.0);
       hipStream_t s_keep = s;
       s = so;  // TM_STEP brackets the stream named s
-      TM_STEP(0, per_param * (double)o.total, adam_slice(st, pb, o.total, hp, step, so));
+      // the flat sweep over what the products have not updated: the stretches between the fused matrices
+      std::sort(fused.begin(), fused.end(), [](const Range &a, const Range &b) { return a.first < b.first; });
+      int64_t at = 0;
+      for (size_t i = 0; i <= fused.size(); ++i) {
+        const int64_t end = i < fused.size() ? fused[i].first : o.total;
+        if (end > at) TM_STEP(0, per_param * (double)(end - at), adam_slice(st, pb + at, end - at, hp, step, so));
+        if (i < fused.size()) at = fused[i].first + fused[i].count;
+      }
       s = s_keep;
     }
   }

@@ -155,11 +155,15 @@ def test_tuning_changes_speed_only(env):
     st.close()
 
 
-def test_backward_with_overlapped_optimizer_equals_the_two_calls(env):
-    """tm_stage_bwd_adam = tm_stage_bwd then tm_adam_step, bit for bit: master weights, both moments, the
-    bf16 copy, the input gradient; two iterations, so that the second forward pass sees updated weights."""
+@pytest.mark.parametrize("cfg", [SMALL_GPT.replace(n_layers=3), SMALL_GPT.replace(n_layers=3, seq=192),
+                                 SMALL_LLAMA.replace(n_layers=2, seq=256), TINY],
+                         ids=["ragged_tokens_flat_sweep", "fused_into_the_products", "fused_llama", "fp32_flat_sweep"])
+def test_backward_with_overlapped_optimizer_equals_the_two_calls(env, cfg):
+    """tm_stage_bwd_adam = tm_stage_bwd then tm_adam_step, bit for bit: gradients, master weights, both moments, the
+    bf16 copy, the input gradient; two iterations, so that the second forward pass sees updated weights.  With a
+    token count that is a multiple of 64 the matrices' updates ride in the weight-gradient products' epilogues and
+    the flat sweep covers the vectors between them; otherwise (and for fp32 stages) the flat sweep does it all."""
     torch, tm = env
-    cfg = SMALL_GPT.replace(n_layers=3)
     flat = si.make_flat_params(cfg)
     x, dy = to_dev(torch, si.make_x(cfg), cfg.dtype), to_dev(torch, si.make_dy(cfg), cfg.dtype)
     a, b = GpuStage(torch, tm, cfg, flat), GpuStage(torch, tm, cfg, flat)
@@ -174,9 +178,27 @@ def test_backward_with_overlapped_optimizer_equals_the_two_calls(env):
         tm.tm_stage_bwd_adam(b.handle, dy, b.dx, hp, step, stream_ptr(torch))
         torch.cuda.synchronize()
         for name in ("y", "dx", "grads", "master", "m", "v", "params"):
-            assert torch.equal(getattr(a, name), getattr(b, name)), (step, name)
+            if getattr(a, name) is not None:                  # fp32 stages have no separate master copy
+                assert torch.equal(getattr(a, name), getattr(b, name)), (step, name)
+    # transient gradients: the same update, the vectors' gradients stored as before, the matrices' unspecified
+    c = GpuStage(torch, tm, cfg, flat)
+    tm.tm_stage_grad_mode(c.handle, tm.TM_GRAD_TRANSIENT)
+    c.grads.fill_(3.0)
+    for step in (1, 2):
+        c.fwd(x)
+        tm.tm_stage_bwd_adam(c.handle, dy, c.dx, hp, step, stream_ptr(torch))
+    torch.cuda.synchronize()
+    for name in ("y", "dx", "master", "m", "v", "params"):
+        if getattr(a, name) is not None:
+            assert torch.equal(getattr(a, name), getattr(c, name)), name
+    for name, off, shape in tm.tm_stage_param_layout(cfg):
+        if shape[1] == 1:
+            assert torch.equal(a.grads[off:off + shape[0]], c.grads[off:off + shape[0]]), name
+    with pytest.raises(tm.TmError):
+        tm.tm_stage_grad_mode(c.handle, 3)
     a.close()
     b.close()
+    c.close()
 
 
 def test_backward_on_one_stream_equals_backward_on_two(env, monkeypatch):
