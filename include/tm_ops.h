@@ -70,10 +70,17 @@ int tm_op_norm_fwd(int dtype, int kind, int64_t T, int64_t h, double eps, const 
 
 /* dx[T,h] = (dres or 0) + gradient of the norm w.r.t. x for output gradient dout; dgain[h] (+)=,
  * doffset[h] (+)= (LayerNorm), accumulate as above.  dres may be NULL and may alias dx.
- * scratch: see above with width 2h. */
+ * scratch: see above with width 3h. */
 int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x,
                    const float *mean, const float *rstd, const void *gain, const void *dres,
                    void *dx, float *dgain, float *doffset, void *scratch, int accumulate, void *stream);
+
+/* As tm_op_norm_bwd, and dx_colsum[h] (+)= column sums of dx as stored: when dx is the output gradient of a linear map
+ * with a bias (dres = that map's output gradient path), this is the bias gradient, without another pass over dx. */
+int tm_op_norm_bwd_colsum(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x,
+                          const float *mean, const float *rstd, const void *gain, const void *dres,
+                          void *dx, float *dgain, float *doffset, float *dx_colsum, void *scratch, int accumulate,
+                          void *stream);
 
 /* g[T,f] = gelu(u[T,f])  or  silu(u[T,0:f]) * u[T,f:2f]  for TM_ACT_SWIGLU (u is [T,2f]). */
 int tm_op_act_fwd(int dtype, int act, int64_t T, int64_t f, const void *u, void *g, void *stream);

@@ -101,6 +101,7 @@ EXPORTS = {
     "tm_op_bias_grad": (C.c_int, [C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 3 + [C.c_int, C.c_void_p]),
     "tm_op_norm_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64, C.c_double] + [C.c_void_p] * 7),
     "tm_op_norm_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 10 + [C.c_int, C.c_void_p]),
+    "tm_op_norm_bwd_colsum": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 11 + [C.c_int, C.c_void_p]),
     "tm_op_act_fwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 3),
     "tm_op_act_bwd": (C.c_int, [C.c_int, C.c_int, C.c_int64, C.c_int64] + [C.c_void_p] * 4),
     "tm_op_rotary": (C.c_int, [C.c_int] + [C.c_int64] * 5 + [C.c_double, C.c_int, C.c_void_p, C.c_void_p]),
@@ -461,3 +462,9 @@ def tm_moe_bwd(cfg, params, c, dout, dc, grads, accumulate, workspace, stream: i
         workspace_bytes = int(workspace.numel()) * int(workspace.element_size())
     _check(lib().tm_moe_bwd(C.byref(make_moe_config(cfg)), _ptr(params), _ptr(c), _ptr(dout), _ptr(dc), _ptr(grads), accumulate,
                             _ptr(workspace), workspace_bytes, stream))
+
+
+def tm_op_norm_bwd_colsum(dtype, kind, T, h, dout, x, mean, rstd, gain, dres, dx, dgain, doffset, dx_colsum, scratch,
+                          accumulate=1, stream=0):
+    _check(lib().tm_op_norm_bwd_colsum(dtype, kind, T, h, _ptr(dout), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gain), _ptr(dres),
+                                       _ptr(dx), _ptr(dgain), _ptr(doffset), _ptr(dx_colsum), _ptr(scratch), accumulate, stream))

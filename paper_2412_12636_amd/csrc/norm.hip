@@ -5,8 +5,8 @@
 
 namespace tmk {
 
-constexpr int kNormThreads = 256;
-constexpr int kNormMaxChunks = 8;  // 16-byte chunks per thread: hidden <= 256 * 8 * Vec::N
+constexpr int kNormThreads = 512;
+constexpr int kNormMaxChunks = 4;  // 16-byte chunks per thread: hidden <= 512 * 4 * Vec::N
 
 // ---------------------------------------------------------------------------------------
 // forward: one block per token row; the row stays in registers between the passes.
@@ -76,9 +76,11 @@ __global__ __launch_bounds__(kNormThreads) void norm_fwd_kernel(
 // ---------------------------------------------------------------------------------------
 // backward: block b handles rows b, b+G, ...; each thread keeps the gain/offset gradient of
 // its own columns in registers and writes one partial row per block at the end.
-// partial layout: [G][2][h] fp32 (gain partials, then offset partials)
+// partial layout: [G][3][h] fp32 (gain partials, offset partials, and with XSUM the column sums of the
+// stored dx: the gradient of the bias of the linear map that produced x's residual input, which would
+// otherwise cost one more pass over dx)
 // ---------------------------------------------------------------------------------------
-template <typename T, int KIND, int NCH>
+template <typename T, int KIND, int NCH, bool XSUM>
 __global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
     const T *__restrict__ dout, const T *__restrict__ x, const float *__restrict__ mean,
     const float *__restrict__ rstd, const T *__restrict__ gain, const T *dres, T *dx,
@@ -87,12 +89,15 @@ __global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
   __shared__ float red[2 * kNormThreads / kWave];
   const uint32_t row_bytes = (uint32_t)h * sizeof(T);
   const rsrc_t rg = make_rsrc(gain, row_bytes);
-  float gacc[NCH][VN], oacc[NCH][VN], gn[NCH][VN];
+  float gacc[NCH][VN], oacc[NCH][VN], gn[NCH][VN], xacc[XSUM ? NCH : 1][VN];
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     buf_load_vec<T>(rg, (threadIdx.x + c * kNormThreads) * 16u, gn[c]);
 #pragma unroll
-    for (int i = 0; i < VN; ++i) gacc[c][i] = oacc[c][i] = 0.f;
+    for (int i = 0; i < VN; ++i) {
+      gacc[c][i] = oacc[c][i] = 0.f;
+      if (XSUM) xacc[c][i] = 0.f;
+    }
   }
   for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
     const rsrc_t rd = make_rsrc(dout + row * h, row_bytes), rx = make_rsrc(x + row * h, row_bytes);
@@ -132,12 +137,16 @@ __global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
 #pragma unroll
-      for (int i = 0; i < VN; ++i) res[c][i] += (w[c][i] - mw - xh[c][i] * mwx) * rs;
+      for (int i = 0; i < VN; ++i) {
+        res[c][i] += (w[c][i] - mw - xh[c][i] * mwx) * rs;
+        if (XSUM) xacc[c][i] += to_f32(from_f32<T>(res[c][i]));  // the value as stored
+      }
       buf_store_vec<T>(ro, (threadIdx.x + c * kNormThreads) * 16u, res[c]);
     }
   }
-  const rsrc_t rp = make_rsrc(partial + (int64_t)blockIdx.x * 2 * h, (uint32_t)h * 4u);
-  const rsrc_t rq = make_rsrc(partial + (int64_t)blockIdx.x * 2 * h + h, (uint32_t)h * 4u);
+  const rsrc_t rp = make_rsrc(partial + (int64_t)blockIdx.x * 3 * h, (uint32_t)h * 4u);
+  const rsrc_t rq = make_rsrc(partial + (int64_t)blockIdx.x * 3 * h + h, (uint32_t)h * 4u);
+  const rsrc_t rz = make_rsrc(partial + (int64_t)blockIdx.x * 3 * h + 2 * h, (uint32_t)h * 4u);
 #pragma unroll
   for (int c = 0; c < NCH; ++c) {
     const uint32_t col = (threadIdx.x + c * kNormThreads) * VN;
@@ -151,7 +160,49 @@ __global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
       }
       buf_store_vec<float>(rp, (col + v4 * 4) * 4u, a);
       buf_store_vec<float>(rq, (col + v4 * 4) * 4u, b);
+      if (XSUM) {
+        float z[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) z[i] = xacc[c][v4 * 4 + i];
+        buf_store_vec<float>(rz, (col + v4 * 4) * 4u, z);
+      }
     }
+  }
+}
+
+// the three column reductions of the norm's backward pass in one launch: slice s of the partial rows goes to outs[s]
+// (NULL: skipped); same summation order as reduce_partials_kernel
+struct ReduceOuts {
+  float *out[3];
+};
+__global__ __launch_bounds__(256) void reduce_partials3_kernel(const float *__restrict__ partial, int R, int h, ReduceOuts outs,
+                                                               int accumulate) {
+  __shared__ float sm[4][64];
+  const int lane = threadIdx.x & 63, ry = threadIdx.x >> 6;
+  const int per_slice = (h + 63) / 64;
+  const int slice = blockIdx.x / per_slice, c = (blockIdx.x % per_slice) * 64 + lane;
+  float *out = outs.out[slice];
+  if (!out) return;  // uniform over the block
+  const int64_t ld = 3 * (int64_t)h;
+  const float *src = partial + (int64_t)slice * h;
+  float s = 0.f;
+  if (c < h) {
+    int r = ry;
+    for (; r + 12 < R; r += 16) {
+      const float a0 = src[(int64_t)r * ld + c], a1 = src[(int64_t)(r + 4) * ld + c];
+      const float a2 = src[(int64_t)(r + 8) * ld + c], a3 = src[(int64_t)(r + 12) * ld + c];
+      s += a0;
+      s += a1;
+      s += a2;
+      s += a3;
+    }
+    for (; r < R; r += 4) s += src[(int64_t)r * ld + c];
+  }
+  sm[ry][lane] = s;
+  __syncthreads();
+  if (ry == 0 && c < h) {
+    const float t = ((sm[0][lane] + sm[1][lane]) + sm[2][lane]) + sm[3][lane];
+    out[c] = accumulate ? out[c] + t : t;
   }
 }
 
@@ -258,18 +309,18 @@ static int norm_fwd_t(int kind, int64_t rows, int h, float eps, const void *x, c
   return check_launch("norm_fwd");
 }
 
-template <typename T>
+template <typename T, bool XSUM>
 static int norm_bwd_t(int kind, int64_t rows, int h, const void *dout, const void *x, const float *mean,
                       const float *rstd, const void *gain, const void *dres, void *dx, float *partial, hipStream_t s) {
   const int G = norm_bwd_blocks(rows);
   const int nch = pick_nch(h, Vec<T>::N);
   g_last_kernel = "norm_bwd_kernel";
   if (kind == TM_NORM_LAYERNORM) {
-    TM_NCH_SWITCH(nch, (norm_bwd_kernel<T, TM_NORM_LAYERNORM, NCH><<<G, kNormThreads, 0, s>>>(
+    TM_NCH_SWITCH(nch, (norm_bwd_kernel<T, TM_NORM_LAYERNORM, NCH, XSUM><<<G, kNormThreads, 0, s>>>(
                            (const T *)dout, (const T *)x, mean, rstd, (const T *)gain, (const T *)dres, (T *)dx,
                            partial, rows, h)))
   } else {
-    TM_NCH_SWITCH(nch, (norm_bwd_kernel<T, TM_NORM_RMSNORM, NCH><<<G, kNormThreads, 0, s>>>(
+    TM_NCH_SWITCH(nch, (norm_bwd_kernel<T, TM_NORM_RMSNORM, NCH, XSUM><<<G, kNormThreads, 0, s>>>(
                            (const T *)dout, (const T *)x, mean, rstd, (const T *)gain, (const T *)dres, (T *)dx,
                            partial, rows, h)))
   }
@@ -291,7 +342,7 @@ static int check_width(const char *what, int dtype, int64_t T, int64_t h) {
 extern "C" int64_t tm_op_reduce_scratch_bytes(int64_t T, int64_t width) {
   if (T <= 0 || width <= 0) return TM_EINVAL;
   const int64_t g1 = norm_bwd_blocks(T), g2 = colsum_groups(T);
-  return (g1 > g2 ? g1 : g2) * width * (int64_t)sizeof(float);
+  return (g1 > g2 ? g1 : g2) * width * (int64_t)sizeof(float);  // callers of the norm pass width = 3h
 }
 
 extern "C" int tm_op_norm_fwd(int dtype, int kind, int64_t T, int64_t h, double eps, const void *x, const void *gain,
@@ -308,9 +359,9 @@ extern "C" int tm_op_norm_fwd(int dtype, int kind, int64_t T, int64_t h, double 
              : norm_fwd_t<float>(kind, T, (int)h, (float)eps, x, gain, offset, out, mean, rstd, s);
 }
 
-extern "C" int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x,
-                              const float *mean, const float *rstd, const void *gain, const void *dres, void *dx,
-                              float *dgain, float *doffset, void *scratch, int accumulate, void *stream) {
+static int norm_bwd_any(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x, const float *mean,
+                        const float *rstd, const void *gain, const void *dres, void *dx, float *dgain, float *doffset,
+                        float *dx_colsum, void *scratch, int accumulate, void *stream) {
   if (int e = check_width("norm_bwd", dtype, T, h)) return e;
   if (kind != TM_NORM_LAYERNORM && kind != TM_NORM_RMSNORM) return fail(TM_EINVAL, "norm_bwd: unknown kind %d", kind);
   if (!dout || !x || !rstd || !gain || !dx || !dgain || !scratch || (kind == TM_NORM_LAYERNORM && (!mean || !doffset)))
@@ -319,15 +370,32 @@ extern "C" int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const v
   if (h > hmax) return fail(TM_ESIZE, "norm_bwd: width %lld above the limit %lld", (long long)h, (long long)hmax);
   hipStream_t s = (hipStream_t)stream;
   float *partial = (float *)scratch;
-  int e = dtype == TM_DTYPE_BF16
-              ? norm_bwd_t<bf16>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s)
-              : norm_bwd_t<float>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s);
+  int e;
+  if (dx_colsum)
+    e = dtype == TM_DTYPE_BF16 ? norm_bwd_t<bf16, true>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s)
+                               : norm_bwd_t<float, true>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s);
+  else
+    e = dtype == TM_DTYPE_BF16 ? norm_bwd_t<bf16, false>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s)
+                               : norm_bwd_t<float, false>(kind, T, (int)h, dout, x, mean, rstd, gain, dres, dx, partial, s);
   if (e) return e;
   const int G = norm_bwd_blocks(T);
-  const int nb = (int)ceil_div(h, 64);
-  reduce_partials_kernel<<<nb, 256, 0, s>>>(partial, G, 2 * h, (int)h, dgain, accumulate);
-  if (kind == TM_NORM_LAYERNORM) reduce_partials_kernel<<<nb, 256, 0, s>>>(partial + h, G, 2 * h, (int)h, doffset, accumulate);
+  ReduceOuts outs{{dgain, kind == TM_NORM_LAYERNORM ? doffset : nullptr, dx_colsum}};
+  reduce_partials3_kernel<<<3 * (int)ceil_div(h, 64), 256, 0, s>>>(partial, G, (int)h, outs, accumulate);
   return check_launch("norm_bwd reduce");
+}
+
+extern "C" int tm_op_norm_bwd(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x,
+                              const float *mean, const float *rstd, const void *gain, const void *dres, void *dx,
+                              float *dgain, float *doffset, void *scratch, int accumulate, void *stream) {
+  return norm_bwd_any(dtype, kind, T, h, dout, x, mean, rstd, gain, dres, dx, dgain, doffset, nullptr, scratch, accumulate, stream);
+}
+
+extern "C" int tm_op_norm_bwd_colsum(int dtype, int kind, int64_t T, int64_t h, const void *dout, const void *x,
+                                     const float *mean, const float *rstd, const void *gain, const void *dres, void *dx,
+                                     float *dgain, float *doffset, float *dx_colsum, void *scratch, int accumulate,
+                                     void *stream) {
+  if (!dx_colsum) return fail(TM_EINVAL, "norm_bwd_colsum: NULL pointer");
+  return norm_bwd_any(dtype, kind, T, h, dout, x, mean, rstd, gain, dres, dx, dgain, doffset, dx_colsum, scratch, accumulate, stream);
 }
 
 extern "C" int tm_op_bias_grad(int dtype, int64_t T, int64_t N, const void *dy, float *db, void *scratch,

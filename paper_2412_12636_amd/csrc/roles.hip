@@ -250,7 +250,7 @@ HeadPlan head_plan(int dtype, int64_t T, int64_t h, int64_t v_local) {
   p.logits = take(T * v_local * es);
   p.dhn = take(T * h * es);
   p.loss_t = take(T * 4);
-  p.reduce = take(tm_op_reduce_scratch_bytes(T, 2 * h));
+  p.reduce = take(tm_op_reduce_scratch_bytes(T, 3 * h));
   p.total = at;
   return p;
 }

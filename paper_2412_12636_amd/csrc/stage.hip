@@ -187,7 +187,7 @@ static Plan make_plan(const tm_stage_config_t *c) {
   p.dctx = take(T * A * es);
   p.dqkv = take(T * nqkv * es);
   p.dvec = take(tm_op_attn_bwd_scratch_bytes(c->dtype, c->seq, c->micro_batch, c->n_q_heads, c->n_kv_heads, c->head_dim));
-  const int64_t widest = std::max(std::max(2 * h, f1), std::max(nqkv, h));
+  const int64_t widest = std::max(std::max(3 * h, f1), std::max(nqkv, h));
   const int64_t n_params = layer_offsets(c).total * c->n_layers;
   p.reduce = take(std::max(tm_op_reduce_scratch_bytes(T, widest), tm_sq_sum_scratch_bytes(n_params)));
   p.splitk_bytes = 0;
@@ -667,7 +667,8 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     TM_TRY(fork());
     fused.clear();
     TM_STEP(mm(d.h, d.f), 0, wgrad(pb, o.w_fc2, d.h, d.f, dy, ws + k.g));
-    if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, acc, s));
+    // (below the top layer this bias gradient has come out of the first norm's backward pass of the layer above)
+    if (bias && l == c.n_layers - 1) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, acc, s));
     // activation
     void *du = ws + pl.dwide;
     TM_STEP(0, es * d.T * (d.f + 2 * d.f1), tm_op_act_bwd(dt, c.act, d.T, d.f, dg, ws + k.u, du, s));
@@ -680,15 +681,21 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, acc, s));
     // c = Norm(x1): dx1 = dy + norm gradient
     void *dx1 = ws + pl.dx1;
-    TM_STEP(0, 4 * es * Th,
-            tm_op_norm_bwd(dt, c.norm, d.T, d.h, dc, ws + k.x1, (const float *)(ws + k.mean2),
-                           (const float *)(ws + k.rstd2), P(o.norm2_gain), dy, dx1, G(o.norm2_gain),
-                           G(o.norm2_offset), red, acc, s));
+    // with biases the column sums of dx1, the out-projection's bias gradient, come out of the same pass
+    if (bias)
+      TM_STEP(0, 4 * es * Th,
+              tm_op_norm_bwd_colsum(dt, c.norm, d.T, d.h, dc, ws + k.x1, (const float *)(ws + k.mean2),
+                                    (const float *)(ws + k.rstd2), P(o.norm2_gain), dy, dx1, G(o.norm2_gain),
+                                    G(o.norm2_offset), G(o.b_out), red, acc, s));
+    else
+      TM_STEP(0, 4 * es * Th,
+              tm_op_norm_bwd(dt, c.norm, d.T, d.h, dc, ws + k.x1, (const float *)(ws + k.mean2),
+                             (const float *)(ws + k.rstd2), P(o.norm2_gain), dy, dx1, G(o.norm2_gain),
+                             G(o.norm2_offset), red, acc, s));
     // x1 = x + ctx Wout^T + bout
     TM_STEP(mm(d.h, d.A), 0, tm_op_linear_dgrad_ws(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
     TM_STEP(mm(d.h, d.A), 0, wgrad(pb, o.w_out, d.h, d.A, dx1, ws + k.ctx));
-    if (bias) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dx1, G(o.b_out), red, acc, s));
     // attention, rotary
     TM_STEP(2 * attn_flops, 0,
             tm_op_attn_bwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
@@ -705,10 +712,17 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     TM_STEP(mm(d.nqkv, d.h), 0, wgrad(pb, o.w_qkv, d.nqkv, d.h, ws + pl.dqkv, ws + k.a));
     if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, acc, s));
     // a = Norm(x): dx = dx1 + norm gradient
-    TM_STEP(0, 4 * es * Th,
-            tm_op_norm_bwd(dt, c.norm, d.T, d.h, da, ws + k.x, (const float *)(ws + k.mean1),
-                           (const float *)(ws + k.rstd1), P(o.norm1_gain), dx1, dx, G(o.norm1_gain),
-                           G(o.norm1_offset), red, acc, s));
+    // dx is the output gradient of the layer below: its column sums are that layer's FC2 bias gradient
+    if (bias && l > 0)
+      TM_STEP(0, 4 * es * Th,
+              tm_op_norm_bwd_colsum(dt, c.norm, d.T, d.h, da, ws + k.x, (const float *)(ws + k.mean1),
+                                    (const float *)(ws + k.rstd1), P(o.norm1_gain), dx1, dx, G(o.norm1_gain),
+                                    G(o.norm1_offset), grads + pb - o.total + o.b_fc2, red, acc, s));
+    else
+      TM_STEP(0, 4 * es * Th,
+              tm_op_norm_bwd(dt, c.norm, d.T, d.h, da, ws + k.x, (const float *)(ws + k.mean1),
+                             (const float *)(ws + k.rstd1), P(o.norm1_gain), dx1, dx, G(o.norm1_gain),
+                             G(o.norm1_offset), red, acc, s));
     dy = dx;
     if (hp) {
       // this layer's gradients: the products on the side stream and the norm / bias gradients on the main one

@@ -222,6 +222,14 @@ def test_gpt175b_full_depth_equals_chained_layers_and_layers_match_checker(env):
         tm.tm_stage_destroy(hl)
     torch.cuda.synchronize()
     assert torch.equal(dys[0], dx)
+    # Below the top layer the FC2 bias gradient (column sums of the layer's output gradient) comes out of the first
+    # norm's backward pass of the layer above, in a 1-layer stage out of the column-sum kernel: the same stored
+    # values added in another order.  Those entries agree to fp32 summation accuracy, everything else bit for bit.
+    for name, off, shape in tm.tm_stage_param_layout(cfg):
+        if name.endswith(".b_fc2") and not name.startswith(f"layer{cfg.n_layers - 1}."):
+            a, b = grads1[off:off + shape[0]].double(), grads[off:off + shape[0]].double()
+            assert float((a - b).abs().max() / b.abs().max()) <= 1e-5, name
+            grads1[off:off + shape[0]] = grads[off:off + shape[0]]       # checked: leave the rest to the exact comparison
     assert torch.equal(grads1, grads)
 
     for l in (0, cfg.n_layers - 1):

@@ -217,7 +217,7 @@ def test_norm_fwd_bwd(env, dtype, kind, T, h):
     dx = torch.empty((T, h), dtype=td, device="cuda")
     g0, o0 = rng.standard_normal(h).astype(np.float32), rng.standard_normal(h).astype(np.float32)
     dgain, doff = f32_dev(torch, g0), f32_dev(torch, o0)
-    scratch = torch.empty(tm.tm_op_reduce_scratch_bytes(T, 2 * h), dtype=torch.uint8, device="cuda")
+    scratch = torch.empty(tm.tm_op_reduce_scratch_bytes(T, 3 * h), dtype=torch.uint8, device="cuda")
     tm.tm_op_norm_bwd(dtype, kind, T, h, to_dev(torch, dout, dtype), xd, mean if ln else None, rstd, gd,
                       to_dev(torch, dres, dtype), dx, dgain, doff if ln else None, scratch, 1, s)
     rdx, rdg, rdo = so.norm_bwd(dout, xhat, r, gain.astype(np.float64), kind)
@@ -232,6 +232,23 @@ def test_norm_fwd_bwd(env, dtype, kind, T, h):
     assert rel_err(to_host(dgain), rdg) <= 1e-4
     if ln:
         assert rel_err(to_host(doff), rdo) <= 1e-4
+    # the variant that also returns the column sums of dx (a bias gradient without another pass): same dx, same
+    # gain / offset gradients bit for bit, and the sums of the values as stored
+    dx2 = torch.empty_like(dx)
+    dg2, do2 = torch.empty_like(dgain), torch.empty_like(doff)
+    c0 = rng.standard_normal(h).astype(np.float32)
+    csum = f32_dev(torch, c0)
+    tm.tm_op_norm_bwd(dtype, kind, T, h, to_dev(torch, dout, dtype), xd, mean if ln else None, rstd, gd,
+                      to_dev(torch, dres, dtype), dx, dgain, doff if ln else None, scratch, 0, s)
+    tm.tm_op_norm_bwd_colsum(dtype, kind, T, h, to_dev(torch, dout, dtype), xd, mean if ln else None, rstd, gd,
+                             to_dev(torch, dres, dtype), dx2, dg2, do2 if ln else None, csum, scratch, 0, s)
+    torch.cuda.synchronize()
+    assert torch.equal(dx, dx2) and torch.equal(dgain, dg2) and (not ln or torch.equal(doff, do2))
+    assert rel_err(to_host(csum), to_host(dx2).sum(axis=0)) <= 1e-5
+    tm.tm_op_norm_bwd_colsum(dtype, kind, T, h, to_dev(torch, dout, dtype), xd, mean if ln else None, rstd, gd,
+                             to_dev(torch, dres, dtype), dx2, dg2, do2 if ln else None, csum, scratch, 1, s)
+    assert rel_err(to_host(csum), 2.0 * to_host(dx2).sum(axis=0)) <= 1e-5
+    assert rel_err(to_host(csum), 2.0 * (rdx + dres).sum(axis=0)) <= tol_of(dtype)
 
 
 # ------------------------------------------------------------------ activations
