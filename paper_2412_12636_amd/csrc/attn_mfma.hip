@@ -71,13 +71,14 @@ struct FlashParams {
 };
 
 // ---- global -> LDS: one [64][128] tile, 4 wave-wide loads per wave -------------------------------
-struct TileLoader {
-  uint32_t voff[4];
+template <int NW = 4> struct TileLoaderN {
+  static constexpr int NL = 16 / NW;  // wave-wide loads per wave and tile
+  uint32_t voff[NL];
   // row_stride: elements between consecutive tile rows in global memory
   __device__ __forceinline__ void init(int64_t row_stride, int wave, int lane) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int idx = (i * 4 + wave) * 64 + lane;  // chunk position in the LDS tile
+    for (int i = 0; i < NL; ++i) {
+      const int idx = (i * NW + wave) * 64 + lane;  // chunk position in the LDS tile
       const int row = idx >> 4, c = unplace(idx & 15, row);
       voff[i] = (uint32_t)(((int64_t)row * row_stride + c * 8) * 2);
     }
@@ -88,11 +89,12 @@ struct TileLoader {
   __device__ __forceinline__ void issue(rsrc_t rs, char *tile, int64_t rows0, int64_t base, int wave) const {
     const uint32_t roff = (uint32_t)(rows0 * 2), soff = (uint32_t)(base * 2);
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * 4 + wave) * 1024), 16, voff[i] + roff, soff, 0,
+    for (int i = 0; i < NL; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_ptr_t)(tile + (i * NW + wave) * 1024), 16, voff[i] + roff, soff, 0,
                                                0);
   }
 };
+typedef TileLoaderN<4> TileLoader;
 
 // A-operand fragment, tile rows as MFMA rows: row r32 + lane%32, reduction slots 16ks + 8hh + 0..7
 __device__ __forceinline__ bf16x8 frag_rows(const char *tile, int r32, int ks, int lane) {
@@ -112,6 +114,36 @@ __device__ __forceinline__ bf16x8 frag_cols(const char *tile, int c32, int kk, i
   for (int t = 0; t < 2; ++t) {
     const int row = 16 * kk + 8 * t + 4 * (g >> 1) + (s >> 2);
     const char *a = tile + row * ROWB + (place(c, row) << 4) + (half << 3);
+    x.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(a));
+  }
+  return x.v;
+}
+// The same two fragment reads with the address arithmetic written out.  Every lane-dependent part of an address
+// fits one per-lane base (relative to the tile, which must start on a 256-byte boundary); what changes with the
+// reduction slice, the 32-column block and the row group is an XOR of the 16-byte chunk index with a compile-time
+// constant plus a multiple of the row pitch, so that one register per kind of read serves all of them (written
+// through place() the compiler keeps one address register per read, about forty of them).
+__device__ __forceinline__ uint32_t rows_base(int lane) {  // for frag_rows: row lane%32 of a 32-row block
+  const int l32 = lane & 31, hh = lane >> 5;
+  return (uint32_t)(l32 * ROWB + ((hh ^ row_key(l32)) << 4));
+}
+__device__ __forceinline__ bf16x8 frag_rows_at(const char *tile, uint32_t base, int r32, int ks) {
+  const uint32_t x = (uint32_t)(((2 * ks) ^ ((ks & 1) << 3)) << 4);  // place(2ks + hh, row) = hh ^ row_key ^ this
+  return *reinterpret_cast<const bf16x8 *>(tile + ((base ^ x) + (uint32_t)(r32 * ROWB)));
+}
+__device__ __forceinline__ uint32_t cols_base(int lane) {  // for frag_cols: the lane's column piece and row inside a group of 8
+  const int g = lane >> 4, s = lane & 15;
+  const int col = 16 * (g & 1) + 4 * (s & 3), c = col >> 3, half = (col >> 2) & 1;
+  const int r = 4 * (g >> 1) + (s >> 2);
+  const int pl = c ^ row_key(r) ^ (((c >> 1) & 1) << 3);
+  return (uint32_t)(r * ROWB + (pl << 4) + (half << 3));
+}
+__device__ __forceinline__ bf16x8 frag_cols_at(const char *tile, uint32_t base, int c32, int kk) {
+  union { s16x4 h[2]; bf16x8 v; } x;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const uint32_t xr = (uint32_t)((((c32 >> 3)) ^ (t << 3)) << 4);  // chunk index: + 4 per 32 columns, row_key bit 3 = t
+    const char *a = tile + ((base ^ xr) + (uint32_t)((16 * kk + 8 * t) * ROWB));
     x.h[t] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4 *)(a));
   }
   return x.v;
@@ -342,24 +374,27 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
 }
 
 // =================================================================================================
-// dK, dV: block = 128 key rows of one (batch entry, query head); wave = 32 key rows; loops over query
-// tiles of 64 rows from the diagonal to the end.  One query head per kv head: the block's result is the
-// gradient.  Grouped heads: it is that head's fp32 partial.
+// dK, dV: block = 128 key rows of one (batch entry, query head), eight waves: wave = 32 key rows x one 32-query
+// half of every 64-row query tile (waves w and w + 4 share a SIMD and the key rows and take the two halves);
+// loops over the query tiles from the diagonal to the end.  The two halves' sums over their queries are added
+// through LDS at the end (first half + second half: a fixed order).  One query head per kv head: the block's
+// result is the gradient.  Grouped heads: it is that head's fp32 partial.
 // =================================================================================================
-__global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p) {
-  extern __shared__ __align__(16) char smem[];  // [stage][Q, dO] tiles, then [stage][lse, D] rows of floats
+__global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams p) {
+  extern __shared__ __align__(1024) char smem[];  // [stage][Q, dO] tiles, then [stage][lse, D] rows of floats
   const int kt = blockIdx.x, g = blockIdx.y, n = blockIdx.z;
   const int group = p.nq / p.nkv, kap = g / group;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int kr = wave & 3, t = wave >> 2;  // key-row group, query half
   const int l32 = lane & 31, hh = lane >> 5;
-  const int j0w = kt * 128 + wave * 32;
+  const int j0w = kt * 128 + kr * 32;
   const int j = j0w + l32;
   const bool jvalid = j < p.seq;
   const int64_t tstride = (int64_t)p.batch * p.row;
   const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
   const int64_t cstride = (int64_t)p.batch * p.nq * D;
   const rsrc_t rq = make_rsrc(p.qkv, p.qkv_bytes), rdo = make_rsrc(p.dctx, p.ctx_bytes);
-  TileLoader lq, ldo;
+  TileLoaderN<8> lq, ldo;
   lq.init(tstride, wave, lane);
   ldo.init(cstride, wave, lane);
   auto tile = [&](int stage, int which) { return smem + (stage * 2 + which) * TILE_BYTES; };
@@ -375,13 +410,13 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p)
 #pragma unroll
     for (int v = 0; v < 16; ++v) dk[dt][v] = dv[dt][v] = 0.f;
   const float sc2 = p.scale * kLog2e;
+  const uint32_t rb = rows_base(lane), cb = cols_base(lane);
 
   const int it_begin = (kt * 128) / TILE;
   const int it_end = (p.seq + TILE - 1) / TILE;
-  const int per_head = it_end - it_begin, total = per_head;
-  // the query tiles of this head, double buffered; the row statistics of a
-  // step are fetched into registers one step ahead by the first wave and put into LDS just before
-  // the barrier that publishes the step's tiles
+  const int total = it_end - it_begin;
+  // the query tiles of this head, double buffered; the row statistics of a step are fetched into registers one
+  // step ahead by the first wave and put into LDS just before the barrier that publishes the step's tiles
   float st_lse = 0.f, st_d = 0.f;
   auto issue_step = [&](int step, int stage) {
     const int i0 = (it_begin + step) * TILE;
@@ -406,50 +441,70 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const FlashParams p)
     }
     __syncthreads();  // tiles and statistics of this step are visible; the other stage is free
     if (step + 1 < total) issue_step(step + 1, cur ^ 1);
-    if (i0 + TILE - 1 < j0w) continue;  // every query of this tile lies before every key row of the wave
+    if (i0 + t * 32 + 31 < j0w) continue;  // every query of this wave's half lies before every key row of the wave
     const char *qt = tile(cur, 0), *dot = tile(cur, 1);
     const float *lse_s = stats + cur * 2 * TILE, *dv_s = lse_s + TILE;
 
-    const bool diag = i0 < j0w + 31;  // some query index may be below some key index
-    f32x16 pr[2], ds[2];
+    const bool diag = i0 + t * 32 < j0w + 31;  // some query index may be below some key index
+    f32x16 s, dp;
 #pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      f32x16 s, dp;
+    for (int v = 0; v < 16; ++v) s[v] = dp[v] = 0.f;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[v] = dp[v] = 0.f;
+    for (int ks = 0; ks < D / 16; ++ks) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(qt, rb, t * 32, ks), kf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(dot, rb, t * 32, ks), vf[ks], dp, 0, 0, 0);
+    }
 #pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(qt, t * 32, ks, lane), kf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(dot, t * 32, ks, lane), vf[ks], dp, 0, 0, 0);
-      }
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const int ib = t * 32 + 8 * q4 + 4 * hh;  // four consecutive query rows of this lane
+      const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + ib);
+      const f32x4 d4 = *reinterpret_cast<const f32x4 *>(dv_s + ib);
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const int ib = t * 32 + 8 * q4 + 4 * hh;  // four consecutive query rows of this lane
-        const f32x4 l4 = *reinterpret_cast<const f32x4 *>(lse_s + ib);
-        const f32x4 d4 = *reinterpret_cast<const f32x4 *>(dv_s + ib);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int v = q4 * 4 + e;
-          float x = __builtin_amdgcn_exp2f(s[v] * sc2 - l4[e]);
-          if (diag && i0 + ib + e < j) x = 0.f;
-          pr[t][v] = x;
-          ds[t][v] = x * (dp[v] - d4[e]);
-        }
+      for (int e = 0; e < 4; ++e) {
+        const int v = q4 * 4 + e;
+        float x = __builtin_amdgcn_exp2f(s[v] * sc2 - l4[e]);
+        if (diag && i0 + ib + e < j) x = 0.f;
+        s[v] = x;                     // P
+        dp[v] = x * (dp[v] - d4[e]);  // dS
       }
     }
 #pragma unroll
-    for (int kk = 0; kk < TILE / 16; ++kk) {
-      const bf16x8 pf = pack8(pr[kk >> 1], 8 * (kk & 1));
-      const bf16x8 df = pack8(ds[kk >> 1], 8 * (kk & 1));
+    for (int k2 = 0; k2 < 2; ++k2) {
+      const int kk = 2 * t + k2;
+      const bf16x8 pf = pack8(s, 8 * k2);
+      const bf16x8 df = pack8(dp, 8 * k2);
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt) {
-        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(dot, dt * 32, kk, lane), pf, dv[dt], 0, 0, 0);
-        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(qt, dt * 32, kk, lane), df, dk[dt], 0, 0, 0);
+        dv[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_at(dot, cb, dt * 32, kk), pf, dv[dt], 0, 0, 0);
+        dk[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_at(qt, cb, dt * 32, kk), df, dk[dt], 0, 0, 0);
       }
     }
   }
   wait_loads();
-  if (jvalid) {
+  // the second query half hands its sums to the first through LDS (the tiles are no longer needed): dK, then dV
+  float *xch = reinterpret_cast<float *>(smem) + (size_t)kr * (D / 32) * 16 * 64;  // [kr][dt][v][lane]
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    __syncthreads();
+    if (t == 1) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xch[(dt * 16 + v) * 64 + lane] = which == 0 ? dk[dt][v] : dv[dt][v];
+    }
+    __syncthreads();
+    if (t == 0) {
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float other = xch[(dt * 16 + v) * 64 + lane];
+          if (which == 0) dk[dt][v] += other;
+          else dv[dt][v] += other;
+        }
+    }
+  }
+  if (jvalid && t == 0) {
     if (p.part) {
       float *out = p.part + (((int64_t)n * p.nq + g) * p.seq + j) * (2 * D);
       store_transposed_f32(dk, p.scale, out, hh);
@@ -545,7 +600,7 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   }
   g_last_kernel = "flash_bwd_dq_kernel+flash_bwd_dkv_kernel";
   flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
-  flash_bwd_dkv_kernel<<<gk, 256, lds, s>>>(p);
+  flash_bwd_dkv_kernel<<<gk, 512, lds, s>>>(p);
   if (p.part) {
     const int64_t total = batch * nkv * seq * (2 * D / 4);
     flash_dkv_reduce_kernel<<<(unsigned)ceil_div(total, (int64_t)256), 256, 0, s>>>(p);
