@@ -250,3 +250,61 @@ def test_gpt175b_full_depth_equals_chained_layers_and_layers_match_checker(env):
             e = rel_err(gl[off:off + k], rg[name].reshape(-1))
             assert e <= TOL_BF16, (l, name, e)
             off += k
+
+
+def test_gpt175b_benchmark_configuration_equals_the_three_calls(env):
+    """The launch configuration the benchmark times (12 layers at the 175B-shard width, measured tile
+    configurations, transient gradients, tm_stage_fwd + tm_stage_bwd_adam with every weight matrix updated in
+    the epilogue of its weight-gradient product) against the plain sequence tm_stage_fwd, tm_stage_bwd,
+    tm_adam_step on a second copy of the same state: outputs, input gradients, master weights, both moments
+    and the bf16 weights bit for bit over two iterations (the second forward pass reads updated weights and
+    the moments are no longer zero).  The plain sequence is the one the other tests hold against the checker."""
+    torch, tm = env
+    cfg = si.PRESETS["gpt175b"]
+    n = tm.tm_stage_param_count(cfg)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(si.BASE_SEED + 7)
+    master0 = torch.empty(n, dtype=torch.float32, device="cuda")
+    for lo in range(0, n, 1 << 28):
+        master0[lo:lo + (1 << 28)].normal_(0.0, 0.02, generator=gen)
+    for name, off, shape in tm.tm_stage_param_layout(cfg):
+        if name.endswith("_gain"):
+            master0[off:off + shape[0]] += 1.0
+    params0 = master0.to(torch.bfloat16)
+    master0.copy_(params0)
+    shape = (cfg.seq, cfg.micro_batch, cfg.hidden)
+    x = torch.empty(shape, device="cuda").normal_(0, 1, generator=gen).to(torch.bfloat16)
+    dy = torch.empty(shape, device="cuda").normal_(0, 1e-2, generator=gen).to(torch.bfloat16)
+    s = stream_ptr(torch)
+
+    def state():
+        st = {"params": params0.clone(), "master": master0.clone(), "grads": torch.zeros(n, device="cuda"),
+              "m": torch.zeros(n, device="cuda"), "v": torch.zeros(n, device="cuda"),
+              "ws": torch.empty(tm.tm_stage_workspace_bytes(cfg), dtype=torch.uint8, device="cuda"),
+              "y": torch.empty_like(x), "dx": torch.empty_like(x)}
+        st["h"] = tm.tm_stage_init(cfg, st["params"], st["master"], st["grads"], st["m"], st["v"], st["ws"])
+        return st
+
+    print("benchmark configuration at full size: building two states", flush=True)
+    a, b = state(), state()
+    del master0, params0
+    tm.tm_stage_grad_mode(b["h"], tm.TM_GRAD_TRANSIENT)
+    tm.tm_stage_tune(b["h"], s)
+    hp_plain = tm.make_hparams(**si.ADAM_DEFAULTS, zero_grads=1)
+    hp = tm.make_hparams(**si.ADAM_DEFAULTS)
+    for step in (1, 2):
+        print(f"  iteration {step}: three calls, then forward + backward-with-update", flush=True)
+        tm.tm_stage_fwd(a["h"], x, a["y"], s)
+        tm.tm_stage_bwd(a["h"], dy, a["dx"], s)
+        tm.tm_adam_step(a["h"], hp_plain, step, s)
+        tm.tm_stage_fwd(b["h"], x, b["y"], s)
+        tm.tm_stage_bwd_adam(b["h"], dy, b["dx"], hp, step, s)
+        torch.cuda.synchronize()
+        for name in ("y", "dx", "master", "m", "v", "params"):
+            assert torch.equal(a[name], b[name]), (step, name)
+        assert bool(torch.isfinite(a["y"].float()).all())
+    # the update moved the weights, and by no more than the step size allows (|delta| <= lr per step for Adam)
+    moved = (a["master"][:1 << 24] - a["params"][:1 << 24].float()).abs().max()
+    assert float(moved) <= 2 ** -8 * float(a["master"][:1 << 24].abs().max())   # bf16 copy = rounded master
+    tm.tm_stage_destroy(a["h"])
+    tm.tm_stage_destroy(b["h"])
