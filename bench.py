@@ -71,7 +71,7 @@ def cpu_baseline(si, cfg, budget_s: float):
         threads = max([p.get("num_threads", 1) for p in threadpool_info() if p.get("user_api") == "blas"] or [1])
     except Exception:
         threads = len(os.sched_getaffinity(0))
-    seq_s = min(cfg.seq, 256)
+    seq_s = min(cfg.seq, 512)
     sample = cfg.replace(n_layers=1, seq=seq_s)
     p = si.make_layer_params(sample, 0)
     x, dy = si.make_x(sample), si.make_dy(sample)
