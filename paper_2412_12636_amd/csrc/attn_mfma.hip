@@ -198,7 +198,7 @@ __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)"
 // forward: block = 128 query rows of one (batch entry, query head); wave = 32 query rows
 // =================================================================================================
 __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) {
-  __shared__ __align__(16) char lds[2][2][TILE_BYTES];  // [stage][K, V]
+  __shared__ __align__(1024) char lds[2][2][TILE_BYTES];  // [stage][K, V]
   const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
   const int kap = g / (p.nq / p.nkv);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -222,6 +222,7 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
     for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
   float m = -INFINITY, l = 0.f;
   const float sc2 = p.scale * kLog2e;
+  const uint32_t rb = rows_base(lane), cb = cols_base(lane);
 
   const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
   const int ntile = (kv_end + TILE - 1) / TILE;
@@ -239,6 +240,9 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
     if (j0 > q0w + 31) continue;  // every key of this tile lies after every query row of the wave
     const char *kt = lds[cur][0], *vt = lds[cur][1];
 
+    // Only the last one or two tiles of the walk can hold a key index above a query index of the wave: only those
+    // pay for the mask.  The running maximum is kept in exponent units (m = max * scale * log2 e); the accumulators
+    // and the row sum are rescaled only when some row of the wave saw its maximum rise.
     f32x16 s[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -246,42 +250,47 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
       for (int v = 0; v < 16; ++v) s[t][v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks)
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt, t * 32, ks, lane), qf[ks], s[t], 0, 0, 0);
+        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(kt, rb, t * 32, ks), qf[ks], s[t], 0, 0, 0);
     }
-    const bool diag = j0 + TILE - 1 > q0w;  // some key index may exceed some query index
-    float mx = m;
+    if (j0 + TILE - 1 > q0w) {  // wave-uniform
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (j0 + t * 32 + acc_row(v, hh) > q) s[t][v] = -INFINITY;
+    }
+    float mraw = -INFINITY;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float x = s[t][v] * sc2;
-        if (diag && j0 + t * 32 + acc_row(v, hh) > q) x = -INFINITY;
-        s[t][v] = x;
-        mx = fmaxf(mx, x);
-      }
+      for (int v = 0; v < 16; ++v) mraw = fmaxf(mraw, s[t][v]);
+    float mx = fmaxf(m, mraw * sc2);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float alpha = __builtin_amdgcn_exp2f(m - mx);
-    m = mx;
+    if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {  // wave-uniform
+      const float alpha = __builtin_amdgcn_exp2f(m - mx);
+      m = mx;
+      l *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+    }
     float ps = 0.f;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float e = __builtin_amdgcn_exp2f(s[t][v] - mx);
+        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][v], sc2, -m));
         s[t][v] = e;
         ps += e;
       }
-    l = l * alpha + ps;
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
+    l += ps;
 #pragma unroll
     for (int kk = 0; kk < TILE / 16; ++kk) {
       const bf16x8 pf = pack8(s[kk >> 1], 8 * (kk & 1));
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt)
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(vt, dt * 32, kk, lane), pf, o[dt], 0, 0, 0);
+        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_at(vt, cb, dt * 32, kk), pf, o[dt], 0, 0, 0);
     }
   }
   wait_loads();
