@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
 // dQ: same walk as the forward pass; dQ^T += K^T dS^T
 // =================================================================================================
 __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams p) {
-  __shared__ __align__(16) char lds[2][2][TILE_BYTES];  // [stage][K, V]
+  __shared__ __align__(1024) char lds[2][2][TILE_BYTES];  // [stage][K, V]
   const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
   const int kap = g / (p.nq / p.nkv);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -334,6 +334,7 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
   const float sc2 = p.scale * kLog2e;
+  const uint32_t rb = rows_base(lane), cb = cols_base(lane);
 
   const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
   const int ntile = (kv_end + TILE - 1) / TILE;
@@ -351,7 +352,6 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
     if (j0 > q0w + 31) continue;
     const char *kt = lds[cur][0], *vt = lds[cur][1];
 
-    const bool diag = j0 + TILE - 1 > q0w;
     f32x16 ds[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -360,22 +360,26 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
       for (int v = 0; v < 16; ++v) s[v] = dp[v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < D / 16; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(kt, t * 32, ks, lane), qf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows(vt, t * 32, ks, lane), dof[ks], dp, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(kt, rb, t * 32, ks), qf[ks], s, 0, 0, 0);
+        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(vt, rb, t * 32, ks), dof[ks], dp, 0, 0, 0);
       }
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float pr = __builtin_amdgcn_exp2f(s[v] * sc2 - lse2);
-        if (diag && j0 + t * 32 + acc_row(v, hh) > q) pr = 0.f;
-        ds[t][v] = pr * (dp[v] - dq_d);
-      }
+      for (int v = 0; v < 16; ++v)
+        ds[t][v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], sc2, -lse2)) * (dp[v] - dq_d);
+    }
+    if (j0 + TILE - 1 > q0w) {  // wave-uniform: only the last one or two tiles can hold a key above a query
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (j0 + t * 32 + acc_row(v, hh) > q) ds[t][v] = 0.f;
     }
 #pragma unroll
     for (int kk = 0; kk < TILE / 16; ++kk) {
       const bf16x8 df = pack8(ds[kk >> 1], 8 * (kk & 1));
 #pragma unroll
       for (int dt = 0; dt < D / 32; ++dt)
-        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols(kt, dt * 32, kk, lane), df, acc[dt], 0, 0, 0);
+        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_at(kt, cb, dt * 32, kk), df, acc[dt], 0, 0, 0);
     }
   }
   wait_loads();
@@ -409,9 +413,18 @@ __global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams
   auto tile = [&](int stage, int which) { return smem + (stage * 2 + which) * TILE_BYTES; };
   float *stats = reinterpret_cast<float *>(smem + 4 * TILE_BYTES);  // [stage][2][TILE]
 
-  bf16x8 kf[D / 16], vf[D / 16];
+  // The wave's K fragments stay in registers; its V fragments live in LDS ([key-row group][slice][lane], 16 bytes
+  // each: 32 KB a block, written once by the first query half) and are read again at every use, which keeps the
+  // kernel inside 256 registers without spills.
+  bf16x8 kf[D / 16];
   load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)j * tstride + koff, jvalid, hh, kf);
-  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)j * tstride + voff, jvalid, hh, vf);
+  char *vl = smem + 4 * TILE_BYTES + 2 * 2 * TILE * (int)sizeof(float) + (kr * (D / 16) * 64 + lane) * 16;
+  if (t == 0) {
+    bf16x8 vf[D / 16];
+    load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)j * tstride + voff, jvalid, hh, vf);
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) *reinterpret_cast<bf16x8 *>(vl + ks * 64 * 16) = vf[ks];
+  }
 
   f32x16 dk[D / 32], dv[D / 32];
 #pragma unroll
@@ -461,7 +474,7 @@ __global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
       s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(qt, rb, t * 32, ks), kf[ks], s, 0, 0, 0);
-      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(dot, rb, t * 32, ks), vf[ks], dp, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(dot, rb, t * 32, ks), *reinterpret_cast<const bf16x8 *>(vl + ks * 64 * 16), dp, 0, 0, 0);
     }
 #pragma unroll
     for (int q4 = 0; q4 < 4; ++q4) {
@@ -471,11 +484,15 @@ __global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int v = q4 * 4 + e;
-        float x = __builtin_amdgcn_exp2f(s[v] * sc2 - l4[e]);
-        if (diag && i0 + ib + e < j) x = 0.f;
+        const float x = __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], sc2, -l4[e]));
         s[v] = x;                     // P
         dp[v] = x * (dp[v] - d4[e]);  // dS
       }
+    }
+    if (diag) {  // wave-uniform: only the first tiles of the walk can hold a query below a key of the wave
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (i0 + t * 32 + acc_row(v, hh) < j) s[v] = dp[v] = 0.f;
     }
 #pragma unroll
     for (int k2 = 0; k2 < 2; ++k2) {
@@ -599,7 +616,7 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   if (nq != nkv && !part) return fail(TM_EINVAL, "flash_bwd: grouped heads need the partial buffer");
   dim3 gq((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
   dim3 gk((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
-  const int lds = 4 * TILE_BYTES + 2 * 2 * TILE * (int)sizeof(float);
+  const int lds = 4 * TILE_BYTES + 2 * 2 * TILE * (int)sizeof(float) + 128 * D * 2;  // tiles, row statistics, V fragments
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(&flash_bwd_dkv_kernel),
