@@ -26,6 +26,7 @@
 // leave a chip of 256 compute units with seq/128 * kv heads blocks: 32 for a 4096-token sequence and one
 // kv head).
 #include <math.h>
+#include <stdlib.h>
 
 #include "attn.h"
 
@@ -195,8 +196,79 @@ __device__ __forceinline__ void store_transposed_f32(const f32x16 (&acc)[D / 32]
 __device__ __forceinline__ void wait_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // =================================================================================================
-// forward: block = 128 query rows of one (batch entry, query head); wave = 32 query rows
+// forward
 // =================================================================================================
+// One wave's work on one staged K / V tile of 64 keys for its 32 query rows (lane%32 = query row): S^T = K Q^T,
+// online softmax, O^T += V^T P^T.  Only the last one or two tiles of a walk can hold a key index above a query
+// index of the wave: only those pay for the mask.  The running maximum is kept in exponent units
+// (m = max * scale * log2 e); the accumulators and the row sum are rescaled only when some row of the wave saw its
+// maximum rise (the factor is exactly 1 otherwise).
+struct FwdRow {
+  f32x16 o[D / 32];
+  float m, l;
+};
+__device__ __forceinline__ void fwd_tile(const char *kt, const char *vt, const bf16x8 (&qf)[D / 16], FwdRow &r, int j0,
+                                         int q0w, int q, int hh, float sc2, uint32_t rb, uint32_t cb) {
+  f32x16 s[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[t][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks)
+      s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(kt, rb, t * 32, ks), qf[ks], s[t], 0, 0, 0);
+  }
+  if (j0 + TILE - 1 > q0w) {  // wave-uniform
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (j0 + t * 32 + acc_row(v, hh) > q) s[t][v] = -INFINITY;
+  }
+  float mraw = -INFINITY;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) mraw = fmaxf(mraw, s[t][v]);
+  float mx = fmaxf(r.m, mraw * sc2);
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  if (__builtin_amdgcn_ballot_w64(mx > r.m) != 0) {  // wave-uniform
+    const float alpha = __builtin_amdgcn_exp2f(r.m - mx);
+    r.m = mx;
+    r.l *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) r.o[dt][v] *= alpha;
+  }
+  float ps = 0.f;
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][v], sc2, -r.m));
+      s[t][v] = e;
+      ps += e;
+    }
+  r.l += ps;
+#pragma unroll
+  for (int kk = 0; kk < TILE / 16; ++kk) {
+    const bf16x8 pf = pack8(s[kk >> 1], 8 * (kk & 1));
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+      r.o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_at(vt, cb, dt * 32, kk), pf, r.o[dt], 0, 0, 0);
+  }
+}
+__device__ __forceinline__ void fwd_finish(const FlashParams &p, FwdRow &r, int q, int n, int g, int hh) {
+  r.l += __shfl_xor(r.l, 32, 64);
+  if (q < p.seq) {
+    const int64_t trow = (int64_t)q * p.batch + n;
+    store_transposed(r.o, 1.f / r.l, p.ctx + trow * (p.nq * D) + g * D, hh);
+    if (hh == 0) p.lse[((int64_t)n * p.nq + g) * p.seq + q] = (r.m + log2f(r.l)) * 0.6931471805599453f;
+  }
+}
+
+// block = 128 query rows of one (batch entry, query head); wave = 32 query rows
 __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) {
   __shared__ __align__(1024) char lds[2][2][TILE_BYTES];  // [stage][K, V]
   const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
@@ -205,7 +277,6 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
   const int l32 = lane & 31, hh = lane >> 5;
   const int q0w = qt * 128 + wave * 32;
   const int q = q0w + l32;
-  const bool qvalid = q < p.seq;
   const int64_t tstride = (int64_t)p.batch * p.row;  // elements between consecutive positions
   const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
   const rsrc_t rs = make_rsrc(p.qkv, p.qkv_bytes);
@@ -213,14 +284,15 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
   ld.init(tstride, wave, lane);
 
   bf16x8 qf[D / 16];
-  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)q * tstride + g * D, qvalid, hh, qf);
+  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)q * tstride + g * D, q < p.seq, hh, qf);
 
-  f32x16 o[D / 32];
+  FwdRow r;
 #pragma unroll
   for (int dt = 0; dt < D / 32; ++dt)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
-  float m = -INFINITY, l = 0.f;
+    for (int v = 0; v < 16; ++v) r.o[dt][v] = 0.f;
+  r.m = -INFINITY;
+  r.l = 0.f;
   const float sc2 = p.scale * kLog2e;
   const uint32_t rb = rows_base(lane), cb = cols_base(lane);
 
@@ -238,73 +310,133 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
       ld.issue(rs, lds[cur ^ 1][1], r0, (int64_t)n * p.row + voff, wave);
     }
     if (j0 > q0w + 31) continue;  // every key of this tile lies after every query row of the wave
-    const char *kt = lds[cur][0], *vt = lds[cur][1];
-
-    // Only the last one or two tiles of the walk can hold a key index above a query index of the wave: only those
-    // pay for the mask.  The running maximum is kept in exponent units (m = max * scale * log2 e); the accumulators
-    // and the row sum are rescaled only when some row of the wave saw its maximum rise.
-    f32x16 s[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[t][v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks)
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(kt, rb, t * 32, ks), qf[ks], s[t], 0, 0, 0);
-    }
-    if (j0 + TILE - 1 > q0w) {  // wave-uniform
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (j0 + t * 32 + acc_row(v, hh) > q) s[t][v] = -INFINITY;
-    }
-    float mraw = -INFINITY;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) mraw = fmaxf(mraw, s[t][v]);
-    float mx = fmaxf(m, mraw * sc2);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    if (__builtin_amdgcn_ballot_w64(mx > m) != 0) {  // wave-uniform
-      const float alpha = __builtin_amdgcn_exp2f(m - mx);
-      m = mx;
-      l *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[dt][v] *= alpha;
-    }
-    float ps = 0.f;
-#pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(s[t][v], sc2, -m));
-        s[t][v] = e;
-        ps += e;
-      }
-    l += ps;
-#pragma unroll
-    for (int kk = 0; kk < TILE / 16; ++kk) {
-      const bf16x8 pf = pack8(s[kk >> 1], 8 * (kk & 1));
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_at(vt, cb, dt * 32, kk), pf, o[dt], 0, 0, 0);
-    }
+    fwd_tile(lds[cur][0], lds[cur][1], qf, r, j0, q0w, q, hh, sc2, rb, cb);
   }
   wait_loads();
-  l += __shfl_xor(l, 32, 64);
-  if (qvalid) {
-    const int64_t trow = (int64_t)q * p.batch + n;
-    store_transposed(o, 1.f / l, p.ctx + trow * (p.nq * D) + g * D, hh);
-    if (hh == 0) p.lse[((int64_t)n * p.nq + g) * p.seq + q] = (m + log2f(l)) * 0.6931471805599453f;
+  fwd_finish(p, r, q, n, g, hh);
+}
+
+// The same for grids of at most one block per compute unit (short sequences, few heads), where the chain of tile
+// steps of the last query rows bounds the kernel: eight waves; waves w and w + 4 share a SIMD and 32 query rows
+// and take the even and the odd key tiles, each with its own maximum, row sum and accumulators; at the end the odd
+// side's state goes through LDS and the even side merges it (o = o1 2^(m1-m) + o2 2^(m2-m), the row sum alike).
+// Half as many steps, and the two waves of a SIMD overlap each other's softmax and MFMA phases.
+__global__ __launch_bounds__(512, 1) void flash_fwd_split_kernel(const FlashParams p) {
+  extern __shared__ __align__(1024) char smem[];  // [stage][parity][K, V] tiles
+  const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
+  const int kap = g / (p.nq / p.nkv);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qg = wave & 3, par = wave >> 2;
+  const int l32 = lane & 31, hh = lane >> 5;
+  const int q0w = qt * 128 + qg * 32;
+  const int q = q0w + l32;
+  const int64_t tstride = (int64_t)p.batch * p.row;
+  const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
+  const rsrc_t rs = make_rsrc(p.qkv, p.qkv_bytes);
+  TileLoaderN<8> ld;
+  ld.init(tstride, wave, lane);
+  auto tile = [&](int stage, int parity, int which) { return smem + ((stage * 2 + parity) * 2 + which) * TILE_BYTES; };
+
+  bf16x8 qf[D / 16];
+  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)q * tstride + g * D, q < p.seq, hh, qf);
+
+  FwdRow r;
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) r.o[dt][v] = 0.f;
+  r.m = -INFINITY;
+  r.l = 0.f;
+  const float sc2 = p.scale * kLog2e;
+  const uint32_t rb = rows_base(lane), cb = cols_base(lane);
+
+  const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
+  const int ntile = (kv_end + TILE - 1) / TILE, nstep = (ntile + 1) / 2;
+  auto issue_step = [&](int step, int stage) {  // both parities' tiles; a tile past the walk's end is not fetched
+#pragma unroll
+    for (int parity = 0; parity < 2; ++parity) {
+      const int jt = 2 * step + parity;
+      if (jt < ntile) {
+        const int64_t r0 = (int64_t)jt * TILE * tstride;
+        ld.issue(rs, tile(stage, parity, 0), r0, (int64_t)n * p.row + koff, wave);
+        ld.issue(rs, tile(stage, parity, 1), r0, (int64_t)n * p.row + voff, wave);
+      }
+    }
+  };
+  issue_step(0, 0);
+  for (int step = 0; step < nstep; ++step) {
+    const int cur = step & 1;
+    wait_loads();
+    __builtin_amdgcn_s_barrier();  // this step's tiles are in LDS; everyone is done with the other stage
+    if (step + 1 < nstep) issue_step(step + 1, cur ^ 1);
+    const int jt = 2 * step + par, j0 = jt * TILE;
+    if (jt >= ntile || j0 > q0w + 31) continue;
+    fwd_tile(tile(cur, par, 0), tile(cur, par, 1), qf, r, j0, q0w, q, hh, sc2, rb, cb);
+  }
+  wait_loads();
+  __syncthreads();  // the tiles are no longer needed: the odd side's state goes where they were
+  float *xch = reinterpret_cast<float *>(smem) + (size_t)qg * ((D / 32) * 16 + 2) * 64;  // [qg][o..., m, l][lane]
+  if (par == 1) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) xch[(dt * 16 + v) * 64 + lane] = r.o[dt][v];
+    xch[(D / 32) * 16 * 64 + lane] = r.m;
+    xch[((D / 32) * 16 + 1) * 64 + lane] = r.l;
+  }
+  __syncthreads();
+  if (par == 0) {
+    const float m2 = xch[(D / 32) * 16 * 64 + lane], l2 = xch[((D / 32) * 16 + 1) * 64 + lane];
+    const float mm = fmaxf(r.m, m2);  // r.m is finite: the even side always has key tile 0
+    const float a1 = __builtin_amdgcn_exp2f(r.m - mm), a2 = __builtin_amdgcn_exp2f(m2 - mm);
+    r.m = mm;
+    r.l = r.l * a1 + l2 * a2;
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) r.o[dt][v] = r.o[dt][v] * a1 + xch[(dt * 16 + v) * 64 + lane] * a2;
+    fwd_finish(p, r, q, n, g, hh);
   }
 }
 
 // =================================================================================================
 // dQ: same walk as the forward pass; dQ^T += K^T dS^T
 // =================================================================================================
+// one wave, one staged K / V tile: probabilities from the stored log-sum-exp, dS = P (dP - D), dQ^T += K^T dS^T
+__device__ __forceinline__ void dq_tile(const char *kt, const char *vt, const bf16x8 (&qf)[D / 16],
+                                        const bf16x8 (&dof)[D / 16], f32x16 (&acc)[D / 32], float lse2, float dq_d, int j0,
+                                        int q0w, int q, int hh, float sc2, uint32_t rb, uint32_t cb) {
+  f32x16 ds[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    f32x16 s, dp;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = dp[v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < D / 16; ++ks) {
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(kt, rb, t * 32, ks), qf[ks], s, 0, 0, 0);
+      dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(vt, rb, t * 32, ks), dof[ks], dp, 0, 0, 0);
+    }
+#pragma unroll
+    for (int v = 0; v < 16; ++v)
+      ds[t][v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], sc2, -lse2)) * (dp[v] - dq_d);
+  }
+  if (j0 + TILE - 1 > q0w) {  // wave-uniform: only the last one or two tiles can hold a key above a query
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (j0 + t * 32 + acc_row(v, hh) > q) ds[t][v] = 0.f;
+  }
+#pragma unroll
+  for (int kk = 0; kk < TILE / 16; ++kk) {
+    const bf16x8 df = pack8(ds[kk >> 1], 8 * (kk & 1));
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+      acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_at(kt, cb, dt * 32, kk), df, acc[dt], 0, 0, 0);
+  }
+}
+
 __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams p) {
   __shared__ __align__(1024) char lds[2][2][TILE_BYTES];  // [stage][K, V]
   const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
@@ -350,40 +482,87 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
       ld.issue(rs, lds[cur ^ 1][1], r0, (int64_t)n * p.row + voff, wave);
     }
     if (j0 > q0w + 31) continue;
-    const char *kt = lds[cur][0], *vt = lds[cur][1];
-
-    f32x16 ds[2];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      f32x16 s, dp;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[v] = dp[v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < D / 16; ++ks) {
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(kt, rb, t * 32, ks), qf[ks], s, 0, 0, 0);
-        dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_rows_at(vt, rb, t * 32, ks), dof[ks], dp, 0, 0, 0);
-      }
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        ds[t][v] = __builtin_amdgcn_exp2f(__builtin_fmaf(s[v], sc2, -lse2)) * (dp[v] - dq_d);
-    }
-    if (j0 + TILE - 1 > q0w) {  // wave-uniform: only the last one or two tiles can hold a key above a query
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-          if (j0 + t * 32 + acc_row(v, hh) > q) ds[t][v] = 0.f;
-    }
-#pragma unroll
-    for (int kk = 0; kk < TILE / 16; ++kk) {
-      const bf16x8 df = pack8(ds[kk >> 1], 8 * (kk & 1));
-#pragma unroll
-      for (int dt = 0; dt < D / 32; ++dt)
-        acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_cols_at(kt, cb, dt * 32, kk), df, acc[dt], 0, 0, 0);
-    }
+    dq_tile(lds[cur][0], lds[cur][1], qf, dof, acc, lse2, dq_d, j0, q0w, q, hh, sc2, rb, cb);
   }
   wait_loads();
   if (qvalid) store_transposed(acc, p.scale, p.dqkv + ((int64_t)q * p.batch + n) * p.row + g * D, hh);
+}
+
+// eight waves for grids of at most one block per compute unit: waves w and w + 4 take the even and the odd key
+// tiles of the same 32 query rows; the odd side's sums are added to the even side's through LDS at the end
+__global__ __launch_bounds__(512, 1) void flash_bwd_dq_split_kernel(const FlashParams p) {
+  extern __shared__ __align__(1024) char smem[];  // [stage][parity][K, V] tiles
+  const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
+  const int kap = g / (p.nq / p.nkv);
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int qg = wave & 3, par = wave >> 2;
+  const int l32 = lane & 31, hh = lane >> 5;
+  const int q0w = qt * 128 + qg * 32;
+  const int q = q0w + l32;
+  const bool qvalid = q < p.seq;
+  const int64_t tstride = (int64_t)p.batch * p.row;
+  const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
+  const int64_t cstride = (int64_t)p.batch * p.nq * D;
+  const rsrc_t rs = make_rsrc(p.qkv, p.qkv_bytes);
+  TileLoaderN<8> ld;
+  ld.init(tstride, wave, lane);
+  auto tile = [&](int stage, int parity, int which) { return smem + ((stage * 2 + parity) * 2 + which) * TILE_BYTES; };
+
+  bf16x8 qf[D / 16], dof[D / 16];
+  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)q * tstride + g * D, qvalid, hh, qf);
+  load_row_frags(p.dctx + (int64_t)n * p.nq * D + (int64_t)q * cstride + g * D, qvalid, hh, dof);
+  const int64_t si = ((int64_t)n * p.nq + g) * p.seq + q;
+  const float lse2 = qvalid ? p.lse_in[si] * kLog2e : 0.f;
+  const float dq_d = qvalid ? p.dvec[si] : 0.f;
+
+  f32x16 acc[D / 32];
+#pragma unroll
+  for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
+  const float sc2 = p.scale * kLog2e;
+  const uint32_t rb = rows_base(lane), cb = cols_base(lane);
+
+  const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
+  const int ntile = (kv_end + TILE - 1) / TILE, nstep = (ntile + 1) / 2;
+  auto issue_step = [&](int step, int stage) {
+#pragma unroll
+    for (int parity = 0; parity < 2; ++parity) {
+      const int jt = 2 * step + parity;
+      if (jt < ntile) {
+        const int64_t r0 = (int64_t)jt * TILE * tstride;
+        ld.issue(rs, tile(stage, parity, 0), r0, (int64_t)n * p.row + koff, wave);
+        ld.issue(rs, tile(stage, parity, 1), r0, (int64_t)n * p.row + voff, wave);
+      }
+    }
+  };
+  issue_step(0, 0);
+  for (int step = 0; step < nstep; ++step) {
+    const int cur = step & 1;
+    wait_loads();
+    __builtin_amdgcn_s_barrier();
+    if (step + 1 < nstep) issue_step(step + 1, cur ^ 1);
+    const int jt = 2 * step + par, j0 = jt * TILE;
+    if (jt >= ntile || j0 > q0w + 31) continue;
+    dq_tile(tile(cur, par, 0), tile(cur, par, 1), qf, dof, acc, lse2, dq_d, j0, q0w, q, hh, sc2, rb, cb);
+  }
+  wait_loads();
+  __syncthreads();  // the tiles are no longer needed
+  float *xch = reinterpret_cast<float *>(smem) + (size_t)qg * (D / 32) * 16 * 64;  // [qg][dt][v][lane]
+  if (par == 1) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) xch[(dt * 16 + v) * 64 + lane] = acc[dt][v];
+  }
+  __syncthreads();
+  if (par == 0) {
+#pragma unroll
+    for (int dt = 0; dt < D / 32; ++dt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[dt][v] += xch[(dt * 16 + v) * 64 + lane];
+    if (qvalid) store_transposed(acc, p.scale, p.dqkv + ((int64_t)q * p.batch + n) * p.row + g * D, hh);
+  }
 }
 
 // =================================================================================================
@@ -583,6 +762,21 @@ static FlashParams make_params(int64_t seq, int64_t batch, int64_t nq, int64_t n
   return p;
 }
 
+// The eight-wave kernels that split a query block's key tiles between two waves serve grids that leave compute
+// units without a second block (at most one block per unit).  TM_ATTN_SPLIT=0 / 1 in the environment forces the
+// choice (tuning and test aid).
+static bool use_split(dim3 grid) {
+  if (const char *e = getenv("TM_ATTN_SPLIT")) return e[0] == '1';
+  static int units = 0;
+  if (!units) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        units <= 0)
+      units = 256;
+  }
+  return (int64_t)grid.x * grid.y * grid.z <= units;
+}
+
 int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, int64_t d, const void *qkv, void *ctx,
                          float *lse, hipStream_t s) {
   (void)d;
@@ -592,8 +786,21 @@ int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   p.ctx = (bf16 *)ctx;
   p.lse = lse;
   dim3 grid((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
-  g_last_kernel = "flash_fwd_kernel";
-  flash_fwd_kernel<<<grid, 256, 0, s>>>(p);
+  if (use_split(grid)) {
+    const int lds = 8 * TILE_BYTES;
+    static bool attr_set = false;
+    if (!attr_set) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void *>(&flash_fwd_split_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
+        return fail(TM_ELAUNCH, "flash_fwd: cannot reserve LDS");
+      attr_set = true;
+    }
+    g_last_kernel = "flash_fwd_split_kernel";
+    flash_fwd_split_kernel<<<grid, 512, lds, s>>>(p);
+  } else {
+    g_last_kernel = "flash_fwd_kernel";
+    flash_fwd_kernel<<<grid, 256, 0, s>>>(p);
+  }
   return check_launch("flash_fwd");
 }
 
@@ -625,7 +832,19 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
     attr_set = true;
   }
   g_last_kernel = "flash_bwd_dq_kernel+flash_bwd_dkv_kernel";
-  flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
+  if (use_split(gq)) {
+    const int lds_q = 8 * TILE_BYTES;
+    static bool attr_q = false;
+    if (!attr_q) {
+      if (hipFuncSetAttribute(reinterpret_cast<const void *>(&flash_bwd_dq_split_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_q) != hipSuccess)
+        return fail(TM_ELAUNCH, "flash_bwd: cannot reserve LDS");
+      attr_q = true;
+    }
+    flash_bwd_dq_split_kernel<<<gq, 512, lds_q, s>>>(p);
+  } else {
+    flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
+  }
   flash_bwd_dkv_kernel<<<gk, 512, lds, s>>>(p);
   if (p.part) {
     const int64_t total = batch * nkv * seq * (2 * D / 4);

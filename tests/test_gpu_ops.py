@@ -352,6 +352,47 @@ def test_attention_fwd_bwd(env, dtype, seq, batch, nq, nkv, d):
     assert rel_err(got[..., A + nkv * d:], dv.reshape(seq, batch, -1)) <= tol
 
 
+@pytest.mark.parametrize("split", ["0", "1"], ids=["four_wave_blocks", "eight_wave_split_key_tiles"])
+@pytest.mark.parametrize("seq,batch,nq,nkv", [(700, 1, 3, 3), (300, 2, 4, 2), (64, 1, 1, 1), (1, 1, 2, 1), (129, 1, 2, 2)],
+                         ids=["ragged_11_key_tiles", "grouped_heads", "one_key_tile", "one_position", "one_row_past_a_block"])
+def test_attention_block_forms(env, monkeypatch, split, seq, batch, nq, nkv):
+    """The head-size-128 kernels come in two block forms, chosen by the grid size (TM_ATTN_SPLIT forces one): four waves
+    walking all key tiles of their query rows, and eight waves where two waves share the query rows and take the even
+    and the odd key tiles (their softmax states merged at the end).  Both against the checker, forward and backward;
+    with one key tile the odd side has nothing to do and must contribute nothing."""
+    torch, tm = env
+    monkeypatch.setenv("TM_ATTN_SPLIT", split)
+    d, dtype = 128, BF16
+    print(f"attention block form split={split} seq={seq} batch={batch} nq={nq} nkv={nkv}", flush=True)
+    rng = np.random.default_rng(seq * 7 + nq)
+    A, W = nq * d, (nq + 2 * nkv) * d
+    qkv = rand(rng, (seq, batch, W), 1.0, dtype)
+    dctx = rand(rng, (seq, batch, A), 0.1, dtype)
+    s = stream_ptr(torch)
+    qd = to_dev(torch, qkv, dtype)
+    ctx = torch.empty((seq, batch, A), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((batch, nq, seq), dtype=torch.float32, device="cuda")
+    tm.tm_op_attn_fwd(dtype, seq, batch, nq, nkv, d, qd, ctx, lse, s)
+    q64 = qkv.astype(np.float64)
+    q = q64[..., :A].reshape(seq, batch, nq, d)
+    k = q64[..., A:A + nkv * d].reshape(seq, batch, nkv, d)
+    v = q64[..., A + nkv * d:].reshape(seq, batch, nkv, d)
+    tol = tol_of(dtype)
+    assert rel_err(to_host(ctx), so.attention_fwd(q, k, v).reshape(seq, batch, A)) <= tol
+    sc = q[:, 0, nq - 1] @ k[:, 0, (nq - 1) // (nq // nkv)].T / math.sqrt(d)
+    sc = np.where(np.tril(np.ones((seq, seq), bool)), sc, -np.inf)
+    mx = sc.max(axis=1)
+    assert np.abs(to_host(lse[0, nq - 1]) - (mx + np.log(np.exp(sc - mx[:, None]).sum(axis=1)))).max() <= 1e-3
+    dqkv = torch.zeros((seq, batch, W), dtype=torch.bfloat16, device="cuda")
+    scratch = torch.empty(tm.tm_op_attn_bwd_scratch_bytes(dtype, seq, batch, nq, nkv, d), dtype=torch.uint8, device="cuda")
+    tm.tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, qd, ctx, to_dev(torch, dctx, dtype), lse, scratch, dqkv, s)
+    dq, dk, dv = so.attention_bwd(dctx.astype(np.float64).reshape(seq, batch, nq, d), q, k, v)
+    got = to_host(dqkv)
+    assert rel_err(got[..., :A], dq.reshape(seq, batch, A)) <= tol
+    assert rel_err(got[..., A:A + nkv * d], dk.reshape(seq, batch, -1)) <= tol
+    assert rel_err(got[..., A + nkv * d:], dv.reshape(seq, batch, -1)) <= tol
+
+
 def test_attention_is_bit_reproducible(env):
     torch, tm = env
     rng = np.random.default_rng(8)
