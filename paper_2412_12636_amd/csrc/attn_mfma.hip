@@ -488,83 +488,6 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
   if (qvalid) store_transposed(acc, p.scale, p.dqkv + ((int64_t)q * p.batch + n) * p.row + g * D, hh);
 }
 
-// eight waves for grids of at most one block per compute unit: waves w and w + 4 take the even and the odd key
-// tiles of the same 32 query rows; the odd side's sums are added to the even side's through LDS at the end
-__global__ __launch_bounds__(512, 1) void flash_bwd_dq_split_kernel(const FlashParams p) {
-  extern __shared__ __align__(1024) char smem[];  // [stage][parity][K, V] tiles
-  const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
-  const int kap = g / (p.nq / p.nkv);
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int qg = wave & 3, par = wave >> 2;
-  const int l32 = lane & 31, hh = lane >> 5;
-  const int q0w = qt * 128 + qg * 32;
-  const int q = q0w + l32;
-  const bool qvalid = q < p.seq;
-  const int64_t tstride = (int64_t)p.batch * p.row;
-  const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
-  const int64_t cstride = (int64_t)p.batch * p.nq * D;
-  const rsrc_t rs = make_rsrc(p.qkv, p.qkv_bytes);
-  TileLoaderN<8> ld;
-  ld.init(tstride, wave, lane);
-  auto tile = [&](int stage, int parity, int which) { return smem + ((stage * 2 + parity) * 2 + which) * TILE_BYTES; };
-
-  bf16x8 qf[D / 16], dof[D / 16];
-  load_row_frags(p.qkv + (int64_t)n * p.row + (int64_t)q * tstride + g * D, qvalid, hh, qf);
-  load_row_frags(p.dctx + (int64_t)n * p.nq * D + (int64_t)q * cstride + g * D, qvalid, hh, dof);
-  const int64_t si = ((int64_t)n * p.nq + g) * p.seq + q;
-  const float lse2 = qvalid ? p.lse_in[si] * kLog2e : 0.f;
-  const float dq_d = qvalid ? p.dvec[si] : 0.f;
-
-  f32x16 acc[D / 32];
-#pragma unroll
-  for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[dt][v] = 0.f;
-  const float sc2 = p.scale * kLog2e;
-  const uint32_t rb = rows_base(lane), cb = cols_base(lane);
-
-  const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
-  const int ntile = (kv_end + TILE - 1) / TILE, nstep = (ntile + 1) / 2;
-  auto issue_step = [&](int step, int stage) {
-#pragma unroll
-    for (int parity = 0; parity < 2; ++parity) {
-      const int jt = 2 * step + parity;
-      if (jt < ntile) {
-        const int64_t r0 = (int64_t)jt * TILE * tstride;
-        ld.issue(rs, tile(stage, parity, 0), r0, (int64_t)n * p.row + koff, wave);
-        ld.issue(rs, tile(stage, parity, 1), r0, (int64_t)n * p.row + voff, wave);
-      }
-    }
-  };
-  issue_step(0, 0);
-  for (int step = 0; step < nstep; ++step) {
-    const int cur = step & 1;
-    wait_loads();
-    __builtin_amdgcn_s_barrier();
-    if (step + 1 < nstep) issue_step(step + 1, cur ^ 1);
-    const int jt = 2 * step + par, j0 = jt * TILE;
-    if (jt >= ntile || j0 > q0w + 31) continue;
-    dq_tile(tile(cur, par, 0), tile(cur, par, 1), qf, dof, acc, lse2, dq_d, j0, q0w, q, hh, sc2, rb, cb);
-  }
-  wait_loads();
-  __syncthreads();  // the tiles are no longer needed
-  float *xch = reinterpret_cast<float *>(smem) + (size_t)qg * (D / 32) * 16 * 64;  // [qg][dt][v][lane]
-  if (par == 1) {
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) xch[(dt * 16 + v) * 64 + lane] = acc[dt][v];
-  }
-  __syncthreads();
-  if (par == 0) {
-#pragma unroll
-    for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[dt][v] += xch[(dt * 16 + v) * 64 + lane];
-    if (qvalid) store_transposed(acc, p.scale, p.dqkv + ((int64_t)q * p.batch + n) * p.row + g * D, hh);
-  }
-}
-
 // =================================================================================================
 // dK, dV: block = 128 key rows of one (batch entry, query head), eight waves: wave = 32 key rows x one 32-query
 // half of every 64-row query tile (waves w and w + 4 share a SIMD and the key rows and take the two halves);
@@ -762,9 +685,10 @@ static FlashParams make_params(int64_t seq, int64_t batch, int64_t nq, int64_t n
   return p;
 }
 
-// The eight-wave kernels that split a query block's key tiles between two waves serve grids that leave compute
-// units without a second block (at most one block per unit).  TM_ATTN_SPLIT=0 / 1 in the environment forces the
-// choice (tuning and test aid).
+// The eight-wave forward kernel that splits a query block's key tiles between two waves serves grids that leave
+// compute units without a second block (at most one block per unit).  TM_ATTN_SPLIT=0 / 1 in the environment forces
+// the choice (tuning and test aid).  (The same form of the dQ kernel was faster alone and slower inside the backward
+// pass, where its 128 KB blocks wait for LDS beside the weight-gradient products of the other stream: not kept.)
 static bool use_split(dim3 grid) {
   if (const char *e = getenv("TM_ATTN_SPLIT")) return e[0] == '1';
   static int units = 0;
@@ -832,19 +756,7 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
     attr_set = true;
   }
   g_last_kernel = "flash_bwd_dq_kernel+flash_bwd_dkv_kernel";
-  if (use_split(gq)) {
-    const int lds_q = 8 * TILE_BYTES;
-    static bool attr_q = false;
-    if (!attr_q) {
-      if (hipFuncSetAttribute(reinterpret_cast<const void *>(&flash_bwd_dq_split_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, lds_q) != hipSuccess)
-        return fail(TM_ELAUNCH, "flash_bwd: cannot reserve LDS");
-      attr_q = true;
-    }
-    flash_bwd_dq_split_kernel<<<gq, 512, lds_q, s>>>(p);
-  } else {
-    flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
-  }
+  flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
   flash_bwd_dkv_kernel<<<gk, 512, lds, s>>>(p);
   if (p.part) {
     const int64_t total = batch * nkv * seq * (2 * D / 4);

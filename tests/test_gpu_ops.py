@@ -356,9 +356,10 @@ def test_attention_fwd_bwd(env, dtype, seq, batch, nq, nkv, d):
 @pytest.mark.parametrize("seq,batch,nq,nkv", [(700, 1, 3, 3), (300, 2, 4, 2), (64, 1, 1, 1), (1, 1, 2, 1), (129, 1, 2, 2)],
                          ids=["ragged_11_key_tiles", "grouped_heads", "one_key_tile", "one_position", "one_row_past_a_block"])
 def test_attention_block_forms(env, monkeypatch, split, seq, batch, nq, nkv):
-    """The head-size-128 kernels come in two block forms, chosen by the grid size (TM_ATTN_SPLIT forces one): four waves
-    walking all key tiles of their query rows, and eight waves where two waves share the query rows and take the even
-    and the odd key tiles (their softmax states merged at the end).  Both against the checker, forward and backward;
+    """The head-size-128 forward kernel comes in two block forms, chosen by the grid size (TM_ATTN_SPLIT forces one): four
+    waves walking all key tiles of their query rows, and eight waves where two waves share the query rows and take the
+    even and the odd key tiles (their softmax states merged at the end).  Both against the checker (and the backward
+    pass from each one's log-sum-exp);
     with one key tile the odd side has nothing to do and must contribute nothing."""
     torch, tm = env
     monkeypatch.setenv("TM_ATTN_SPLIT", split)
