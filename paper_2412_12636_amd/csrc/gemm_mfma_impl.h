@@ -90,9 +90,13 @@ __device__ __forceinline__ void tile_of_block(const MfmaGemmParams &p, int BM, i
   const int xcd = pid % NXCD, local = pid / NXCD;
   const int base = nblk / NXCD, rem = nblk % NXCD;
   const int lid = xcd * base + (xcd < rem ? xcd : rem) + local;
-  const int per_group = GROUP_M * p.tiles_n;
-  const int group = lid / per_group, first_m = group * GROUP_M;
-  const int gsz = p.tiles_m - first_m < GROUP_M ? p.tiles_m - first_m : GROUP_M;
+  // 32 compute units of an XCD run a patch of gm x (tiles / gm) tiles at a time and fetch gm*BM + (tiles/gm)*BN operand
+  // rows a step from memory (first touches in that XCD's L2; 20 % of the requests with 8 x 4 tiles of 256x192, 18 % with
+  // 4 x 8): 8 row-tiles for the 128- and 192-row tiles (two blocks a unit), 4 for the 256-row tiles
+  const int gm = BM >= 256 ? GROUP_M / 2 : GROUP_M;
+  const int per_group = gm * p.tiles_n;
+  const int group = lid / per_group, first_m = group * gm;
+  const int gsz = p.tiles_m - first_m < gm ? p.tiles_m - first_m : gm;
   const int in_group = lid - group * per_group;
   m0 = (first_m + in_group % gsz) * BM;
   n0 = (in_group / gsz) * BN;
