@@ -36,35 +36,43 @@ __global__ __launch_bounds__(kRoleThreads) void embed_fwd_kernel(const int32_t *
   }
 }
 
-// ---- embedding backward: one block per vocabulary row, tokens scanned in order (reproducible) -----
+// ---- embedding backward: one block per vocabulary row, its tokens' rows added in token order (reproducible) -----
 template <typename T>
 __global__ __launch_bounds__(kRoleThreads) void embed_bwd_kernel(const int32_t *__restrict__ tokens, const T *__restrict__ dx0,
                                                                 float *__restrict__ dw, int64_t n_tokens, int h, int v0,
                                                                 int accumulate) {
   constexpr int VN = Vec<T>::N;
   constexpr int MAXCH = 8;  // h <= 256 * 8 * VN
-  __shared__ int32_t tok[1024];
+  // 256 tokens are compared at once (one per thread); the waves' ballots go to LDS and every thread then walks the set
+  // bits in ascending token order, so the sum is taken in the same order as a serial scan
+  __shared__ unsigned long long hits[kRoleThreads / 64];
   const int want = (int)blockIdx.x + v0;
   float acc[MAXCH][VN];
 #pragma unroll
   for (int k = 0; k < MAXCH; ++k)
 #pragma unroll
     for (int i = 0; i < VN; ++i) acc[k][i] = 0.f;
-  for (int64_t t0 = 0; t0 < n_tokens; t0 += 1024) {
-    const int m = (int)(n_tokens - t0 < 1024 ? n_tokens - t0 : 1024);
+  for (int64_t t0 = 0; t0 < n_tokens; t0 += kRoleThreads) {
+    const int64_t t = t0 + threadIdx.x;
+    const unsigned long long b = __builtin_amdgcn_ballot_w64(t < n_tokens && tokens[t] == want);
+    __syncthreads();  // the previous chunk's masks have been read by everyone
+    if ((threadIdx.x & 63) == 0) hits[threadIdx.x >> 6] = b;
     __syncthreads();
-    for (int i = threadIdx.x; i < m; i += kRoleThreads) tok[i] = tokens[t0 + i];
-    __syncthreads();
-    for (int i = 0; i < m; ++i) {
-      if (tok[i] != want) continue;  // uniform over the block
 #pragma unroll
-      for (int k = 0; k < MAXCH; ++k) {
-        const int c = (k * kRoleThreads + threadIdx.x) * VN;
-        if (c < h) {
-          float a[VN];
-          load_vec<T>(dx0 + (t0 + i) * h + c, a);
+    for (int w = 0; w < kRoleThreads / 64; ++w) {
+      unsigned long long m = hits[w];  // uniform over the block
+      while (m) {
+        const int i = w * 64 + __builtin_ctzll(m);
+        m &= m - 1;
 #pragma unroll
-          for (int e = 0; e < VN; ++e) acc[k][e] += a[e];
+        for (int k = 0; k < MAXCH; ++k) {
+          const int c = (k * kRoleThreads + threadIdx.x) * VN;
+          if (c < h) {
+            float a[VN];
+            load_vec<T>(dx0 + (t0 + i) * h + c, a);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) acc[k][e] += a[e];
+          }
         }
       }
     }
