@@ -109,47 +109,97 @@ static MoePlan moe_plan(const tm_moe_config_t *c) {
   return p;
 }
 
-// ---- router: one block per token; the token's row sits in LDS, a wave forms one logit at a time -----
+// ---- router: one block per 8 tokens; a thread keeps 8 x 16 partial logits over its share of the hidden axis, so a
+// chunk of a router row is fetched once for 8 tokens (one block per token fetched the whole router matrix per token:
+// 1.3 GB through L2 at 2048 tokens and 16 experts).  More than 16 experts: in groups of 16.
+constexpr int kRouterTokens = 8, kRouterGroup = 16;
 template <typename T>
 __global__ __launch_bounds__(kMoeThreads) void moe_router_kernel(const T *__restrict__ c, const T *__restrict__ wr,
                                                                  float *__restrict__ logits, int *__restrict__ top_idx,
-                                                                 float *__restrict__ gates, int h, int E, int k) {
-  extern __shared__ __align__(16) char smem[];
+                                                                 float *__restrict__ gates, int n_tokens, int h, int E, int k) {
   constexpr int VN = Vec<T>::N;
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-  T *crow = reinterpret_cast<T *>(smem);
-  float *lg = reinterpret_cast<float *>(smem + (size_t)h * sizeof(T));
-  const int t = blockIdx.x, tid = threadIdx.x, nch = h / VN;
-  for (int ch = tid; ch < nch; ch += kMoeThreads)
-    reinterpret_cast<u32x4 *>(crow)[ch] = reinterpret_cast<const u32x4 *>(c + (int64_t)t * h)[ch];
-  __syncthreads();
+  constexpr int NWAVE = kMoeThreads / kWave;
+  __shared__ float part[NWAVE][kRouterTokens][kRouterGroup];
+  __shared__ float lg[kRouterTokens][kMoeMaxExperts];
+  const int t0 = blockIdx.x * kRouterTokens, tid = threadIdx.x, nch = h / VN;
   const int wave = tid / kWave, lane = tid % kWave;
-  for (int e = wave; e < E; e += kMoeThreads / kWave) {
-    float acc = 0.f;
-    for (int ch = lane; ch < nch; ch += kWave) {
-      float a[VN], w[VN];
-      load_vec<T>(crow + ch * VN, a);
-      load_vec<T>(wr + (int64_t)e * h + ch * VN, w);
+  for (int e0 = 0; e0 < E; e0 += kRouterGroup) {
+    float acc[kRouterTokens][kRouterGroup];
 #pragma unroll
-      for (int i = 0; i < VN; ++i) acc = fmaf(a[i], w[i], acc);
+    for (int j = 0; j < kRouterTokens; ++j)
+#pragma unroll
+      for (int e = 0; e < kRouterGroup; ++e) acc[j][e] = 0.f;
+    for (int ch = tid; ch < nch; ch += kMoeThreads) {
+      // All 24 loads of a chunk are issued before the first use, raw, with no branches around them (tokens past the
+      // end repeat the last token, experts past the end the last expert; those results are never stored).
+      typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+      u32x4 ra[kRouterTokens], rw[kRouterGroup];
+#pragma unroll
+      for (int j = 0; j < kRouterTokens; ++j) {
+        const int tj = t0 + j < n_tokens ? t0 + j : n_tokens - 1;
+        ra[j] = *reinterpret_cast<const u32x4 *>(c + (int64_t)tj * h + ch * VN);
+      }
+#pragma unroll
+      for (int e = 0; e < kRouterGroup; ++e) {
+        const int ee = e0 + e < E ? e0 + e : E - 1;
+        rw[e] = *reinterpret_cast<const u32x4 *>(wr + (int64_t)ee * h + ch * VN);
+      }
+      float a[kRouterTokens][VN];
+#pragma unroll
+      for (int j = 0; j < kRouterTokens; ++j) {
+        union { u32x4 raw; Vec<T> v; } u;
+        u.raw = ra[j];
+#pragma unroll
+        for (int i = 0; i < VN; ++i) a[j][i] = to_f32(u.v.v[i]);
+      }
+#pragma unroll
+      for (int e = 0; e < kRouterGroup; ++e) {
+        union { u32x4 raw; Vec<T> v; } u;
+        u.raw = rw[e];
+#pragma unroll
+        for (int i = 0; i < VN; ++i) {
+          const float w = to_f32(u.v.v[i]);
+#pragma unroll
+          for (int j = 0; j < kRouterTokens; ++j) acc[j][e] = fmaf(a[j][i], w, acc[j][e]);
+        }
+      }
     }
-    acc = wave_sum(acc);
-    if (lane == 0) lg[e] = acc;
+    // lanes, then waves in wave order
+#pragma unroll
+    for (int j = 0; j < kRouterTokens; ++j)
+#pragma unroll
+      for (int e = 0; e < kRouterGroup; ++e) {
+        const float v = wave_sum(acc[j][e]);
+        if (lane == 0) part[wave][j][e] = v;
+      }
+    __syncthreads();
+    if (tid < kRouterTokens * kRouterGroup) {
+      const int j = tid / kRouterGroup, e = tid % kRouterGroup;
+      float v = part[0][j][e];
+#pragma unroll
+      for (int w = 1; w < NWAVE; ++w) v += part[w][j][e];
+      if (e0 + e < E) lg[j][e0 + e] = v;
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  for (int e = tid; e < E; e += kMoeThreads) logits[(int64_t)t * E + e] = lg[e];
-  if (tid == 0) {
+  for (int i = tid; i < kRouterTokens * E; i += kMoeThreads) {
+    const int j = i / E, e = i % E;
+    if (t0 + j < n_tokens) logits[(int64_t)(t0 + j) * E + e] = lg[j][e];
+  }
+  if (tid < kRouterTokens && t0 + tid < n_tokens) {
     // the k largest, ties to the lower index; gates = softmax over the chosen logits
+    const int t = t0 + tid;
+    const float *row = lg[tid];
     uint64_t used = 0;
     float val[kMoeMaxTopK];
     int idx[kMoeMaxTopK];
     for (int i = 0; i < k; ++i) {
       int best = -1;
       for (int e = 0; e < E; ++e)
-        if (!((used >> e) & 1) && (best < 0 || lg[e] > lg[best])) best = e;
+        if (!((used >> e) & 1) && (best < 0 || row[e] > row[best])) best = e;
       used |= 1ull << best;
       idx[i] = best;
-      val[i] = lg[best];
+      val[i] = row[best];
     }
     const float top = val[0];  // the maximum
     float sum = 0.f;
@@ -486,17 +536,14 @@ extern "C" int tm_moe_fwd(const tm_moe_config_t *cfg, const void *params, const 
   const int dt = cfg->dtype;
   float *logits = (float *)(ws + p.logits), *gates = (float *)(ws + p.gates);
   int *top_idx = (int *)(ws + p.top_idx), *slot_row = (int *)(ws + p.slot_row), *row_src = (int *)(ws + p.row_src);
-  const int router_lds = (int)(d.h * d.es) + kMoeMaxExperts * 4;
   g_last_kernel = "moe_router_kernel";
-  if (dt == TM_DTYPE_BF16) {
-    TM_TRY(set_lds(moe_router_kernel<bf16>, router_lds, "moe_fwd"));
-    moe_router_kernel<bf16><<<(unsigned)d.T, kMoeThreads, router_lds, s>>>((const bf16 *)c, (const bf16 *)par, logits, top_idx, gates,
-                                                                           (int)d.h, (int)d.E, (int)d.k);
-  } else {
-    TM_TRY(set_lds(moe_router_kernel<float>, router_lds, "moe_fwd"));
-    moe_router_kernel<float><<<(unsigned)d.T, kMoeThreads, router_lds, s>>>((const float *)c, (const float *)par, logits, top_idx,
-                                                                            gates, (int)d.h, (int)d.E, (int)d.k);
-  }
+  const unsigned router_blocks = (unsigned)ceil_div(d.T, (int64_t)kRouterTokens);
+  if (dt == TM_DTYPE_BF16)
+    moe_router_kernel<bf16><<<router_blocks, kMoeThreads, 0, s>>>((const bf16 *)c, (const bf16 *)par, logits, top_idx, gates, (int)d.T,
+                                                                  (int)d.h, (int)d.E, (int)d.k);
+  else
+    moe_router_kernel<float><<<router_blocks, kMoeThreads, 0, s>>>((const float *)c, (const float *)par, logits, top_idx, gates,
+                                                                   (int)d.T, (int)d.h, (int)d.E, (int)d.k);
   moe_plan_kernel<<<1, kPlanWaves * kWave, 0, s>>>(top_idx, slot_row, row_src, (int)(d.T * d.k), (int)d.E, (int)d.El, (int)d.ep, (int)d.C);
   if (dt == TM_DTYPE_BF16)
     moe_gather_kernel<bf16><<<(unsigned)d.rows, kMoeThreads, 0, s>>>((const bf16 *)c, row_src, (bf16 *)(ws + p.buf), (int)d.h, (int)d.k);
