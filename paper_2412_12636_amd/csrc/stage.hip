@@ -9,6 +9,7 @@
 #include <string>
 #include <vector>
 
+#include "attn.h"
 #include "common.h"
 #include "gemm.h"
 #include "sandbox.h"
@@ -67,8 +68,10 @@ static int validate(const tm_stage_config_t *c) {
                                            (int64_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim);
   if (T * widest >= (1LL << 31) * 8) return fail(TM_ESIZE, "config: seq * micro_batch * width too large");
   if (T > 0x7fffffffLL / 8) return fail(TM_ESIZE, "config: too many tokens");
-  const bool flash = c->dtype == TM_DTYPE_BF16 && (c->head_dim == 64 || c->head_dim == 128);
-  if (!flash && c->seq > 8192) return fail(TM_ESIZE, "config: seq above 8192 needs bf16 with head_dim 64 or 128");
+  // the same condition as the attention entry points: what the matrix-core kernels do not take goes to the
+  // plain-ALU kernels, which hold a row of scores in LDS
+  if (!attn_mfma_supported(c->dtype, c->head_dim) && c->seq > attn_generic_max_seq())
+    return fail(TM_ESIZE, "config: seq above %d needs bf16 with head_dim 128", attn_generic_max_seq());
   return TM_OK;
 }
 
@@ -565,6 +568,13 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
   if (!st || !dy_in || !dx_out) return fail(TM_EINVAL, "stage_bwd: NULL argument");
   if ((((uintptr_t)dy_in) | ((uintptr_t)dx_out)) & 255) return fail(TM_EALIGN, "stage_bwd: tensors must be 256-byte aligned");
   if (!st->have_fwd) return fail(TM_ESTATE, "stage_bwd: no forward pass to differentiate");
+  if (hp) {  // before the first launch: a product's fused update would already have written with bad scalars
+    if (step < 1) return fail(TM_EINVAL, "stage_bwd_adam: step must be >= 1 (got %lld)", (long long)step);
+    if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0))
+      return fail(TM_EINVAL, "stage_bwd_adam: betas must lie in [0, 1)");
+  }
+  if (hp && comm_intercepts(st->comm, TM_SCOPE_DP))
+    return fail(TM_ESTATE, "stage_bwd_adam: the attached hook intercepts the data-parallel scope; the update must follow tm_stage_grad_sync");
   const tm_stage_config_t &c = st->cfg;
   const Dims d = dims_of(c);
   const int dt = c.dtype;
@@ -613,8 +623,6 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
   };
 
   tm_comm_t *cm = st->comm;
-  if (hp && comm_intercepts(cm, TM_SCOPE_DP))
-    return fail(TM_ESTATE, "stage_bwd_adam: the attached hook intercepts the data-parallel scope; the update must follow tm_stage_grad_sync");
   const int64_t act_bytes = d.T * d.h * d.es;
   // tm_stage_bwd_adam with the gradients in overwrite mode: the update of a weight matrix rides in the epilogue of
   // its weight-gradient product (the gradient is still stored, but never read back, and the state streams while
@@ -639,6 +647,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     }
     return tm_op_linear_wgrad(dt, d.T, N, K, dyp, xp, dw, acc, sw);
   };
+  auto run = [&]() -> int {
   const void *dy = dy_in;
   if (cm) {
     void *at = const_cast<void *>(dy_in);
@@ -754,6 +763,17 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
   TM_TRY(join());
   if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_SEND, TM_SCOPE_PP, TM_SITE_DX, dt, dx_out, act_bytes, s));
   return TM_OK;
+  };
+  const int rc = run();
+  if (rc != TM_OK && two) {
+    // a step failed after work was forked: whatever the internal streams still hold must precede later work on the
+    // caller's stream (the message of the failure is kept)
+    hipStream_t main_stream = (hipStream_t)stream;
+    if (hipEventRecord(st->ev_join, st->side) == hipSuccess) (void)hipStreamWaitEvent(main_stream, st->ev_join, 0);
+    if (st->opt && hipEventRecord(st->ev_opt[2], st->opt) == hipSuccess) (void)hipStreamWaitEvent(main_stream, st->ev_opt[2], 0);
+    (void)hipGetLastError();
+  }
+  return rc;
 }
 
 extern "C" int tm_stage_attach_comm(tm_stage_t *st, tm_comm_t *c) {

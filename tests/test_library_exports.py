@@ -74,6 +74,22 @@ def test_config_errors(tm):
         assert tm.tm_last_error()
 
 
+def test_long_sequences_need_the_matrix_core_attention(tm):
+    """Sequences above the plain-ALU attention's limit are accepted only where the flash kernels run (bf16, head size
+    128): tm_stage_init must refuse the others itself, before anything is enqueued, with the dispatch's own condition."""
+    long_cfg = si.PRESETS["longctx"].replace(n_layers=1)
+    assert tm.tm_stage_param_count(long_cfg) > 0
+    for bad in (long_cfg.replace(head_dim=64, n_q_heads=16, n_kv_heads=2), long_cfg.replace(dtype=si.DTYPE_FP32),
+                long_cfg.replace(head_dim=256, n_q_heads=4)):
+        for call in (lambda: tm.tm_stage_param_count(bad), lambda: tm.tm_stage_workspace_bytes(bad),
+                     lambda: tm.tm_stage_init(bad, 256, 256, 256, 256, 256, 256, 1 << 40)):
+            with pytest.raises(tm.TmError) as e:
+                call()
+            assert e.value.code == tm.TM_ESIZE
+    # at the limit itself every head size is fine
+    assert tm.tm_stage_param_count(long_cfg.replace(head_dim=64, n_q_heads=16, n_kv_heads=2, seq=8192)) > 0
+
+
 def test_reduce_scratch_query(tm):
     assert tm.tm_op_reduce_scratch_bytes(2048, 12288) == 256 * 12288 * 4
     assert tm.tm_op_reduce_scratch_bytes(5, 8) == 5 * 8 * 4
