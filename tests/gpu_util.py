@@ -4,6 +4,7 @@ conversion, and the error metric.
 Error metric: for a tensor with reference values b and computed values a,
     err = max_i |a_i - b_i| / max_i |b_i|
 (an elementwise relative error does not exist for N(0, sigma) data with entries near zero).
+Beside it the tests report pass_rate(): the share of elements within rtol*|b| + rtol*rms(b).
 Tolerances: bf16 activations and gradients 2e-2; fp32 stages 1e-4 (fp32 accumulation over at
 most a few thousand terms: ~1e-6 per operation, chained through two layers); fp32 master weights
 after Adam 1e-5.
@@ -58,6 +59,16 @@ def rel_err(a: np.ndarray, b: np.ndarray) -> float:
     assert np.isfinite(a).all(), "non-finite values in the GPU result"
     den = np.abs(b).max()
     return float(np.abs(a - b).max() / (den if den > 0 else 1.0))
+
+
+def pass_rate(a: np.ndarray, b: np.ndarray, rtol: float) -> float:
+    """Share of the elements with |a - b| <= rtol * |b| + rtol * rms(b): the elementwise companion of rel_err (an
+    element near zero is held to rtol of the tensor's typical size, a large one to rtol of itself)."""
+    a = np.asarray(a, np.float64).reshape(-1)
+    b = np.asarray(b, np.float64).reshape(-1)
+    assert a.shape == b.shape, (a.shape, b.shape)
+    rms = float(np.sqrt(np.mean(b * b)))
+    return float(np.mean(np.abs(a - b) <= rtol * np.abs(b) + rtol * rms))
 
 
 def snap(a: np.ndarray, dtype: int) -> np.ndarray:

@@ -53,23 +53,23 @@ class GpuStage:
 
 
 def oracle_iteration(cfg: si.StageConfig, layers: List[Dict[str, np.ndarray]], x: np.ndarray, dy: np.ndarray,
-                     progress: bool = False):
-    """fp64 forward and backward through all layers.  Returns y, dx, list of gradient dicts."""
+                     progress=False):
+    """fp64 forward and backward through all layers.  Returns y, dx, list of gradient dicts.  progress: True prints
+    each completed layer; a callable receives the line instead (the conftest fixture that bypasses capture)."""
+    say = progress if callable(progress) else ((lambda m: print(m, flush=True)) if progress else (lambda m: None))
     t0 = time.time()
     stashes = []
     y = x
     for i, p in enumerate(layers):
         y, st = so.layer_fwd(cfg, p, y)
         stashes.append(st)
-        if progress:
-            print(f"  checker forward layer {i} done at {time.time() - t0:.1f} s", flush=True)
+        say(f"  checker forward layer {i} done at {time.time() - t0:.1f} s")
     grads = [None] * len(layers)
     dx = dy
     for i in reversed(range(len(layers))):
         dx, grads[i] = so.layer_bwd(cfg, layers[i], stashes[i], dx)
         stashes[i] = None
-        if progress:
-            print(f"  checker backward layer {i} done at {time.time() - t0:.1f} s", flush=True)
+        say(f"  checker backward layer {i} done at {time.time() - t0:.1f} s")
     return y, dx, grads
 
 
