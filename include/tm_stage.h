@@ -236,6 +236,19 @@ int64_t tm_sq_sum_scratch_bytes(int64_t n);
 int tm_sq_sum(int64_t n, const float *g, void *scratch, double *out, void *stream);
 
 /*
+ * tm_sq_sum for callers that cannot allocate device memory or hand over scratch (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same two kernels, same order, same
+ * bits, with the block partials in a buffer built into the library (8 MiB per GPU, held by every GPU the
+ * library runs on until the process ends).  n is at most tm_sq_sum_static_max_elems() = 2^32 elements
+ * (TM_ESIZE beyond).  g and out are device pointers as in tm_sq_sum.  Allocates nothing, never
+ * synchronises.  All calls on one GPU share that GPU's buffer: calls that overlap on one GPU (two streams,
+ * two threads) race; calls ordered on one stream do not.  Nothing in the buffer has to survive or to be
+ * cleared between calls.
+ */
+int64_t tm_sq_sum_static_max_elems(void);
+int tm_sq_sum_static(int64_t n, const float *g, double *out, void *stream);
+
+/*
  * The same update on bare flat device arrays of n elements (p, m, v updated in
  * place; g read, and cleared if hp->zero_grads; p_bf16 may be NULL).  This is
  * what a distributed-optimizer rank would call on its slice.  Pointers must be

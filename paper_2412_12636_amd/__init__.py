@@ -83,6 +83,8 @@ EXPORTS = {
     "tm_adam_step_range": (C.c_int, [C.c_void_p, C.c_int64, C.c_int64, C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
     "tm_sq_sum_scratch_bytes": (C.c_int64, [C.c_int64]),
     "tm_sq_sum": (C.c_int, [C.c_int64] + [C.c_void_p] * 4),
+    "tm_sq_sum_static_max_elems": (C.c_int64, []),
+    "tm_sq_sum_static": (C.c_int, [C.c_int64] + [C.c_void_p] * 3),
     "tm_stage_bwd_adam": (C.c_int, [C.c_void_p] * 3 + [C.POINTER(tm_adam_hparams_t), C.c_int64, C.c_void_p]),
     "tm_adam_step_flat": (C.c_int, [C.c_int64] + [C.c_void_p] * 5 + [C.POINTER(tm_adam_hparams_t), C.c_int64,
                                                                        C.c_void_p]),
@@ -244,6 +246,14 @@ def tm_sq_sum_scratch_bytes(n: int) -> int:
 
 def tm_sq_sum(n: int, g, scratch, out, stream: int = 0) -> None:
     _check(lib().tm_sq_sum(n, _ptr(g), _ptr(scratch), _ptr(out), stream))
+
+
+def tm_sq_sum_static_max_elems() -> int:
+    return int(lib().tm_sq_sum_static_max_elems())
+
+
+def tm_sq_sum_static(n: int, g, out, stream: int = 0) -> None:
+    _check(lib().tm_sq_sum_static(n, _ptr(g), _ptr(out), stream))
 
 
 def tm_adam_step(handle: int, hp: tm_adam_hparams_t, step: int, stream: int = 0) -> None:

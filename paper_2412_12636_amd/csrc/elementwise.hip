@@ -2,6 +2,8 @@
 // All HBM-bound: 16-byte accesses, fp32 arithmetic.
 #include <math.h>
 
+#include <mutex>
+
 #include "adam.h"
 #include "common.h"
 #include "../../include/tm_ops.h"
@@ -333,6 +335,55 @@ extern "C" int tm_sq_sum(int64_t n, const float *g, void *scratch, double *out, 
   sq_sum_partial_kernel<<<(unsigned)blocks, 256, 0, s>>>(g, n, (double *)scratch);
   sq_sum_final_kernel<<<1, 1024, 0, s>>>((const double *)scratch, blocks, out);
   return check_launch("sq_sum");
+}
+
+// ---- the same reduction for callers that cannot allocate ----------------------------------------------
+// The block partials live in a file-scope device array instead of caller memory.  Each GPU holds its own copy of the
+// array at its own address; the address is asked for once per device, with that device current, and host code
+// uses that pointer, never the array's name (which on the host is only a stand-in for the symbol).
+namespace tmk {
+constexpr int64_t kSqStaticParts = 1 << 20;  // 8 MiB of partials: 2^20 blocks of 4096 elements
+constexpr int kSqMaxDevices = 64;
+}  // namespace tmk
+static __device__ __align__(256) double scratch[tmk::kSqStaticParts];
+static double *g_sq_scratch_ptr[tmk::kSqMaxDevices];  // per device, filled on first use
+static std::mutex g_sq_scratch_mutex;
+
+extern "C" int64_t tm_sq_sum_static_max_elems(void) { return kSqStaticParts * (int64_t)kSqBlockElems; }
+
+extern "C" int tm_sq_sum_static(int64_t n, const float *g, double *out, void *stream) {
+  if (n < 0) return fail(TM_EINVAL, "sq_sum_static: negative length");
+  if (!g || !out) return fail(TM_EINVAL, "sq_sum_static: NULL pointer");
+  if ((((uintptr_t)g) & 15) || (((uintptr_t)out) & 7)) return fail(TM_EALIGN, "sq_sum_static: g must be 16-byte, out 8-byte aligned");
+  const int64_t blocks = ceil_div(n > 0 ? n : 1, (int64_t)kSqBlockElems);
+  if (blocks > kSqStaticParts)
+    return fail(TM_ESIZE, "sq_sum_static: %lld elements, the built-in scratch holds the partials of at most %lld",
+                (long long)n, (long long)(kSqStaticParts * (int64_t)kSqBlockElems));
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kSqMaxDevices) {
+    (void)hipGetLastError();
+    return fail(TM_EARCH, "sq_sum_static: no current device below %d", kSqMaxDevices);
+  }
+  double *part = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_sq_scratch_mutex);
+    if (!g_sq_scratch_ptr[dev]) {
+      void *sym = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !sym) {
+        (void)hipGetLastError();
+        return fail(TM_ELAUNCH, "sq_sum_static: address of the built-in scratch on device %d: %s", dev, hipGetErrorString(e));
+      }
+      g_sq_scratch_ptr[dev] = (double *)sym;
+    }
+    part = g_sq_scratch_ptr[dev];
+  }
+  // nothing has to start at zero: the first kernel writes partials [0, blocks) and the second reads exactly those
+  hipStream_t s = (hipStream_t)stream;
+  g_last_kernel = "sq_sum_partial_kernel";
+  sq_sum_partial_kernel<<<(unsigned)blocks, 256, 0, s>>>(g, n, part);
+  sq_sum_final_kernel<<<1, 1024, 0, s>>>(part, blocks, out);
+  return check_launch("sq_sum_static");
 }
 
 namespace tmk {
