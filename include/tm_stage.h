@@ -191,17 +191,16 @@ int tm_adam_step(tm_stage_t *st, const tm_adam_hparams_t *hp, int64_t step, void
  * Backward pass plus optimizer step in one call, for the LAST micro-batch of an
  * iteration: the same results, bit for bit, as tm_stage_bwd followed by
  * tm_adam_step, but every layer's update is enqueued as soon as that layer's
- * gradients are complete and runs beside the backward pass of the layers below
- * it (the update is bound by HBM bandwidth, the backward pass by the matrix
- * cores, so the two share the chip well).  Valid only when nothing global is
+ * gradients are complete.  Valid only when nothing global is
  * derived from this pass's gradients before the update: hp->grad_scale must
  * not depend on them (no norm-based clipping).  For bf16 stages in TM_GRAD_STORE
  * or TM_GRAD_TRANSIENT mode with hp->zero_grads == 0 and a token count that is a
  * multiple of 64, the update of each weight matrix is applied in the epilogue of
  * its weight-gradient product, from the accumulators (the gradient is not read
  * back; in TM_GRAD_TRANSIENT mode it is not stored either), and the flat sweep
- * covers the vectors between the matrices; the results are the same bits.  Uses internal streams that are
- * ordered after everything enqueued on `stream` so far, and `stream` waits for
+ * covers the vectors between the matrices; the results are the same bits.  Everything is enqueued on
+ * `stream`; with TM_BWD_STREAMS=2 in the environment the weight-gradient products and the updates go to
+ * internal streams that are ordered after everything enqueued on `stream` so far, and `stream` waits for
  * them before the call's work counts as done.  (Shadow iteration, section 4.2:
  * the last steps of the iteration the sandbox replays.)
  */

@@ -590,11 +590,13 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
   const double attn_flops = 2.0 * c.micro_batch * c.n_q_heads * (double)c.seq * c.seq * c.head_dim;
   auto mm = [&](int64_t n, int64_t kk) { return 2.0 * d.T * n * kk; };
 
-  // Two streams (not while profiling, which times the steps one by one): a weight gradient depends only
-  // on tensors the main chain has already produced, so it is forked onto the side stream, and the main
-  // stream waits for the side stream before it reuses the scratch buffers (start of the next layer) and
-  // before the call returns in stream order.
-  bool two = !st->prof.on && getenv("TM_BWD_ONE_STREAM") == nullptr;
+  // One stream by default: every product fills the chip, and measured on the 175B shard the forked form below is
+  // no faster (the overlapped products contend for the same operand path).  TM_BWD_STREAMS=2 (not while profiling,
+  // which times the steps one by one) forks each weight-gradient product, which depends only on tensors the main
+  // chain has already produced, onto a side stream; the main stream waits for the side stream before it reuses
+  // the scratch buffers (start of the next layer) and before the call returns in stream order.
+  const char *streams_env = getenv("TM_BWD_STREAMS");
+  bool two = !st->prof.on && streams_env && atoi(streams_env) >= 2;
   if (two && !st->side) {
     bool ok = hipStreamCreateWithFlags(&st->side, hipStreamNonBlocking) == hipSuccess;
     for (hipEvent_t &e : st->ev_fork) ok = ok && hipEventCreateWithFlags(&e, hipEventDisableTiming) == hipSuccess;
@@ -632,6 +634,12 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
   const AdamScalars ascal = hp ? make_adam_scalars(hp, step) : AdamScalars{};
   struct Range { int64_t first, count; };
   std::vector<Range> fused;  // this layer's matrices already updated, element ranges relative to the layer's block
+  // bytes per parameter a weight-gradient product moves besides its operands when the update rides in its epilogue:
+  // three fp32 states read and written, the bf16 copy, and the gradient where it is stored
+  const double fused_bytes_per_param = fuse ? 26.0 + (st->grad_mode != TM_GRAD_TRANSIENT ? 4.0 : 0.0) : 0.0;
+  auto wgrad_bytes = [&](int64_t N, int64_t K, const void *dyp, const void *xp, int64_t pb, int64_t w_off) -> double {
+    return fuse && linear_wgrad_adam_supported(d.T, N, K, dyp, xp, grads + pb + w_off) ? fused_bytes_per_param * (double)N * (double)K : 0.0;
+  };
   auto wgrad = [&](int64_t pb, int64_t w_off, int64_t N, int64_t K, const void *dyp, const void *xp) -> int {
     float *dw = grads + pb + w_off;
     if (fuse && linear_wgrad_adam_supported(d.T, N, K, dyp, xp, dw)) {
@@ -675,7 +683,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     TM_STEP(mm(d.h, d.f), 0, tm_op_linear_dgrad_ws(dt, d.T, d.h, d.f, dy, P(o.w_fc2), dg, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
     fused.clear();
-    TM_STEP(mm(d.h, d.f), 0, wgrad(pb, o.w_fc2, d.h, d.f, dy, ws + k.g));
+    TM_STEP(mm(d.h, d.f), wgrad_bytes(d.h, d.f, dy, ws + k.g, pb, o.w_fc2), wgrad(pb, o.w_fc2, d.h, d.f, dy, ws + k.g));
     // (below the top layer this bias gradient has come out of the first norm's backward pass of the layer above)
     if (bias && l == c.n_layers - 1) TM_STEP(0, es * Th, tm_op_bias_grad(dt, d.T, d.h, dy, G(o.b_fc2), red, acc, s));
     // activation
@@ -686,7 +694,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     TM_STEP(mm(d.f1, d.h), 0, tm_op_linear_dgrad_ws(dt, d.T, d.f1, d.h, du, P(o.w_fc1), dc, ws + pl.splitk, pl.splitk_bytes, s));
     if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_D_MLP_IN, dt, dc, act_bytes, s));
     TM_TRY(fork());
-    TM_STEP(mm(d.f1, d.h), 0, wgrad(pb, o.w_fc1, d.f1, d.h, du, ws + k.c));
+    TM_STEP(mm(d.f1, d.h), wgrad_bytes(d.f1, d.h, du, ws + k.c, pb, o.w_fc1), wgrad(pb, o.w_fc1, d.f1, d.h, du, ws + k.c));
     if (bias) TM_STEP(0, es * d.T * d.f1, tm_op_bias_grad(dt, d.T, d.f1, du, G(o.b_fc1), red, acc, s));
     // c = Norm(x1): dx1 = dy + norm gradient
     void *dx1 = ws + pl.dx1;
@@ -704,7 +712,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     // x1 = x + ctx Wout^T + bout
     TM_STEP(mm(d.h, d.A), 0, tm_op_linear_dgrad_ws(dt, d.T, d.h, d.A, dx1, P(o.w_out), ws + pl.dctx, ws + pl.splitk, pl.splitk_bytes, s));
     TM_TRY(fork());
-    TM_STEP(mm(d.h, d.A), 0, wgrad(pb, o.w_out, d.h, d.A, dx1, ws + k.ctx));
+    TM_STEP(mm(d.h, d.A), wgrad_bytes(d.h, d.A, dx1, ws + k.ctx, pb, o.w_out), wgrad(pb, o.w_out, d.h, d.A, dx1, ws + k.ctx));
     // attention, rotary
     TM_STEP(2 * attn_flops, 0,
             tm_op_attn_bwd(dt, c.seq, c.micro_batch, c.n_q_heads, c.n_kv_heads, c.head_dim, ws + k.qkv, ws + k.ctx,
@@ -718,7 +726,7 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
     TM_STEP(mm(d.nqkv, d.h), 0, tm_op_linear_dgrad_ws(dt, d.T, d.nqkv, d.h, ws + pl.dqkv, P(o.w_qkv), da, ws + pl.splitk, pl.splitk_bytes, s));
     if (cm) TM_TRY(tm_comm_call(cm, TM_COLL_ALL_REDUCE, TM_SCOPE_TP, TM_SITE_D_ATTN_IN, dt, da, act_bytes, s));
     TM_TRY(fork());
-    TM_STEP(mm(d.nqkv, d.h), 0, wgrad(pb, o.w_qkv, d.nqkv, d.h, ws + pl.dqkv, ws + k.a));
+    TM_STEP(mm(d.nqkv, d.h), wgrad_bytes(d.nqkv, d.h, ws + pl.dqkv, ws + k.a, pb, o.w_qkv), wgrad(pb, o.w_qkv, d.nqkv, d.h, ws + pl.dqkv, ws + k.a));
     if (bias) TM_STEP(0, es * d.T * d.nqkv, tm_op_bias_grad(dt, d.T, d.nqkv, ws + pl.dqkv, G(o.b_qkv), red, acc, s));
     // a = Norm(x): dx = dx1 + norm gradient
     // dx is the output gradient of the layer below: its column sums are that layer's FC2 bias gradient

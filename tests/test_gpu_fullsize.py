@@ -2,6 +2,7 @@
 times.  Products and attention are checked on sampled output rows the CPU checker evaluates one by
 one from the definition; stage iterations at full width and reduced depth are compared in full."""
 import math
+import os
 import time
 
 import numpy as np
@@ -151,22 +152,56 @@ def test_adam_sweep_sampled_elements(env):
     assert float(gr.abs().max()) == 0.0
 
 
-@pytest.mark.parametrize("preset", ["gpt175b", "llama70b"])
-def test_stage_full_width_one_layer(env, preset):
+# Max-norm tolerance of a whole stage at full width against the fp64 checker, by depth.  One layer meets the stated
+# 2e-2 (measured 1.5e-2 / 1.3e-2 / 1.4e-2 at the three widths).  From the second layer on a layer inherits the
+# rounding of the layers around it, and at these widths it amplifies what it inherits (tests/test_depth_reading.py:
+# a perturbation of one bf16 rounding on a layer's input moves the gradients that pass through the softmax 2.4 to
+# 3.3 times as much, the residual stream 1.75 times), so the distance to an fp64 reference grows with depth although
+# every layer on its own, given the same inputs, stays within 2e-2 (the chain test below).  Measured worst tensor:
+# 175B shard 3.6e-2 at 2 layers, 6.5e-2 at 4, 1.08e-1 at 12 (y: 1.3e-2, 1.8e-2, 2.2e-2); Llama-70B shard 2.7e-2 at 2.
+# The table holds the asserted bounds (measured values with a margin of about a quarter); y keeps 2e-2 up to 4 layers.
+DEPTH_TOL = {("gpt175b", 1): 2e-2, ("llama70b", 1): 2e-2, ("longctx", 1): 2e-2,
+             ("gpt175b", 2): 4.5e-2, ("llama70b", 2): 3.5e-2, ("gpt175b", 12): 1.4e-1}
+Y_TOL_DEEP = 3e-2          # stage output at 12 layers (measured 2.2e-2)
+# (one layer at the 175B width is held to 2e-2 by the chain test below, layers 0 and 11)
+STAGE_CASES = [("llama70b", 1), ("longctx", 1), ("gpt175b", 2), ("llama70b", 2)]
+
+
+@pytest.mark.parametrize("preset,layers", STAGE_CASES, ids=[f"{p}_L{l}" for p, l in STAGE_CASES])
+def test_stage_full_width_reduced_depth(env, progress, preset, layers):
+    """Whole-stage parity at the full width of the three large presets: one layer to the stated tolerance (the
+    16384-token shard included), two layers to the depth table above; every tensor's error and elementwise pass
+    rate are reported."""
     torch, tm = env
-    cfg = si.PRESETS[preset].replace(n_layers=1)
-    print(f"stage parity {preset} at full width, 1 layer", flush=True)
-    run_and_compare(torch, tm, cfg, progress=True)
+    cfg = si.PRESETS[preset].replace(n_layers=layers)
+    progress(f"stage parity {preset} at full width, {layers} layer(s)")
+    tol = DEPTH_TOL[(preset, layers)]
+    report = {}
+    run_and_compare(torch, tm, cfg, progress=progress, tol=lambda name: TOL_BF16 if name == "y" else tol, report=report)
+    worst = sorted(report.items(), key=lambda kv: -kv[1][0])[:4]
+    progress("  " + "; ".join(f"{k} err {e:.2e} pass {r:.4f}" for k, (e, r) in worst))
+
+
+@pytest.mark.skipif(os.environ.get("TM_TEST_FULL_DEPTH") != "1",
+                    reason="five minutes of fp64 checker time and about 110 GB of host memory: run with TM_TEST_FULL_DEPTH=1")
+def test_gpt175b_full_depth_against_checker(env, progress):
+    """The benchmark's workload, all 12 layers, against the fp64 checker run over the whole stage (measured: worst
+    tensor 1.08e-1 on a QKV weight gradient, y 2.2e-2, dx 8.2e-2; see the depth table)."""
+    torch, tm = env
+    cfg = si.PRESETS["gpt175b"]
+    report = {}
+    run_and_compare(torch, tm, cfg, progress=progress, adam=False, report=report,
+                    tol=lambda name: Y_TOL_DEEP if name == "y" else DEPTH_TOL[("gpt175b", 12)])
+    worst = sorted(report.items(), key=lambda kv: -kv[1][0])[:6]
+    progress("  " + "; ".join(f"{k} err {e:.2e} pass {r:.4f}" for k, (e, r) in worst))
 
 
 def test_gpt175b_full_depth_equals_chained_layers_and_layers_match_checker(env):
     """The benchmark's workload: 12 layers at the 175B-shard width.
 
-    Against an fp64 reference a deep bf16 stack cannot be held to 2e-2 at this width: with
-    N(0, 0.02^2) weights and hidden 12288 the attention logits have a standard deviation near 5, so
-    a relative error e on a layer's input moves its softmax weights by about 7e, and the bf16
-    roundings of every layer compound (measured: 1.5e-2 after one layer, 3.5e-2 after two).  The
-    full-depth run is therefore pinned in two steps that together say the same thing:
+    Against the fp64 checker run over the whole stage the distance grows with depth (depth table above; the full
+    run is test_gpt175b_full_depth_against_checker).  What the stated 2e-2 can and does hold is every layer on its
+    own; the full-depth run is therefore also pinned in two steps that together say so:
       1. the 12-layer call is BIT-IDENTICAL to twelve 1-layer calls chained through their own
          outputs (same kernels, same order: pins sequencing, stash and gradient offsets);
       2. individual layers of that chain (first and last) match the checker to 2e-2 when the checker
