@@ -53,6 +53,8 @@ static const TileConfig kConfigs[] = {
     {256, 256, 2, 4, 1, {1.00, 1.10, 1.06}}, {256, 256, 4, 2, 1, {1.00, 1.10, 1.06}},
     // the pipelined kernel with three LDS stages
     {256, 128, 4, 2, 1, {1.05, 0.78, 0.80}}, {128, 256, 2, 4, 1, {1.05, 0.78, 0.80}},
+    // the kernel with loader waves (gemm_ldw_kernel)
+    {256, 192, 4, 2, 1, {1.12, 1.17, 1.10}}, {128, 192, 2, 2, 2, {1.00, 1.00, 1.00}}, {256, 192, 4, 2, 1, {1.10, 1.10, 1.05}},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 
@@ -98,20 +100,38 @@ int gemm_mfma_force_config(int index) {
   return TM_OK;
 }
 
-// Configurations found by gemm_mfma_tune(), keyed by (layout, M, N, K).
+// Configurations found by gemm_mfma_tune(), keyed by (layout, M, N, K).  A weight-gradient product that also applies
+// the update (c_mode 3) spends most of its time in the epilogue, streaming the optimizer state; it is faster with
+// two small blocks per compute unit (one multiplies while the other streams) than with one large block, so it keeps
+// the best of the configurations that allow two blocks: layout key 3.
 typedef std::tuple<int, int64_t, int64_t, int64_t> TuneKey;
 static std::map<TuneKey, int> g_tuned;
 static std::mutex g_tuned_mutex;
+constexpr int kFusedLayoutKey = 3;
+
+static int heuristic_config_fused(const GemmArgs &g) {
+  double best = 1e300;
+  int pick = 0;
+  for (int c = 0; c < kNumConfigs; ++c) {
+    const TileConfig &t = kConfigs[c];
+    if (t.occ < 2) continue;
+    const int64_t nb = ceil_div(g.M, t.bm) * ceil_div(g.N, t.bn);
+    const double cost = (double)ceil_div(nb, 256 * t.occ) * t.occ * t.bm * t.bn / t.speed[2];
+    if (cost < best) best = cost, pick = c;
+  }
+  return pick;
+}
 
 static int pick_config(const GemmArgs &g) {
   const int f = forced_config();
   if (f >= 0) return f;
+  const bool fused = g.c_mode == 3;
   {
     std::lock_guard<std::mutex> lock(g_tuned_mutex);
-    auto it = g_tuned.find(TuneKey(layout_of(g), g.M, g.N, g.K));
+    auto it = g_tuned.find(TuneKey(fused ? kFusedLayoutKey : layout_of(g), g.M, g.N, g.K));
     if (it != g_tuned.end()) return it->second;
   }
-  return heuristic_config(g);
+  return fused ? heuristic_config_fused(g) : heuristic_config(g);
 }
 
 static int launch_config(const GemmArgs &g, int config, hipStream_t s) {
@@ -220,9 +240,11 @@ int gemm_mfma_tune(const GemmArgs *variants, int n, hipStream_t s) {
       if (rc == TM_OK && hipEventElapsedTime(&ms, e0, e1) == hipSuccess && ms < ms_of[c]) ms_of[c] = ms;
     }
   }
-  int best = 0;
-  for (int c = 1; c < kNumConfigs; ++c)
+  int best = 0, best_two = -1;  // best_two: among the configurations with two blocks per compute unit
+  for (int c = 0; c < kNumConfigs; ++c) {
     if (ms_of[c] < ms_of[best]) best = c;
+    if (kConfigs[c].occ >= 2 && (best_two < 0 || ms_of[c] < ms_of[best_two])) best_two = c;
+  }
   // the cost model's pick stays unless it loses by more than 2 %: keeps the choice stable against timer noise
   const int first = heuristic_config(v[0]);
   if (ms_of[first] <= 1.02f * ms_of[best]) best = first;
@@ -237,6 +259,7 @@ int gemm_mfma_tune(const GemmArgs *variants, int n, hipStream_t s) {
   }
   std::lock_guard<std::mutex> lock(g_tuned_mutex);
   g_tuned[key] = best;
+  if (layout_of(v[0]) == 2 && best_two >= 0) g_tuned[TuneKey(kFusedLayoutKey, v[0].M, v[0].N, v[0].K)] = best_two;
   return TM_OK;
 }
 

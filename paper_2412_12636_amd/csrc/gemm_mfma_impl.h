@@ -115,7 +115,9 @@ template <int EPI> __device__ __forceinline__ f32x16 mfma_for(bf16x8 a, bf16x8 b
   else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
-template <int TM, int TN, int EPI>
+// VB: accumulator registers of a 32x32 tile whose state reads are in flight together in the update epilogue (EPI 3):
+// all sixteen where a wave has 256 registers, eight where three waves share a SIMD's register file
+template <int TM, int TN, int EPI, int VB = 16>
 __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (&acc)[TM][TN], int row_base,
                                          int col_base, int l32, int hh) {
   if constexpr (EPI == 3) {
@@ -129,36 +131,39 @@ __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const int col = col_base + j * 32 + l32;
-        const bool col_ok = col < p.N;
-        uint32_t off[16];
-        float pw[16], mw[16], vw[16];
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = row_base + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-          off[v] = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
-        }
+        for (int v0 = 0; v0 < 16; v0 += VB) {
+          const int col = col_base + j * 32 + l32;
+          const bool col_ok = col < p.N;
+          uint32_t off[VB];
+          float pw[VB], mw[VB], vw[VB];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          pw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rp, off[v], 0, kNonTemporal));
-          mw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off[v], 0, kNonTemporal));
-          vw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, off[v], 0, kNonTemporal));
-        }
+          for (int u = 0; u < VB; ++u) {
+            const int v = v0 + u;
+            const int row = row_base + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+            off[u] = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
+          }
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float g = acc[i][j][v];
-          adam_one(pw[v], g, mw[v], vw[v], p.adam.a);
-          if (p.adam.store_grad)
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, g), rc, off[v], 0, kNonTemporal);
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, pw[v]), rp, off[v], 0, kNonTemporal);
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, mw[v]), rm, off[v], 0, kNonTemporal);
-          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, vw[v]), rv, off[v], 0, kNonTemporal);
-          const bf16 lo = (bf16)pw[v];
-          __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, lo), rl, col_ok ? off[v] >> 1 : 0xfffffff0u, 0,
-                                                kNonTemporal);
+          for (int u = 0; u < VB; ++u) {
+            pw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rp, off[u], 0, kNonTemporal));
+            mw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off[u], 0, kNonTemporal));
+            vw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, off[u], 0, kNonTemporal));
+          }
+#pragma unroll
+          for (int u = 0; u < VB; ++u) {
+            const float g = acc[i][j][v0 + u];
+            adam_one(pw[u], g, mw[u], vw[u], p.adam.a);
+            if (p.adam.store_grad)
+              __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, g), rc, off[u], 0, kNonTemporal);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, pw[u]), rp, off[u], 0, kNonTemporal);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, mw[u]), rm, off[u], 0, kNonTemporal);
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, vw[u]), rv, off[u], 0, kNonTemporal);
+            const bf16 lo = (bf16)pw[u];
+            __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, lo), rl, col_ok ? off[u] >> 1 : 0xfffffff0u, 0,
+                                                  kNonTemporal);
+          }
         }
-      }
     return;
   }
   if constexpr (EPI != 0) {
@@ -411,6 +416,73 @@ __device__ __forceinline__ void epilogue_lds(const MfmaGemmParams &p, const f32x
   }
 }
 
+// The same epilogue in pieces, for blocks in which only some waves hold accumulators: all NW waves copy the
+// residual in (residual_in) or the finished tile out, the accumulator waves add in between.
+template <int BM, int BN, int NW>
+__device__ __forceinline__ void epilogue_lds_copy(const MfmaGemmParams &p, char *lds, int m0, int n0, bool residual_in) {
+  constexpr int CPR = BN / 8, ROWB = BN * 2, NT = 64 * NW, CHUNKS = BM * CPR;
+  if (residual_in && !p.residual) return;
+  const int tid = threadIdx.x;
+  const rsrc_t rg = make_rsrc(residual_in ? (const void *)p.residual : (const void *)p.C, p.c_bytes);
+#pragma unroll
+  for (int it = 0; it < (CHUNKS + NT - 1) / NT; ++it) {
+    const int idx = it * NT + tid, row = idx / CPR, c = idx % CPR;
+    if (CHUNKS % NT != 0 && idx >= CHUNKS) break;  // the last pass may be ragged
+    const int gcol = n0 + c * 8;
+    const uint32_t off = gcol < p.N ? (uint32_t)(((int64_t)(m0 + row) * p.ldc + gcol) * 2) : 0xfffffff0u;
+    char *at = lds + row * ROWB + (epi_place<CPR>(c, row) << 4);
+    if (residual_in) {
+      *reinterpret_cast<u32x4 *>(at) = buf_load16(rg, off, 0);
+    } else {
+      const u32x4 v = *reinterpret_cast<const u32x4 *>(at);
+      __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u32, v), rg, off, 0, 0);
+    }
+  }
+}
+template <int BM, int BN, int TM, int TN>
+__device__ __forceinline__ void epilogue_lds_acc(const MfmaGemmParams &p, const f32x16 (&acc)[TM][TN], char *lds, int n0,
+                                                 int wrow, int wcol, int lane) {
+  constexpr int CPR = BN / 8, ROWB = BN * 2;
+  const int l32 = lane & 31, hh = lane >> 5;
+  const rsrc_t rbias = make_rsrc(p.bias ? (const void *)p.bias : p.C, (uint32_t)p.N * 2u);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int tcol = wcol + j * 32 + 8 * q + 4 * hh;  // column inside the tile
+      float bv[4] = {0.f, 0.f, 0.f, 0.f};
+      if (p.bias) {
+        const int col = n0 + tcol;
+        const u32x2 braw = __builtin_bit_cast(
+            u32x2, __builtin_amdgcn_raw_buffer_load_b64(rbias, col < p.N ? (uint32_t)col * 2u : 0xfffffff0u, 0, 0));
+        bv[0] = __builtin_bit_cast(float, braw[0] << 16);
+        bv[1] = __builtin_bit_cast(float, braw[0] & 0xffff0000u);
+        bv[2] = __builtin_bit_cast(float, braw[1] << 16);
+        bv[3] = __builtin_bit_cast(float, braw[1] & 0xffff0000u);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int row = wrow + i * 32 + l32;
+        char *at = lds + row * ROWB + (epi_place<CPR>(tcol >> 3, row) << 4) + ((tcol & 4) << 1);
+        float r[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) r[e] = acc[i][j][4 * q + e] + bv[e];
+        if (p.residual) {
+          const u32x2 rr = *reinterpret_cast<const u32x2 *>(at);
+          r[0] += __builtin_bit_cast(float, rr[0] << 16);
+          r[1] += __builtin_bit_cast(float, rr[0] & 0xffff0000u);
+          r[2] += __builtin_bit_cast(float, rr[1] << 16);
+          r[3] += __builtin_bit_cast(float, rr[1] & 0xffff0000u);
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[e] = (bf16)r[e];
+        *reinterpret_cast<bf16x4 *>(at) = o;
+      }
+    }
+  }
+}
+
 // =================================================================================================
 // pipelined kernel: WGM x WGN waves, two LDS stages, the barrier sits before the LAST reduction slice
 // =================================================================================================
@@ -565,6 +637,137 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
     epilogue_lds<BM, BN, NW, TM, TN>(p, acc, lds, m0, n0, wm * WM, wn * WN, lane);
   } else {
     epilogue<TM, TN, EPI>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
+  }
+}
+
+// =================================================================================================
+// kernel with loader waves: WGM x WGN waves multiply, NP more waves do nothing but fetch
+// =================================================================================================
+// A wave issues its instructions in order, and a global -> LDS load can only be issued while the memory pipeline
+// has room for it: a whole 64 KB stage goes through that pipeline at about 45 bytes per clock, so a wave that has
+// to issue its share of a stage between two MFMAs stands still for hundreds of clocks, and its MFMAs with it
+// (time stamps inside the pipelined kernel: the slice of a step that carries the loads takes 1100 clocks for 380
+// clocks of MFMA work).  Here the waves that multiply never issue a global load.  They read fragments and issue
+// MFMAs; NP extra waves (one per SIMD) issue all the loads of a step right after the step's barrier and then wait
+// for them, and the SIMD's issue logic serves the multiplying waves while a loader wave is held up.  Two LDS stages
+// and the same barrier placement as the pipelined kernel (before the last reduction slice of a step), so an output
+// element is accumulated in the same order as in every other configuration.
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(64 * (WGM * WGN + NP), 3) void gemm_ldw_kernel(const MfmaGemmParams p) {
+  extern __shared__ __align__(16) char lds[];
+  constexpr int NC = WGM * WGN;  // multiplying waves
+  constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
+  static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
+  typedef typename DirectSel<BM, BK, A_KC, NP>::type LA;  // the tiles are fetched by the NP loader waves
+  typedef typename DirectSel<BN, BK, B_KC, NP>::type LB;
+  constexpr int B_BASE = 2 * LA::BYTES;
+  constexpr int KS = BK / 16;
+  static_assert(KS % 2 == 0, "fragment buffers alternate");
+  constexpr int MF = TM * TN;
+  constexpr int DSN = TM * (A_KC ? 1 : 2) + TN * (B_KC ? 1 : 2);
+
+  int m0, n0;
+  tile_of_block(p, BM, BN, m0, n0);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nk = (p.K + BK - 1) / BK;
+
+  if (wave >= NC) {
+    // ---- loader wave: stage 0, barrier, stage 1; then per step: wait for step kt+1, barrier, fetch step kt+2 ----
+    const int lw = wave - NC;
+    LA la;
+    LB lb;
+    const rsrc_t ra = make_rsrc(p.A, p.a_bytes), rb = make_rsrc(p.B, p.b_bytes);
+    la.init(p.lda, m0, lw, lane);
+    lb.init(p.ldb, n0, lw, lane);
+    la.issue(ra, lds, 0, p.lda, lw);
+    lb.issue(rb, lds + B_BASE, 0, p.ldb, lw);
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    {
+      const int k1 = (1 < nk ? 1 : nk - 1) * BK;  // never past K: a surplus fetch repeats the last step
+      la.issue(ra, lds + LA::BYTES, k1, p.lda, lw);
+      lb.issue(rb, lds + B_BASE + LB::BYTES, k1, p.ldb, lw);
+    }
+    for (int kt = 0; kt < nk; ++kt) {
+      wait_vmcnt<0>();  // this wave's part of step kt+1 has landed
+      __builtin_amdgcn_s_barrier();
+      const int k2 = (kt + 2 < nk ? kt + 2 : nk - 1) * BK;
+      la.issue(ra, lds + (kt & 1) * LA::BYTES, k2, p.lda, lw);
+      lb.issue(rb, lds + B_BASE + (kt & 1) * LB::BYTES, k2, p.ldb, lw);
+    }
+    wait_vmcnt<0>();  // drain the look-ahead loads before the stages are reused or the block exits
+    if constexpr (EPI == 0) {
+      __syncthreads();
+      epilogue_lds_copy<BM, BN, NC + NP>(p, lds, m0, n0, /*residual_in=*/true);
+      __syncthreads();  // the multiplying waves add their accumulators in between
+      __syncthreads();
+      epilogue_lds_copy<BM, BN, NC + NP>(p, lds, m0, n0, /*residual_in=*/false);
+    }
+    return;
+  }
+
+  // ---- multiplying wave ----
+  const int wm = wave / WGN, wn = wave % WGN;
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  bf16x8 a[2][TM], b[2][TN];
+  __builtin_amdgcn_s_barrier();  // stage 0 is in LDS
+#pragma unroll
+  for (int i = 0; i < TM; ++i) a[0][i] = LA::frag(lds, wm * WM + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) b[0][j] = LB::frag(lds + B_BASE, wn * WN + j * 32, 0, lane);
+  __builtin_amdgcn_s_setprio(1);
+  for (int kt = 0; kt < nk; ++kt) {
+    const char *As = lds + (kt & 1) * LA::BYTES;
+    const char *Bs = lds + B_BASE + (kt & 1) * LB::BYTES;
+    const char *An = lds + ((kt + 1) & 1) * LA::BYTES;
+    const char *Bn = lds + B_BASE + ((kt + 1) & 1) * LB::BYTES;
+#pragma unroll
+    for (int ks = 0; ks + 1 < KS; ++ks) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) a[(ks + 1) & 1][i] = LA::frag(As, wm * WM + i * 32, ks + 1, lane);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) b[(ks + 1) & 1][j] = LB::frag(Bs, wn * WN + j * 32, ks + 1, lane);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma_for<EPI>(a[ks & 1][i], b[ks & 1][j], acc[i][j]);
+      sched_mid<MF, DSN, 0>();
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // every read of the current stage is complete; past the barrier the loaders overwrite it, and the next stage
+    // (complete: the loaders waited for it) may be read
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[0][i] = LA::frag(An, wm * WM + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[0][j] = LB::frag(Bn, wn * WN + j * 32, 0, lane);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = mfma_for<EPI>(a[(KS - 1) & 1][i], b[(KS - 1) & 1][j], acc[i][j]);
+    sched_last<MF, DSN, 0, 0>();
+  }
+  __builtin_amdgcn_s_setprio(0);
+  if constexpr (EPI == 0) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();  // the loaders' last loads have landed and every fragment read is done: the stages are free
+    epilogue_lds_copy<BM, BN, NC + NP>(p, lds, m0, n0, /*residual_in=*/true);
+    __syncthreads();
+    epilogue_lds_acc<BM, BN, TM, TN>(p, acc, lds, n0, wm * WM, wn * WN, lane);
+    __syncthreads();
+    epilogue_lds_copy<BM, BN, NC + NP>(p, lds, m0, n0, /*residual_in=*/false);
+  } else {
+    epilogue<TM, TN, EPI, 8>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
   }
 }
 
@@ -928,6 +1131,29 @@ static int launch_alt(const GemmArgs &g, hipStream_t s) {
   return check_launch("gemm_alt");
 }
 
+template <int BM, int BN, int WGM, int WGN, int NP, bool A_KC, bool B_KC, int EPI>
+static int launch_ldw(const GemmArgs &g, hipStream_t s) {
+  constexpr int BK = GEMM_BK;
+  const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, BM, BN);
+  constexpr int lds_bytes = 2 * (BM + BN) * BK * 2 > BM * BN * 2 ? 2 * (BM + BN) * BK * 2 : BM * BN * 2;
+  static_assert(lds_bytes <= 160 * 1024, "LDS");
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(&gemm_ldw_kernel<BM, BN, BK, WGM, WGN, NP, A_KC, B_KC, EPI>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+      return fail(TM_ELAUNCH, "gemm_mfma: cannot reserve %d bytes of LDS", lds_bytes);
+    attr_set = true;
+  }
+  const int64_t nblk = (int64_t)p.tiles_m * p.tiles_n;
+  if (nblk > 0x7fffffff) return fail(TM_ESIZE, "gemm_mfma: too many tiles");
+  if (g.k_splits > 1) return fail(TM_EINVAL, "gemm_mfma: the loader-wave kernel does not split the reduction");
+  if (EPI == 3 && !g.adam) return fail(TM_EINVAL, "gemm_mfma: the fused update needs its target");
+  static const std::string name = kernel_tag(NP == 4 ? "gemm_ldw4_kernel" : "gemm_ldw2_kernel", BM, BN, WGM, WGN, A_KC, B_KC, EPI);
+  g_last_kernel = name.c_str();
+  gemm_ldw_kernel<BM, BN, BK, WGM, WGN, NP, A_KC, B_KC, EPI><<<dim3((unsigned)nblk), 64 * (WGM * WGN + NP), lds_bytes, s>>>(p);
+  return check_launch("gemm_ldw");
+}
+
 template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs &g, hipStream_t s) {
   const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, 128, 128);
   static const std::string name = kernel_tag("gemm_staged_kernel", 128, 128, 2, 2, A_KC, B_KC, EPI);
@@ -942,6 +1168,8 @@ template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs
 #define TM_GEMM_ALT_CONFIGS(X) X(256, 256, 2, 4) X(256, 256, 4, 2)
 // ... then the pipelined kernel with three LDS stages of both tiles (tiles whose three stages fit 160 KB)
 #define TM_GEMM_PIPE33_CONFIGS(X) X(256, 128, 4, 2) X(128, 256, 2, 4)
+// ... then the kernel with loader waves (eight multiplying waves and four loaders)
+#define TM_GEMM_LDW_CONFIGS(X) X(256, 192, 4, 2, 4) X(128, 192, 2, 2, 2) X(256, 192, 4, 2, 2)
 #define TM_GEMM_CONFIGS(X) \
   X(128, 192, 2, 2) X(128, 128, 2, 2) X(192, 128, 2, 2) X(256, 192, 4, 2) X(192, 256, 2, 4) X(256, 256, 2, 4) \
   X(256, 256, 4, 2) X(256, 128, 4, 2) X(256, 192, 2, 2)
@@ -963,7 +1191,10 @@ template <bool A_KC, bool B_KC, int EPI> static int launch_staged(const GemmArgs
   template __global__ void gemm_alt_kernel<256, 256, GEMM_BK, 2, 4, AKC, BKC, EPI>(const MfmaGemmParams); \
   template __global__ void gemm_alt_kernel<256, 256, GEMM_BK, 4, 2, AKC, BKC, EPI>(const MfmaGemmParams); \
   template __global__ void gemm_pipe_kernel<256, 128, GEMM_BK, 4, 2, AKC, BKC, EPI, 3, 3>(const MfmaGemmParams); \
-  template __global__ void gemm_pipe_kernel<128, 256, GEMM_BK, 2, 4, AKC, BKC, EPI, 3, 3>(const MfmaGemmParams);
+  template __global__ void gemm_pipe_kernel<128, 256, GEMM_BK, 2, 4, AKC, BKC, EPI, 3, 3>(const MfmaGemmParams); \
+  template __global__ void gemm_ldw_kernel<256, 192, GEMM_BK, 4, 2, 4, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_ldw_kernel<128, 192, GEMM_BK, 2, 2, 2, AKC, BKC, EPI>(const MfmaGemmParams); \
+  template __global__ void gemm_ldw_kernel<256, 192, GEMM_BK, 4, 2, 2, AKC, BKC, EPI>(const MfmaGemmParams);
 
 // config: index into the list above, as chosen by gemm_mfma_config()
 template <bool A_KC, bool B_KC, int EPI> static int launch_layout(const GemmArgs &g, int config, hipStream_t s) {
@@ -980,6 +1211,10 @@ template <bool A_KC, bool B_KC, int EPI> static int launch_layout(const GemmArgs
 #define X(BM_, BN_, WGM_, WGN_) \
   if (config == idx++) return launch_pipe<BM_, BN_, WGM_, WGN_, A_KC, B_KC, EPI, 3, 3>(g, s);
   TM_GEMM_PIPE33_CONFIGS(X)
+#undef X
+#define X(BM_, BN_, WGM_, WGN_, NP_) \
+  if (config == idx++) return launch_ldw<BM_, BN_, WGM_, WGN_, NP_, A_KC, B_KC, EPI>(g, s);
+  TM_GEMM_LDW_CONFIGS(X)
 #undef X
   return fail(TM_EINVAL, "gemm_mfma: no tile configuration %d", config);
 }
