@@ -264,6 +264,37 @@ def time_roles(torch, tm, cfg, v_local: int, gen, stream: int, reps: int):
                     "dx0 once and writes both fp32 gradients once; head flops = 3 products of 2*T*v_local*h"}
 
 
+def power_probe(torch, tm, cfg, gen, stream: int, reps: int = 300):
+    """The largest forward product of the preset (FC1), sustained over `reps` back-to-back launches that rotate
+    through twelve weight matrices, once with the recipe's random operands and once with all-zero operands: the same
+    kernel, the same memory traffic and instruction stream, only the switching activity of the data differs.  A large
+    gap says the matrix cores run against the chip's power limit, not against issue or memory limits."""
+    T, N, K, nl = cfg.seq * cfg.micro_batch, cfg.fc1_width, cfg.hidden, 12
+    out = {"shape": [T, N, K], "reps": reps}
+    y = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+    for kind in ("random", "zeros"):
+        if kind == "random":
+            x = torch.empty((T, K), dtype=torch.float32, device="cuda").normal_(0, 1, generator=gen).to(torch.bfloat16)
+            w = torch.empty((nl, N, K), dtype=torch.float32, device="cuda").normal_(0, 0.02, generator=gen).to(torch.bfloat16)
+        else:
+            x = torch.zeros((T, K), dtype=torch.bfloat16, device="cuda")
+            w = torch.zeros((nl, N, K), dtype=torch.bfloat16, device="cuda")
+        for r in range(20):
+            tm.tm_op_linear_fwd(1, T, N, K, x, w[r % nl], None, None, y, stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for r in range(reps):
+            tm.tm_op_linear_fwd(1, T, N, K, x, w[r % nl], None, None, y, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out[kind] = {"ms": round(ms, 5), "tflops": round(2.0 * T * N * K / (ms * 1e-3) / 1e12, 1)}
+        del x, w
+    out["zeros_over_random"] = round(out["zeros"]["tflops"] / out["random"]["tflops"], 4)
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -276,10 +307,11 @@ def main() -> int:
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 4 GiB device copy before the timed region (reference reading "
                          "for the FETCH_SIZE / WRITE_SIZE counters under rocprofv3 --pmc)")
-    ap.add_argument("--micro-batches", type=int, default=0,
+    ap.add_argument("--micro-batches", type=int, default=12,
                     help="also time a whole iteration of this many micro-batches (gradient accumulation, squared "
-                         "gradient norm, clipping factor on the host, Adam on one data-parallel rank's slice)")
-    ap.add_argument("--dp", type=int, default=1, help="data-parallel size for --micro-batches (Adam updates 1/dp)")
+                         "gradient norm, clipping factor on the host, Adam on one data-parallel rank's slice); the paper's "
+                         "default profiles run 12 to 16 per iteration; 0 leaves it out")
+    ap.add_argument("--dp", type=int, default=3, help="data-parallel size for --micro-batches (Adam updates 1/dp)")
     ap.add_argument("--clip", type=float, default=1.0, help="gradient-norm limit for --micro-batches (0: off)")
     ap.add_argument("--sandbox", default="", metavar="DIR",
                     help="also time the shadow iteration (forward + backward, one micro-batch) under the record / replay "
@@ -287,6 +319,9 @@ def main() -> int:
     ap.add_argument("--moe", action="store_true",
                     help="also time forward + backward + Adam of the mixture-of-experts MLP shard shaped like the paper's "
                          "5.12T-parameter workload (one local expert, 16 experts, top-2, 2048 tokens)")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="also time the preset's FC1 forward product sustained, with random and with all-zero operands "
+                         "(same kernel and traffic; the gap shows how far the matrix cores run against the power limit)")
     ap.add_argument("--roles", type=int, default=0, metavar="V_LOCAL",
                     help="also time the first- and last-stage layers at the preset's width with this many vocabulary "
                          "rows per rank (e.g. 6400 = 51200 / 8)")
@@ -524,15 +559,19 @@ def main() -> int:
 
         iteration()
         torch.cuda.synchronize()
+        n_it = max(1, min(3, args.steps // 3))
         t0 = time.time()
-        for _ in range(max(1, args.steps // 2)):
+        for _ in range(n_it):
             iteration()
         torch.cuda.synchronize()
-        it_ms = (time.time() - t0) * 1e3 / max(1, args.steps // 2)
+        it_ms = (time.time() - t0) * 1e3 / n_it
         out["iteration"] = {"micro_batches": nmb, "dp": dp, "clip": args.clip, "ms": round(it_ms, 3),
                             "tokens_per_s": round(nmb * tokens / (it_ms * 1e-3), 1),
                             "tflops_whole_iteration": round(nmb * flops / (it_ms * 1e-3) / 1e12, 1),
-                            "note": "host wall clock; gradient accumulation from the second micro-batch on"}
+                            "mfma_frac_whole_iteration": round(nmb * flops / (it_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                            "iterations_timed": n_it,
+                            "note": "host wall clock over whole iterations (forward, backward, gradient norm, host-side "
+                                    "clipping factor, Adam on 1/dp of the state); gradient accumulation from the second micro-batch on"}
         tm.tm_stage_grad_mode(h, tm.TM_GRAD_TRANSIENT)
     if args.sandbox:
         out["sandbox"] = time_sandbox(torch, tm, h, x, y, dy, dx, stream, args.sandbox, max(3, args.steps))
@@ -540,6 +579,8 @@ def main() -> int:
         out["moe"] = time_moe(torch, tm, si, gen, stream, max(3, args.steps))
     if args.roles > 0:
         out["roles"] = time_roles(torch, tm, cfg, args.roles, gen, stream, max(3, args.steps))
+    if args.power_probe:
+        out["power_probe"] = power_probe(torch, tm, cfg, gen, stream)
     tm.tm_stage_destroy(h)
     if not args.no_cpu_baseline:
         del master, params, grads, m, v, ws

@@ -15,7 +15,7 @@ namespace tmk {
 int gemm_mfma_nt(const GemmArgs &g, int config, hipStream_t s);  // y = x W^T       (both reduction axes contiguous)
 int gemm_mfma_nn(const GemmArgs &g, int config, hipStream_t s);  // dx = dy W       (W read along its strided axis)
 int gemm_mfma_tn(const GemmArgs &g, int config, hipStream_t s);  // dW (+)= dy^T x  (both strided, fp32 result)
-int gemm_mfma_nn_partial(const GemmArgs &g, hipStream_t s);      // dx = dy W in k_splits fp32 parts, 128x192 tiles
+int gemm_mfma_nn_partial(const GemmArgs &g, bool large, hipStream_t s);  // dx = dy W in k_splits fp32 parts
 
 bool gemm_mfma_supported(const GemmArgs &g) {
   auto operand_ok = [&](const void *ptr, int64_t rs, int64_t cs, int64_t rows) {
@@ -147,11 +147,22 @@ static int launch_config(const GemmArgs &g, int config, hipStream_t s) {
 // over 12288) fills a fraction of the chip.  With scratch from the caller the reduction is cut into parts
 // whose 128x192 tiles make one pass of 512 blocks; the fp32 parts are added in part order and rounded once.
 // The choice depends on the shape only, so results stay reproducible.
-static int splitk_parts(const GemmArgs &g) {
+// With 256x192 tiles (the kernel with loader waves, one block per compute unit) when those make one pass of at least
+// 192 blocks, else with 128x192 tiles, two blocks per unit.
+static int splitk_parts(const GemmArgs &g, bool *large = nullptr) {
+  if (large) *large = false;
   if (g.c_mode != 0 || g.bias || g.residual || !(g.a_cs == 1 && g.b_cs != 1)) return 1;
   const int64_t tiles = ceil_div(g.M, 128) * ceil_div(g.N, 192);
   if (tiles > 256 || g.K < 4096) return 1;
-  int parts = (int)(512 / tiles);
+  const int64_t big = ceil_div(g.M, 256) * ceil_div(g.N, 192);
+  int parts = (int)(256 / big);
+  if (parts > 8) parts = 8;
+  while (parts > 1 && g.K % (64 * parts) != 0) --parts;
+  if (parts > 1 && big * parts >= 192) {
+    if (large) *large = true;
+    return parts;
+  }
+  parts = (int)(512 / tiles);
   if (parts > 8) parts = 8;
   while (parts > 1 && g.K % (64 * parts) != 0) --parts;
   return parts;
@@ -185,7 +196,8 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 }
 
 int gemm_mfma(const GemmArgs &g, hipStream_t s) {
-  const int parts = splitk_parts(g);
+  bool large = false;
+  const int parts = splitk_parts(g, &large);
   if (parts > 1 && g.splitk_scratch && g.splitk_bytes >= (int64_t)parts * g.M * g.N * 4 &&
       (((uintptr_t)g.splitk_scratch) & 15) == 0 && g.M * g.N * 4 < (1LL << 31) && forced_config() < 0) {
     GemmArgs p = g;
@@ -193,7 +205,7 @@ int gemm_mfma(const GemmArgs &g, hipStream_t s) {
     p.ldc = g.N;
     p.c_mode = 2;
     p.k_splits = parts;
-    if (int e = gemm_mfma_nn_partial(p, s)) return e;
+    if (int e = gemm_mfma_nn_partial(p, large, s)) return e;
     const int64_t groups = g.M * (g.N / 8);
     splitk_reduce_kernel<<<(unsigned)ceil_div(groups, (int64_t)256), 256, 0, s>>>((const float *)g.splitk_scratch, parts, g.M, g.N,
                                                                               (bf16 *)g.C, g.ldc);

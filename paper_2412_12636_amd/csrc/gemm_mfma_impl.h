@@ -653,8 +653,20 @@ __global__ __launch_bounds__(64 * WGM * WGN, (WGM * WGN == 4 && BM * BN <= 256 *
 // and the same barrier placement as the pipelined kernel (before the last reduction slice of a step), so an output
 // element is accumulated in the same order as in every other configuration.
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(64 * (WGM * WGN + NP), 3) void gemm_ldw_kernel(const MfmaGemmParams p) {
+__global__ __launch_bounds__(64 * (WGM * WGN + NP), 3) void gemm_ldw_kernel(const MfmaGemmParams p_in) {
   extern __shared__ __align__(16) char lds[];
+  MfmaGemmParams p = p_in;
+  if (gridDim.y > 1) {  // split reduction: this block row takes one part of K and writes its own result
+    const int part = p.K / (int)gridDim.y, first = (int)blockIdx.y * part;
+    const int64_t a_skip = A_KC ? (int64_t)first : (int64_t)first * p.lda;
+    const int64_t b_skip = B_KC ? (int64_t)first : (int64_t)first * p.ldb;
+    p.A += a_skip;
+    p.B += b_skip;
+    p.a_bytes -= (uint32_t)(a_skip * 2);
+    p.b_bytes -= (uint32_t)(b_skip * 2);
+    p.K = part;
+    p.C = (char *)p.C + (size_t)blockIdx.y * p.c_bytes;
+  }
   constexpr int NC = WGM * WGN;  // multiplying waves
   constexpr int WM = BM / WGM, WN = BN / WGN, TM = WM / 32, TN = WN / 32;
   static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tile");
@@ -1146,11 +1158,13 @@ static int launch_ldw(const GemmArgs &g, hipStream_t s) {
   }
   const int64_t nblk = (int64_t)p.tiles_m * p.tiles_n;
   if (nblk > 0x7fffffff) return fail(TM_ESIZE, "gemm_mfma: too many tiles");
-  if (g.k_splits > 1) return fail(TM_EINVAL, "gemm_mfma: the loader-wave kernel does not split the reduction");
+  if (g.k_splits > 1 && (EPI != 2 || g.K % ((int64_t)BK * g.k_splits) != 0))
+    return fail(TM_EINVAL, "gemm_mfma: split reduction needs whole steps per part and fp32 results");
   if (EPI == 3 && !g.adam) return fail(TM_EINVAL, "gemm_mfma: the fused update needs its target");
   static const std::string name = kernel_tag(NP == 4 ? "gemm_ldw4_kernel" : "gemm_ldw2_kernel", BM, BN, WGM, WGN, A_KC, B_KC, EPI);
   g_last_kernel = name.c_str();
-  gemm_ldw_kernel<BM, BN, BK, WGM, WGN, NP, A_KC, B_KC, EPI><<<dim3((unsigned)nblk), 64 * (WGM * WGN + NP), lds_bytes, s>>>(p);
+  gemm_ldw_kernel<BM, BN, BK, WGM, WGN, NP, A_KC, B_KC, EPI>
+      <<<dim3((unsigned)nblk, (unsigned)(g.k_splits > 1 ? g.k_splits : 1)), 64 * (WGM * WGN + NP), lds_bytes, s>>>(p);
   return check_launch("gemm_ldw");
 }
 

@@ -99,21 +99,40 @@ __global__ __launch_bounds__(kNormThreads) void norm_bwd_kernel(
       if (XSUM) xacc[c][i] = 0.f;
     }
   }
-  for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
+  // The loads of a block's NEXT row are in flight while it reduces and stores the current one (the raw 16-byte
+  // chunks wait in registers): without that a block spends most of a row's time waiting for its three loads.
+  typedef uint32_t raw4 __attribute__((ext_vector_type(4)));
+  raw4 nw[NCH], nx[NCH], nr[NCH];
+  auto fetch = [&](int64_t row) {
     const rsrc_t rd = make_rsrc(dout + row * h, row_bytes), rx = make_rsrc(x + row * h, row_bytes);
     const rsrc_t rr = make_rsrc(dres ? dres + row * h : dout, dres ? row_bytes : 0u);  // no residual: reads zeros
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+      const uint32_t off = (threadIdx.x + c * kNormThreads) * 16u;
+      nw[c] = __builtin_bit_cast(raw4, __builtin_amdgcn_raw_buffer_load_b128(rd, off, 0, 0));
+      nx[c] = __builtin_bit_cast(raw4, __builtin_amdgcn_raw_buffer_load_b128(rx, off, 0, 0));
+      nr[c] = __builtin_bit_cast(raw4, __builtin_amdgcn_raw_buffer_load_b128(rr, off, 0, 0));
+    }
+  };
+  auto unpack = [](raw4 raw, float (&out)[VN]) {
+    union { raw4 r; Vec<T> v; } u;
+    u.r = raw;
+#pragma unroll
+    for (int i = 0; i < VN; ++i) out[i] = to_f32(u.v.v[i]);
+  };
+  if ((int64_t)blockIdx.x < rows) fetch(blockIdx.x);
+  for (int64_t row = blockIdx.x; row < rows; row += gridDim.x) {
     const rsrc_t ro = make_rsrc(dx + row * h, row_bytes);
     const float mu = (KIND == TM_NORM_LAYERNORM) ? mean[row] : 0.f;
     const float rs = rstd[row];
     float w[NCH][VN], xh[NCH][VN], res[NCH][VN];
-    // all loads of the row are issued back to back
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-      const uint32_t off = (threadIdx.x + c * kNormThreads) * 16u;
-      buf_load_vec<T>(rd, off, w[c]);
-      buf_load_vec<T>(rx, off, xh[c]);
-      buf_load_vec<T>(rr, off, res[c]);
+      unpack(nw[c], w[c]);
+      unpack(nx[c], xh[c]);
+      unpack(nr[c], res[c]);
     }
+    if (row + gridDim.x < rows) fetch(row + gridDim.x);
     const int nchunk = h / VN;
     float sw = 0.f, swx = 0.f;
 #pragma unroll
