@@ -636,9 +636,12 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
   std::vector<Range> fused;  // this layer's matrices already updated, element ranges relative to the layer's block
   // bytes per parameter a weight-gradient product moves besides its operands when the update rides in its epilogue:
   // three fp32 states read and written, the bf16 copy, and the gradient where it is stored
+  // (plus the product's two operands, read once)
   const double fused_bytes_per_param = fuse ? 26.0 + (st->grad_mode != TM_GRAD_TRANSIENT ? 4.0 : 0.0) : 0.0;
   auto wgrad_bytes = [&](int64_t N, int64_t K, const void *dyp, const void *xp, int64_t pb, int64_t w_off) -> double {
-    return fuse && linear_wgrad_adam_supported(d.T, N, K, dyp, xp, grads + pb + w_off) ? fused_bytes_per_param * (double)N * (double)K : 0.0;
+    return fuse && linear_wgrad_adam_supported(d.T, N, K, dyp, xp, grads + pb + w_off)
+               ? fused_bytes_per_param * (double)N * (double)K + es * (double)d.T * (double)(N + K)
+               : 0.0;
   };
   auto wgrad = [&](int64_t pb, int64_t w_off, int64_t N, int64_t K, const void *dyp, const void *xp) -> int {
     float *dw = grads + pb + w_off;
