@@ -54,7 +54,7 @@ static const TileConfig kConfigs[] = {
     // the pipelined kernel with three LDS stages
     {256, 128, 4, 2, 1, {1.05, 0.78, 0.80}}, {128, 256, 2, 4, 1, {1.05, 0.78, 0.80}},
     // the kernel with loader waves (gemm_ldw_kernel)
-    {256, 192, 4, 2, 1, {1.12, 1.17, 1.10}}, {128, 192, 2, 2, 2, {1.00, 1.00, 1.00}}, {256, 192, 4, 2, 1, {1.10, 1.10, 1.05}},
+    {256, 192, 4, 2, 1, {1.12, 1.17, 1.10}}, {128, 192, 2, 2, 2, {0.70, 0.80, 0.85}}, {256, 192, 4, 2, 1, {1.10, 1.10, 1.05}},
 };
 constexpr int kNumConfigs = sizeof(kConfigs) / sizeof(kConfigs[0]);
 
@@ -271,7 +271,8 @@ int gemm_mfma_tune(const GemmArgs *variants, int n, hipStream_t s) {
   }
   std::lock_guard<std::mutex> lock(g_tuned_mutex);
   g_tuned[key] = best;
-  if (layout_of(v[0]) == 2 && best_two >= 0) g_tuned[TuneKey(kFusedLayoutKey, v[0].M, v[0].N, v[0].K)] = best_two;
+  if (layout_of(v[0]) == 2 && best_two >= 0)
+    g_tuned[TuneKey(kFusedLayoutKey, v[0].M, v[0].N, v[0].K)] = getenv("TM_GEMM_FUSED_ANY") ? best : best_two;
   return TM_OK;
 }
 
