@@ -138,6 +138,30 @@ def test_input_gradient_with_split_reduction(env):
     assert torch.equal(a, b) and torch.equal(c, d)
 
 
+def test_input_gradient_with_split_reduction_on_large_tiles(env):
+    """Same, at a shape whose parts fill the chip with 256 x 192 tiles (the kernel with loader waves writes the fp32
+    partial results): ragged in both output dimensions, eight parts of 512."""
+    torch, tm = env
+    T, N, K = 1000, 4096, 1096                   # 4 x 6 large tiles, eight parts: 192 blocks
+    rng = np.random.default_rng(22)
+    dy, w = rand(rng, (T, N), 0.1, BF16), rand(rng, (N, K), 0.05, BF16)
+    dyd, wd = to_dev(torch, dy, BF16), to_dev(torch, w, BF16)
+    s = stream_ptr(torch)
+    need = tm.tm_op_linear_dgrad_scratch_bytes(BF16, T, N, K)
+    assert need == 8 * T * K * 4
+    scratch = torch.empty(need, dtype=torch.uint8, device="cuda")
+    new = lambda: torch.full((T, K), float("nan"), dtype=torch.bfloat16, device="cuda")
+    a, b, c = new(), new(), new()
+    tm.tm_op_linear_dgrad_ws(BF16, T, N, K, dyd, wd, a, scratch, need, s)
+    scratch.fill_(255)                           # stale partial results must not matter
+    tm.tm_op_linear_dgrad_ws(BF16, T, N, K, dyd, wd, b, scratch, need, s)
+    tm.tm_op_linear_dgrad(BF16, T, N, K, dyd, wd, c, s)
+    torch.cuda.synchronize()
+    ref = dy.astype(np.float64) @ w.astype(np.float64)
+    assert rel_err(to_host(a), ref) <= TOL_BF16 and rel_err(to_host(c), ref) <= TOL_BF16
+    assert torch.equal(a, b)
+
+
 def test_gradient_overwrite_mode_ignores_old_contents(env):
     torch, tm = env
     rng = np.random.default_rng(4)
