@@ -271,7 +271,7 @@ __device__ __forceinline__ void fwd_finish(const FlashParams &p, FwdRow &r, int 
 // block = 128 query rows of one (batch entry, query head); wave = 32 query rows
 __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) {
   __shared__ __align__(1024) char lds[2][2][TILE_BYTES];  // [stage][K, V]
-  const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
+  const int qt = gridDim.z - 1 - blockIdx.z, g = blockIdx.x, n = blockIdx.y;  // heads fastest, longest walks first
   const int kap = g / (p.nq / p.nkv);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
 // Half as many steps, and the two waves of a SIMD overlap each other's softmax and MFMA phases.
 __global__ __launch_bounds__(512, 1) void flash_fwd_split_kernel(const FlashParams p) {
   extern __shared__ __align__(1024) char smem[];  // [stage][parity][K, V] tiles
-  const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
+  const int qt = gridDim.z - 1 - blockIdx.z, g = blockIdx.x, n = blockIdx.y;  // heads fastest, longest walks first
   const int kap = g / (p.nq / p.nkv);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int qg = wave & 3, par = wave >> 2;
@@ -439,7 +439,7 @@ __device__ __forceinline__ void dq_tile(const char *kt, const char *vt, const bf
 
 __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams p) {
   __shared__ __align__(1024) char lds[2][2][TILE_BYTES];  // [stage][K, V]
-  const int qt = gridDim.x - 1 - blockIdx.x, g = blockIdx.y, n = blockIdx.z;
+  const int qt = gridDim.z - 1 - blockIdx.z, g = blockIdx.x, n = blockIdx.y;  // heads fastest, longest walks first
   const int kap = g / (p.nq / p.nkv);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
@@ -497,7 +497,7 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
 // =================================================================================================
 __global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams p) {
   extern __shared__ __align__(1024) char smem[];  // [stage][Q, dO] tiles, then [stage][lse, D] rows of floats
-  const int kt = blockIdx.x, g = blockIdx.y, n = blockIdx.z;
+  const int kt = blockIdx.z, g = blockIdx.x, n = blockIdx.y;  // heads fastest, longest walks first
   const int group = p.nq / p.nkv, kap = g / group;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kr = wave & 3, t = wave >> 2;  // key-row group, query half
@@ -709,7 +709,11 @@ int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   p.qkv = (const bf16 *)qkv;
   p.ctx = (bf16 *)ctx;
   p.lse = lse;
-  dim3 grid((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
+  if (ceil_div(seq, 128) > 65535 || batch > 65535) return fail(TM_ESIZE, "flash_fwd: sequence or batch too long for the grid");
+  // Block order = dispatch order: all heads of the longest walk (last query tile) first, then the next shorter one.
+  // With the heads outermost instead, a long sequence's late heads start their longest walks when the chip is
+  // already draining (16384 tokens, 8 heads, 512 block slots: 408 tile steps end to end against 258 balanced).
+  dim3 grid((unsigned)nq, (unsigned)batch, (unsigned)ceil_div(seq, 128));
   if (use_split(grid)) {
     const int lds = 8 * TILE_BYTES;
     static bool attr_set = false;
@@ -745,8 +749,9 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   p.dqkv = (bf16 *)dqkv;
   p.part = nq == nkv ? nullptr : part;
   if (nq != nkv && !part) return fail(TM_EINVAL, "flash_bwd: grouped heads need the partial buffer");
-  dim3 gq((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
-  dim3 gk((unsigned)ceil_div(seq, 128), (unsigned)nq, (unsigned)batch);
+  if (ceil_div(seq, 128) > 65535 || batch > 65535) return fail(TM_ESIZE, "flash_bwd: sequence or batch too long for the grid");
+  dim3 gq((unsigned)nq, (unsigned)batch, (unsigned)ceil_div(seq, 128));  // heads fastest: see the forward launch
+  dim3 gk((unsigned)nq, (unsigned)batch, (unsigned)ceil_div(seq, 128));
   const int lds = 4 * TILE_BYTES + 2 * 2 * TILE * (int)sizeof(float) + 128 * D * 2;  // tiles, row statistics, V fragments
   static bool attr_set = false;
   if (!attr_set) {
