@@ -437,11 +437,18 @@ __device__ __forceinline__ void dq_tile(const char *kt, const char *vt, const bf
   }
 }
 
-__global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams p) {
-  __shared__ __align__(1024) char lds[2][2][TILE_BYTES];  // [stage][K, V]
-  const int qt = gridDim.z - 1 - blockIdx.z, g = blockIdx.x, n = blockIdx.y;  // heads fastest, longest walks first
+// block = 128 query rows (tile qt) of one (batch entry, query head), four waves; lds: [stage][K, V] tiles, 64 KB.
+// In a block of eight waves the other four only keep the barrier count (one barrier per key tile).
+__device__ __forceinline__ void dq_block(const FlashParams &p, char *lds_base, int qt, int g, int n) {
+  char (*lds)[2][TILE_BYTES] = reinterpret_cast<char (*)[2][TILE_BYTES]>(lds_base);
   const int kap = g / (p.nq / p.nkv);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  if (wave >= 4) {
+    const int kv_end_x = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
+    const int ntile_x = (kv_end_x + TILE - 1) / TILE;
+    for (int jt = 0; jt < ntile_x; ++jt) __builtin_amdgcn_s_barrier();
+    return;
+  }
   const int l32 = lane & 31, hh = lane >> 5;
   const int q0w = qt * 128 + wave * 32;
   const int q = q0w + l32;
@@ -487,6 +494,10 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
   wait_loads();
   if (qvalid) store_transposed(acc, p.scale, p.dqkv + ((int64_t)q * p.batch + n) * p.row + g * D, hh);
 }
+__global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams p) {
+  __shared__ __align__(1024) char lds[4 * TILE_BYTES];
+  dq_block(p, lds, gridDim.z - 1 - blockIdx.z, blockIdx.x, blockIdx.y);  // heads fastest, longest walks first
+}
 
 // =================================================================================================
 // dK, dV: block = 128 key rows of one (batch entry, query head), eight waves: wave = 32 key rows x one 32-query
@@ -495,9 +506,9 @@ __global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams 
 // through LDS at the end (first half + second half: a fixed order).  One query head per kv head: the block's
 // result is the gradient.  Grouped heads: it is that head's fp32 partial.
 // =================================================================================================
-__global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams p) {
-  extern __shared__ __align__(1024) char smem[];  // [stage][Q, dO] tiles, then [stage][lse, D] rows of floats
-  const int kt = blockIdx.z, g = blockIdx.x, n = blockIdx.y;  // heads fastest, longest walks first
+// smem: [stage][Q, dO] tiles, then [stage][lse, D] rows of floats, then the V fragments (kDkvLds bytes)
+constexpr int kDkvLds = 4 * TILE_BYTES + 2 * 2 * TILE * (int)sizeof(float) + 128 * D * 2;
+__device__ __forceinline__ void dkv_block(const FlashParams &p, char *smem, int kt, int g, int n) {
   const int group = p.nq / p.nkv, kap = g / group;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kr = wave & 3, t = wave >> 2;  // key-row group, query half
@@ -645,6 +656,23 @@ __global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams
   }
 }
 
+__global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams p) {
+  extern __shared__ __align__(1024) char smem[];
+  dkv_block(p, smem, blockIdx.z, blockIdx.x, blockIdx.y);  // heads fastest, longest walks first
+}
+
+// Both backward kernels in one launch, for grids that leave compute units idle (at most one block of each kind per
+// unit): the dK/dV block of key tile r and the dQ block of query tile last - r alternate in dispatch order, both
+// kinds longest first, so that the chip works on the two independent halves of the backward pass at once instead of
+// waiting twice for a longest walk (2048 tokens, 12 heads: 192 + 192 blocks on 256 units).  Blocks of eight waves;
+// in a dQ block four of them only keep the barrier count.
+__global__ __launch_bounds__(512, 1) void flash_bwd_both_kernel(const FlashParams p) {
+  extern __shared__ __align__(1024) char smem[];
+  const int rank = blockIdx.z >> 1, tiles = gridDim.z >> 1;
+  if (blockIdx.z & 1) dq_block(p, smem, tiles - 1 - rank, blockIdx.x, blockIdx.y);
+  else dkv_block(p, smem, rank, blockIdx.x, blockIdx.y);
+}
+
 // dK, dV of a kv head = sum of its query heads' partials, added in head order; thread = 4 columns
 __global__ __launch_bounds__(256) void flash_dkv_reduce_kernel(const FlashParams p) {
   const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;  // over [batch][nkv][seq][2 * D / 4]
@@ -691,6 +719,19 @@ static FlashParams make_params(int64_t seq, int64_t batch, int64_t nq, int64_t n
 // pass, where its 128 KB blocks wait for LDS beside the weight-gradient products of the other stream: not kept.)
 static bool use_split(dim3 grid) {
   if (const char *e = getenv("TM_ATTN_SPLIT")) return e[0] == '1';
+  static int units = 0;
+  if (!units) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        units <= 0)
+      units = 256;
+  }
+  return (int64_t)grid.x * grid.y * grid.z <= units;
+}
+
+// One launch for both backward kernels where neither fills the chip by itself.  TM_ATTN_BWD_BOTH=0 / 1 forces the choice.
+static bool use_both(dim3 grid) {
+  if (const char *e = getenv("TM_ATTN_BWD_BOTH")) return e[0] == '1';
   static int units = 0;
   if (!units) {
     int dev = 0;
@@ -750,19 +791,27 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
   p.part = nq == nkv ? nullptr : part;
   if (nq != nkv && !part) return fail(TM_EINVAL, "flash_bwd: grouped heads need the partial buffer");
   if (ceil_div(seq, 128) > 65535 || batch > 65535) return fail(TM_ESIZE, "flash_bwd: sequence or batch too long for the grid");
-  dim3 gq((unsigned)nq, (unsigned)batch, (unsigned)ceil_div(seq, 128));  // heads fastest: see the forward launch
-  dim3 gk((unsigned)nq, (unsigned)batch, (unsigned)ceil_div(seq, 128));
-  const int lds = 4 * TILE_BYTES + 2 * 2 * TILE * (int)sizeof(float) + 128 * D * 2;  // tiles, row statistics, V fragments
+  const unsigned tiles = (unsigned)ceil_div(seq, 128);
+  dim3 gq((unsigned)nq, (unsigned)batch, tiles);  // heads fastest: see the forward launch
+  const int lds = kDkvLds;
+  static_assert(kDkvLds >= 4 * TILE_BYTES, "the dQ block's tiles fit the dK/dV block's LDS");
   static bool attr_set = false;
   if (!attr_set) {
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(&flash_bwd_dkv_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void *>(&flash_bwd_both_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess)
       return fail(TM_ELAUNCH, "flash_bwd: cannot reserve LDS");
     attr_set = true;
   }
   g_last_kernel = "flash_bwd_dq_kernel+flash_bwd_dkv_kernel";
-  flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
-  flash_bwd_dkv_kernel<<<gk, 512, lds, s>>>(p);
+  if (use_both(gq) && 2 * tiles <= 65535) {
+    g_last_kernel = "flash_bwd_both_kernel";
+    flash_bwd_both_kernel<<<dim3((unsigned)nq, (unsigned)batch, 2 * tiles), 512, lds, s>>>(p);
+  } else {
+    flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
+    flash_bwd_dkv_kernel<<<gq, 512, lds, s>>>(p);
+  }
   if (p.part) {
     const int64_t total = batch * nkv * seq * (2 * D / 4);
     flash_dkv_reduce_kernel<<<(unsigned)ceil_div(total, (int64_t)256), 256, 0, s>>>(p);
