@@ -418,6 +418,47 @@ def test_attention_block_forms(env, monkeypatch, split, seq, batch, nq, nkv):
     assert rel_err(got[..., A + nkv * d:], dv.reshape(seq, batch, -1)) <= tol
 
 
+@pytest.mark.parametrize("both", ["0", "1"], ids=["two_launches", "one_launch"])
+@pytest.mark.parametrize("seq,batch,nq,nkv", [(700, 1, 3, 3), (300, 2, 4, 2), (64, 1, 1, 1), (1, 1, 2, 1), (129, 1, 2, 2),
+                                               (193, 1, 2, 1)],
+                         ids=["ragged_11_key_tiles", "grouped_heads", "one_key_tile", "one_position", "one_row_past_a_block",
+                              "one_row_past_a_key_tile"])
+def test_attention_backward_launch_forms(env, monkeypatch, both, seq, batch, nq, nkv):
+    """The head-size-128 backward pass runs as two launches (dQ blocks, then dK/dV blocks) or, for grids that leave
+    compute units idle, as one launch that holds both kinds of blocks (TM_ATTN_BWD_BOTH forces one).  Each form against
+    the checker; nothing may be written past the tensor's last row."""
+    torch, tm = env
+    monkeypatch.setenv("TM_ATTN_BWD_BOTH", both)
+    d, dtype = 128, BF16
+    print(f"attention backward form both={both} seq={seq} batch={batch} nq={nq} nkv={nkv}", flush=True)
+    rng = np.random.default_rng(seq * 11 + nq)
+    A, W = nq * d, (nq + 2 * nkv) * d
+    qkv = rand(rng, (seq, batch, W), 1.0, dtype)
+    dctx = rand(rng, (seq, batch, A), 0.1, dtype)
+    s = stream_ptr(torch)
+    qd = to_dev(torch, qkv, dtype)
+    ctx = torch.empty((seq, batch, A), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((batch, nq, seq), dtype=torch.float32, device="cuda")
+    tm.tm_op_attn_fwd(dtype, seq, batch, nq, nkv, d, qd, ctx, lse, s)
+    q64 = qkv.astype(np.float64)
+    q = q64[..., :A].reshape(seq, batch, nq, d)
+    k = q64[..., A:A + nkv * d].reshape(seq, batch, nkv, d)
+    v = q64[..., A + nkv * d:].reshape(seq, batch, nkv, d)
+    tol = tol_of(dtype)
+    guard = 64                                      # rows after the tensor: nothing may be written there
+    dqkv = torch.full((seq + guard, batch, W), float("nan"), dtype=torch.bfloat16, device="cuda")
+    scratch = torch.empty(tm.tm_op_attn_bwd_scratch_bytes(dtype, seq, batch, nq, nkv, d), dtype=torch.uint8, device="cuda")
+    tm.tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, qd, ctx, to_dev(torch, dctx, dtype), lse, scratch, dqkv[:seq], s)
+    torch.cuda.synchronize()
+    assert torch.isnan(dqkv[seq:]).all()
+    dq, dk, dv = so.attention_bwd(dctx.astype(np.float64).reshape(seq, batch, nq, d), q, k, v)
+    got = to_host(dqkv[:seq])
+    assert np.isfinite(got).all()
+    assert rel_err(got[..., :A], dq.reshape(seq, batch, A)) <= tol
+    assert rel_err(got[..., A:A + nkv * d], dk.reshape(seq, batch, -1)) <= tol
+    assert rel_err(got[..., A + nkv * d:], dv.reshape(seq, batch, -1)) <= tol
+
+
 def test_attention_is_bit_reproducible(env):
     torch, tm = env
     rng = np.random.default_rng(8)
