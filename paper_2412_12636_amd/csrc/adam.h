@@ -47,4 +47,12 @@ struct AdamTarget {
   AdamScalars a;
 };
 
+// Up to eight stretches of one flat state for one launch of the update: element ranges and the first block of each.
+constexpr int kAdamMaxSegments = 8;
+struct AdamSegments {
+  int n;
+  int block0[kAdamMaxSegments];
+  int64_t first[kAdamMaxSegments], count[kAdamMaxSegments];
+};
+
 }  // namespace tmk

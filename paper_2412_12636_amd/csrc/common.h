@@ -113,5 +113,7 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // Adam over flat arrays (elementwise.hip): one sweep at full HBM rate.
 int adam_launch(int64_t n, float *p, float *g, float *m, float *v, void *p_bf16, const tm_adam_hparams_t *hp, int64_t step,
                 hipStream_t s);
+int adam_launch_segments(int n_seg, const int64_t *first, const int64_t *count, float *p, float *g, float *m, float *v,
+                         void *p_bf16, const tm_adam_hparams_t *hp, int64_t step, hipStream_t s);
 
 }  // namespace tmk

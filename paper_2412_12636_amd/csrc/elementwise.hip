@@ -133,13 +133,12 @@ constexpr int kAdamThreads = 64;
 // long stride the HBM channels see scattered pages and the rate drops by a fifth), streaming
 // (non-temporal) accesses since nothing is re-read.  Reads g,p,m,v; writes p,m,v (+ bf16 p, + zeroed g).
 template <bool LOWP, bool ZERO>
-__global__ __launch_bounds__(kAdamThreads) void adam_kernel(float *__restrict__ p, float *__restrict__ g,
-                                                         float *__restrict__ m, float *__restrict__ v,
-                                                         bf16 *__restrict__ p_lowp, int64_t n, AdamScalars a) {
+__device__ __forceinline__ void adam_chunk(float *__restrict__ p, float *__restrict__ g, float *__restrict__ m,
+                                           float *__restrict__ v, bf16 *__restrict__ p_lowp, int64_t n, int64_t i,
+                                           const AdamScalars &a) {
   typedef float f32x4 __attribute__((ext_vector_type(4)));
   typedef bf16 bf16x4 __attribute__((ext_vector_type(4)));
   const int64_t nvec = n / 4;
-  const int64_t i = (int64_t)blockIdx.x * kAdamThreads + threadIdx.x;
   if (i < nvec) {
     f32x4 pv = __builtin_nontemporal_load(reinterpret_cast<f32x4 *>(p) + i);
     f32x4 gv = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g) + i);
@@ -175,6 +174,26 @@ __global__ __launch_bounds__(kAdamThreads) void adam_kernel(float *__restrict__ 
     if (LOWP) p_lowp[tail] = (bf16)pk;
     if (ZERO) g[tail] = 0.f;
   }
+}
+template <bool LOWP, bool ZERO>
+__global__ __launch_bounds__(kAdamThreads) void adam_kernel(float *__restrict__ p, float *__restrict__ g,
+                                                         float *__restrict__ m, float *__restrict__ v,
+                                                         bf16 *__restrict__ p_lowp, int64_t n, AdamScalars a) {
+  adam_chunk<LOWP, ZERO>(p, g, m, v, p_lowp, n, (int64_t)blockIdx.x * kAdamThreads + threadIdx.x, a);
+}
+// The same update over several stretches of one state in one launch (the short vectors between the matrices of a
+// layer): block b serves the stretch whose block range holds it.
+template <bool LOWP, bool ZERO>
+__global__ __launch_bounds__(kAdamThreads) void adam_segments_kernel(float *__restrict__ p, float *__restrict__ g,
+                                                                  float *__restrict__ m, float *__restrict__ v,
+                                                                  bf16 *__restrict__ p_lowp, AdamSegments segs, AdamScalars a) {
+  int sidx = 0;
+#pragma unroll
+  for (int q = 1; q < kAdamMaxSegments; ++q)
+    if (q < segs.n && (int)blockIdx.x >= segs.block0[q]) sidx = q;
+  const int64_t first = segs.first[sidx], n = segs.count[sidx];
+  const int64_t i = (int64_t)((int)blockIdx.x - segs.block0[sidx]) * kAdamThreads + threadIdx.x;
+  adam_chunk<LOWP, ZERO>(p + first, g + first, m + first, v + first, LOWP ? p_lowp + first : nullptr, n, i, a);
 }
 
 // one chunk per thread, blocks in address order (see adam_kernel); the kernels' loops run once
@@ -412,6 +431,52 @@ int adam_launch(int64_t n, float *p, float *g, float *m, float *v, void *p_bf16,
   else
     adam_kernel<false, false><<<grid, kAdamThreads, 0, s>>>(p, g, m, v, nullptr, n, a);
   return check_launch("adam");
+}
+// n_seg stretches [first[i], first[i] + count[i]) of one state, in one launch where they are few and aligned
+int adam_launch_segments(int n_seg, const int64_t *first, const int64_t *count, float *p, float *g, float *m, float *v,
+                         void *p_bf16, const tm_adam_hparams_t *hp, int64_t step, hipStream_t s) {
+  bool one = n_seg >= 1 && n_seg <= kAdamMaxSegments;
+  int64_t blocks = 0;
+  for (int i = 0; one && i < n_seg; ++i) {
+    if (first[i] % 4 || count[i] <= 0) one = false;
+    else blocks += ceil_div(count[i] / 4 > 0 ? count[i] / 4 : 1, (int64_t)kAdamThreads);
+  }
+  if (!one || blocks > 0x7fffffffLL) {  // one launch each
+    for (int i = 0; i < n_seg; ++i) {
+      if (count[i] <= 0) continue;
+      if (int e = adam_launch(count[i], p + first[i], g + first[i], m + first[i], v + first[i],
+                              p_bf16 ? (char *)p_bf16 + first[i] * 2 : nullptr, hp, step, s))
+        return e;
+    }
+    return TM_OK;
+  }
+  if (!hp || !p || !g || !m || !v) return fail(TM_EINVAL, "adam: NULL pointer");
+  if (step < 1) return fail(TM_EINVAL, "adam: step must be >= 1 (got %lld)", (long long)step);
+  if (!(hp->beta1 >= 0.0 && hp->beta1 < 1.0 && hp->beta2 >= 0.0 && hp->beta2 < 1.0))
+    return fail(TM_EINVAL, "adam: betas must lie in [0, 1)");
+  if (((uintptr_t)p | (uintptr_t)g | (uintptr_t)m | (uintptr_t)v) & 15 || ((uintptr_t)p_bf16 & 7))
+    return fail(TM_EALIGN, "adam: arrays must be 16-byte aligned");
+  AdamSegments segs = {};
+  segs.n = n_seg;
+  int b0 = 0;
+  for (int i = 0; i < n_seg; ++i) {
+    segs.first[i] = first[i];
+    segs.count[i] = count[i];
+    segs.block0[i] = b0;
+    b0 += (int)ceil_div(count[i] / 4 > 0 ? count[i] / 4 : 1, (int64_t)kAdamThreads);
+  }
+  const AdamScalars a = make_adam_scalars(hp, step);
+  const bool lowp = p_bf16 != nullptr, zero = hp->zero_grads != 0;
+  g_last_kernel = "adam_segments_kernel";
+  if (lowp && zero)
+    adam_segments_kernel<true, true><<<(unsigned)b0, kAdamThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, segs, a);
+  else if (lowp)
+    adam_segments_kernel<true, false><<<(unsigned)b0, kAdamThreads, 0, s>>>(p, g, m, v, (bf16 *)p_bf16, segs, a);
+  else if (zero)
+    adam_segments_kernel<false, true><<<(unsigned)b0, kAdamThreads, 0, s>>>(p, g, m, v, nullptr, segs, a);
+  else
+    adam_segments_kernel<false, false><<<(unsigned)b0, kAdamThreads, 0, s>>>(p, g, m, v, nullptr, segs, a);
+  return check_launch("adam_segments");
 }
 }  // namespace tmk
 

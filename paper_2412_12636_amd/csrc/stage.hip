@@ -758,11 +758,24 @@ static int stage_bwd(tm_stage_t *st, const void *dy_in, void *dx_out, void *stre
       s = so;  // TM_STEP brackets the stream named s
       // the flat sweep over what the products have not updated: the stretches between the fused matrices
       std::sort(fused.begin(), fused.end(), [](const Range &a, const Range &b) { return a.first < b.first; });
-      int64_t at = 0;
+      // (one launch for all of them: the vectors of a layer are a few thousand elements each)
+      std::vector<int64_t> seg_first, seg_count;
+      int64_t at = 0, left = 0;
       for (size_t i = 0; i <= fused.size(); ++i) {
         const int64_t end = i < fused.size() ? fused[i].first : o.total;
-        if (end > at) TM_STEP(0, per_param * (double)(end - at), adam_slice(st, pb + at, end - at, hp, step, so));
+        if (end > at) {
+          seg_first.push_back(pb + at);
+          seg_count.push_back(end - at);
+          left += end - at;
+        }
         if (i < fused.size()) at = fused[i].first + fused[i].count;
+      }
+      if (left > 0) {
+        const bool lowp = c.dtype == TM_DTYPE_BF16;
+        float *master = lowp ? st->buf.master : (float *)st->buf.params;
+        TM_STEP(0, per_param * (double)left,
+                adam_launch_segments((int)seg_first.size(), seg_first.data(), seg_count.data(), master, st->buf.grads,
+                                     st->buf.exp_avg, st->buf.exp_avg_sq, lowp ? st->buf.params : nullptr, hp, step, so));
       }
       s = s_keep;
     }
