@@ -268,19 +268,23 @@ __device__ __forceinline__ void fwd_finish(const FlashParams &p, FwdRow &r, int 
   }
 }
 
-// block = 128 query rows of one (batch entry, query head); wave = 32 query rows
-__global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) {
+// block = 32 NW query rows of one (batch entry, query head); wave = 32 query rows.  Four waves, two blocks per
+// compute unit; or eight waves, one block: the same waves per unit, but every staged K / V tile serves twice the query
+// rows, which halves the bytes a unit pulls from L2 into LDS per MFMA (what bounds the walk of a long sequence).
+template <int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void flash_fwd_kernel(const FlashParams p) {
   __shared__ __align__(1024) char lds[2][2][TILE_BYTES];  // [stage][K, V]
+  constexpr int QB = 32 * NW;
   const int qt = gridDim.z - 1 - blockIdx.z, g = blockIdx.x, n = blockIdx.y;  // heads fastest, longest walks first
   const int kap = g / (p.nq / p.nkv);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int l32 = lane & 31, hh = lane >> 5;
-  const int q0w = qt * 128 + wave * 32;
+  const int q0w = qt * QB + wave * 32;
   const int q = q0w + l32;
   const int64_t tstride = (int64_t)p.batch * p.row;  // elements between consecutive positions
   const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
   const rsrc_t rs = make_rsrc(p.qkv, p.qkv_bytes);
-  TileLoader ld;
+  TileLoaderN<NW> ld;
   ld.init(tstride, wave, lane);
 
   bf16x8 qf[D / 16];
@@ -296,7 +300,7 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
   const float sc2 = p.scale * kLog2e;
   const uint32_t rb = rows_base(lane), cb = cols_base(lane);
 
-  const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
+  const int kv_end = (qt * QB + QB < p.seq) ? qt * QB + QB : p.seq;
   const int ntile = (kv_end + TILE - 1) / TILE;
   ld.issue(rs, lds[0][0], 0, (int64_t)n * p.row + koff, wave);
   ld.issue(rs, lds[0][1], 0, (int64_t)n * p.row + voff, wave);
@@ -315,6 +319,8 @@ __global__ __launch_bounds__(256, 2) void flash_fwd_kernel(const FlashParams p) 
   wait_loads();
   fwd_finish(p, r, q, n, g, hh);
 }
+template __global__ void flash_fwd_kernel<4>(const FlashParams);
+template __global__ void flash_fwd_kernel<8>(const FlashParams);
 
 // The same for grids of at most one block per compute unit (short sequences, few heads), where the chain of tile
 // steps of the last query rows bounds the kernel: eight waves; waves w and w + 4 share a SIMD and 32 query rows
@@ -439,25 +445,27 @@ __device__ __forceinline__ void dq_tile(const char *kt, const char *vt, const bf
 
 // block = 128 query rows (tile qt) of one (batch entry, query head), four waves; lds: [stage][K, V] tiles, 64 KB.
 // In a block of eight waves the other four only keep the barrier count (one barrier per key tile).
+template <int NW = 4>
 __device__ __forceinline__ void dq_block(const FlashParams &p, char *lds_base, int qt, int g, int n) {
   char (*lds)[2][TILE_BYTES] = reinterpret_cast<char (*)[2][TILE_BYTES]>(lds_base);
+  constexpr int QB = 32 * NW;  // query rows of the block (NW = 8: see the forward kernel)
   const int kap = g / (p.nq / p.nkv);
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  if (wave >= 4) {
-    const int kv_end_x = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
+  if (wave >= NW) {
+    const int kv_end_x = (qt * QB + QB < p.seq) ? qt * QB + QB : p.seq;
     const int ntile_x = (kv_end_x + TILE - 1) / TILE;
     for (int jt = 0; jt < ntile_x; ++jt) __builtin_amdgcn_s_barrier();
     return;
   }
   const int l32 = lane & 31, hh = lane >> 5;
-  const int q0w = qt * 128 + wave * 32;
+  const int q0w = qt * QB + wave * 32;
   const int q = q0w + l32;
   const bool qvalid = q < p.seq;
   const int64_t tstride = (int64_t)p.batch * p.row;
   const int koff = p.nq * D + kap * D, voff = (p.nq + p.nkv) * D + kap * D;
   const int64_t cstride = (int64_t)p.batch * p.nq * D;
   const rsrc_t rs = make_rsrc(p.qkv, p.qkv_bytes);
-  TileLoader ld;
+  TileLoaderN<NW> ld;
   ld.init(tstride, wave, lane);
 
   bf16x8 qf[D / 16], dof[D / 16];
@@ -475,7 +483,7 @@ __device__ __forceinline__ void dq_block(const FlashParams &p, char *lds_base, i
   const float sc2 = p.scale * kLog2e;
   const uint32_t rb = rows_base(lane), cb = cols_base(lane);
 
-  const int kv_end = (qt * 128 + 128 < p.seq) ? qt * 128 + 128 : p.seq;
+  const int kv_end = (qt * QB + QB < p.seq) ? qt * QB + QB : p.seq;
   const int ntile = (kv_end + TILE - 1) / TILE;
   ld.issue(rs, lds[0][0], 0, (int64_t)n * p.row + koff, wave);
   ld.issue(rs, lds[0][1], 0, (int64_t)n * p.row + voff, wave);
@@ -494,10 +502,13 @@ __device__ __forceinline__ void dq_block(const FlashParams &p, char *lds_base, i
   wait_loads();
   if (qvalid) store_transposed(acc, p.scale, p.dqkv + ((int64_t)q * p.batch + n) * p.row + g * D, hh);
 }
-__global__ __launch_bounds__(256, 2) void flash_bwd_dq_kernel(const FlashParams p) {
+template <int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void flash_bwd_dq_kernel(const FlashParams p) {
   __shared__ __align__(1024) char lds[4 * TILE_BYTES];
-  dq_block(p, lds, gridDim.z - 1 - blockIdx.z, blockIdx.x, blockIdx.y);  // heads fastest, longest walks first
+  dq_block<NW>(p, lds, gridDim.z - 1 - blockIdx.z, blockIdx.x, blockIdx.y);  // heads fastest, longest walks first
 }
+template __global__ void flash_bwd_dq_kernel<4>(const FlashParams);
+template __global__ void flash_bwd_dq_kernel<8>(const FlashParams);
 
 // =================================================================================================
 // dK, dV: block = 128 key rows of one (batch entry, query head), eight waves: wave = 32 key rows x one 32-query
@@ -669,7 +680,7 @@ __global__ __launch_bounds__(512, 1) void flash_bwd_dkv_kernel(const FlashParams
 __global__ __launch_bounds__(512, 1) void flash_bwd_both_kernel(const FlashParams p) {
   extern __shared__ __align__(1024) char smem[];
   const int rank = blockIdx.z >> 1, tiles = gridDim.z >> 1;
-  if (blockIdx.z & 1) dq_block(p, smem, tiles - 1 - rank, blockIdx.x, blockIdx.y);
+  if (blockIdx.z & 1) dq_block<4>(p, smem, tiles - 1 - rank, blockIdx.x, blockIdx.y);
   else dkv_block(p, smem, rank, blockIdx.x, blockIdx.y);
 }
 
@@ -729,6 +740,17 @@ static bool use_split(dim3 grid) {
   return (int64_t)grid.x * grid.y * grid.z <= units;
 }
 
+// Blocks of 256 query rows (eight waves) for the forward and dQ walks of grids that still give every compute unit two
+// such blocks.  TM_ATTN_WIDE=0 / 1 forces the choice.
+static bool use_wide(int64_t seq, int64_t batch, int64_t nq) {
+  if (const char *e = getenv("TM_ATTN_WIDE")) return e[0] == '1';
+  int dev = 0, units = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+      units <= 0)
+    units = 256;
+  return ceil_div(seq, 256) * batch * nq >= 2 * (int64_t)units;
+}
+
 // One launch for both backward kernels where neither fills the chip by itself.  TM_ATTN_BWD_BOTH=0 / 1 forces the choice.
 static bool use_both(dim3 grid) {
   if (const char *e = getenv("TM_ATTN_BWD_BOTH")) return e[0] == '1';
@@ -768,7 +790,10 @@ int attn_fwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
     flash_fwd_split_kernel<<<grid, 512, lds, s>>>(p);
   } else {
     g_last_kernel = "flash_fwd_kernel";
-    flash_fwd_kernel<<<grid, 256, 0, s>>>(p);
+    if (use_wide(seq, batch, nq))
+      flash_fwd_kernel<8><<<dim3((unsigned)nq, (unsigned)batch, (unsigned)ceil_div(seq, 256)), 512, 0, s>>>(p);
+    else
+      flash_fwd_kernel<4><<<grid, 256, 0, s>>>(p);
   }
   return check_launch("flash_fwd");
 }
@@ -809,7 +834,10 @@ int attn_bwd_mfma_launch(int64_t seq, int64_t batch, int64_t nq, int64_t nkv, in
     g_last_kernel = "flash_bwd_both_kernel";
     flash_bwd_both_kernel<<<dim3((unsigned)nq, (unsigned)batch, 2 * tiles), 512, lds, s>>>(p);
   } else {
-    flash_bwd_dq_kernel<<<gq, 256, 0, s>>>(p);
+    if (use_wide(seq, batch, nq))
+      flash_bwd_dq_kernel<8><<<dim3((unsigned)nq, (unsigned)batch, (unsigned)ceil_div(seq, 256)), 512, 0, s>>>(p);
+    else
+      flash_bwd_dq_kernel<4><<<gq, 256, 0, s>>>(p);
     flash_bwd_dkv_kernel<<<gq, 512, lds, s>>>(p);
   }
   if (p.part) {

@@ -459,6 +459,49 @@ def test_attention_backward_launch_forms(env, monkeypatch, both, seq, batch, nq,
     assert rel_err(got[..., A + nkv * d:], dv.reshape(seq, batch, -1)) <= tol
 
 
+@pytest.mark.parametrize("seq,batch,nq,nkv", [(700, 1, 3, 3), (300, 2, 4, 2), (257, 1, 2, 1), (1, 1, 1, 1)],
+                         ids=["ragged_3_blocks", "grouped_heads", "one_row_past_a_block", "one_position"])
+def test_attention_blocks_of_256_query_rows(env, monkeypatch, seq, batch, nq, nkv):
+    """Long sequences run the forward and the dQ walk in blocks of 256 query rows (eight waves sharing every staged key /
+    value tile).  TM_ATTN_WIDE=1 forces that form on small shapes (with the other forms switched off): against the
+    checker, and nothing written past the last row."""
+    torch, tm = env
+    monkeypatch.setenv("TM_ATTN_WIDE", "1")
+    monkeypatch.setenv("TM_ATTN_SPLIT", "0")
+    monkeypatch.setenv("TM_ATTN_BWD_BOTH", "0")
+    d, dtype = 128, BF16
+    print(f"attention 256-row blocks seq={seq} batch={batch} nq={nq} nkv={nkv}", flush=True)
+    rng = np.random.default_rng(seq * 13 + nq)
+    A, W = nq * d, (nq + 2 * nkv) * d
+    qkv = rand(rng, (seq, batch, W), 1.0, dtype)
+    dctx = rand(rng, (seq, batch, A), 0.1, dtype)
+    s = stream_ptr(torch)
+    qd = to_dev(torch, qkv, dtype)
+    guard = 64
+    ctx = torch.full((seq + guard, batch, A), float("nan"), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((batch, nq, seq), dtype=torch.float32, device="cuda")
+    tm.tm_op_attn_fwd(dtype, seq, batch, nq, nkv, d, qd, ctx[:seq], lse, s)
+    q64 = qkv.astype(np.float64)
+    q = q64[..., :A].reshape(seq, batch, nq, d)
+    k = q64[..., A:A + nkv * d].reshape(seq, batch, nkv, d)
+    v = q64[..., A + nkv * d:].reshape(seq, batch, nkv, d)
+    tol = tol_of(dtype)
+    torch.cuda.synchronize()
+    assert torch.isnan(ctx[seq:]).all()
+    assert rel_err(to_host(ctx[:seq]), so.attention_fwd(q, k, v).reshape(seq, batch, A)) <= tol
+    dqkv = torch.full((seq + guard, batch, W), float("nan"), dtype=torch.bfloat16, device="cuda")
+    scratch = torch.empty(tm.tm_op_attn_bwd_scratch_bytes(dtype, seq, batch, nq, nkv, d), dtype=torch.uint8, device="cuda")
+    tm.tm_op_attn_bwd(dtype, seq, batch, nq, nkv, d, qd, ctx[:seq], to_dev(torch, dctx, dtype), lse, scratch, dqkv[:seq], s)
+    torch.cuda.synchronize()
+    assert torch.isnan(dqkv[seq:]).all()
+    dq, dk, dv = so.attention_bwd(dctx.astype(np.float64).reshape(seq, batch, nq, d), q, k, v)
+    got = to_host(dqkv[:seq])
+    assert np.isfinite(got).all()
+    assert rel_err(got[..., :A], dq.reshape(seq, batch, A)) <= tol
+    assert rel_err(got[..., A:A + nkv * d], dk.reshape(seq, batch, -1)) <= tol
+    assert rel_err(got[..., A + nkv * d:], dv.reshape(seq, batch, -1)) <= tol
+
+
 def test_attention_is_bit_reproducible(env):
     torch, tm = env
     rng = np.random.default_rng(8)
