@@ -78,7 +78,26 @@ struct MfmaGemmParams {
   int tiles_m, tiles_n;
   uint32_t a_bytes, b_bytes, c_bytes;  // extents of the tensors, for the buffer descriptors
   AdamTarget adam;                     // EPI 3 only
+  int stagger_ticks, stagger_phases, stagger_blocks;  // EPI 3 only, see stagger_by_unit(); 0 ticks: off
 };
+
+// The fused-update product runs in two phases per tile: the main loop, which pulls operands through the compute unit's
+// memory path at the rate that path allows, and the update, which streams 26 bytes per parameter of optimizer state
+// and is bound by HBM when every unit of the chip streams at once.  With one large block per unit, launched together,
+// all units are in the same phase: HBM idles during the main loops and is oversubscribed during the updates.  The
+// first block on each unit is therefore held back by a delay that depends on the unit (its identity in the hardware
+// registers: XCC, shader engine, array, unit): half of the units start one main loop late, so that at any time about
+// half of the chip streams, at twice the share of HBM, while the other half multiplies.  Blocks that start later
+// inherit the phase of the block whose place they take.  (With two small blocks per unit the same offsets gain
+// nothing: that form is bound by the unit's memory path in both phases.)
+__device__ __forceinline__ void stagger_by_unit(int ticks, int phases) {
+  unsigned hw, xcc;
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID, 8, 8)" : "=s"(hw));  // cu_id [3:0], sh_id [4], se_id [7:5]
+  asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
+  const unsigned phase = ((hw & 15) + (hw >> 4) + xcc) % (unsigned)phases;
+  const uint64_t wait = (uint64_t)ticks * phase / (unsigned)phases, t0 = wall_clock64();
+  while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(32);  // the clock only moves forward: ends
+}
 
 // Block id -> output tile.  Hardware block ids go round-robin over the 8 XCDs; ids are first
 // re-numbered so that each XCD owns a contiguous range, then the range is walked in groups of
@@ -117,6 +136,49 @@ template <int EPI> __device__ __forceinline__ f32x16 mfma_for(bf16x8 a, bf16x8 b
 
 // VB: accumulator registers of a 32x32 tile whose state reads are in flight together in the update epilogue (EPI 3):
 // all sixteen where a wave has 256 registers, eight where three waves share a SIMD's register file
+// The update of one 32x32 accumulator tile (EPI 3): register v of lane l holds the gradient of row row0 + 8(v/4) + 4hh + v%4,
+// column col.  All 48 state reads of the tile are in flight together; gradient (if stored), state and the bf16 copy
+// are streamed past the caches.
+struct AdamRsrc {
+  rsrc_t rc, rp, rm, rv, rl;
+};
+__device__ __forceinline__ AdamRsrc adam_rsrc(const MfmaGemmParams &p) {
+  return AdamRsrc{make_rsrc(p.C, p.c_bytes), make_rsrc(p.adam.master, p.c_bytes), make_rsrc(p.adam.exp_avg, p.c_bytes),
+                  make_rsrc(p.adam.exp_avg_sq, p.c_bytes), make_rsrc(p.adam.lowp, p.c_bytes / 2)};
+}
+__device__ __forceinline__ void adam_tile(const MfmaGemmParams &p, const AdamRsrc &r, const f32x16 &g, int row0, int col, int hh) {
+  constexpr int kNonTemporal = 2;
+  uint32_t off[16];
+  float pw[16], mw[16], vw[16];
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const int row = row0 + 8 * (v >> 2) + 4 * hh + (v & 3);
+    off[v] = col < p.N ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    pw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r.rp, off[v], 0, kNonTemporal));
+    mw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r.rm, off[v], 0, kNonTemporal));
+    vw[v] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r.rv, off[v], 0, kNonTemporal));
+  }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) {
+    const float gv = g[v];
+    adam_one(pw[v], gv, mw[v], vw[v], p.adam.a);
+    if (p.adam.store_grad)
+      __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, gv), r.rc, off[v], 0, kNonTemporal);
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, pw[v]), r.rp, off[v], 0, kNonTemporal);
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, mw[v]), r.rm, off[v], 0, kNonTemporal);
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, vw[v]), r.rv, off[v], 0, kNonTemporal);
+    const bf16 lo = (bf16)pw[v];
+    __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, lo), r.rl,
+                                          off[v] != 0xfffffff0u ? off[v] >> 1 : 0xfffffff0u, 0, kNonTemporal);
+  }
+}
+
+#ifndef TM_LDW_VB
+#define TM_LDW_VB 12
+#endif
 template <int TM, int TN, int EPI, int VB = 16>
 __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (&acc)[TM][TN], int row_base,
                                          int col_base, int l32, int hh) {
@@ -128,42 +190,40 @@ __device__ __forceinline__ void epilogue(const MfmaGemmParams &p, const f32x16 (
     const rsrc_t rc = make_rsrc(p.C, p.c_bytes);
     const rsrc_t rp = make_rsrc(p.adam.master, p.c_bytes), rm = make_rsrc(p.adam.exp_avg, p.c_bytes);
     const rsrc_t rv = make_rsrc(p.adam.exp_avg_sq, p.c_bytes), rl = make_rsrc(p.adam.lowp, p.c_bytes / 2);
+    constexpr int NACC = TM * TN * 16;  // the wave's accumulator registers, walked tile by tile in batches of VB
+    static_assert(NACC % VB == 0, "whole batches");
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+    for (int f0 = 0; f0 < NACC; f0 += VB) {
+      uint32_t off[VB];
+      float pw[VB], mw[VB], vw[VB];
 #pragma unroll
-      for (int j = 0; j < TN; ++j)
+      for (int u = 0; u < VB; ++u) {
+        const int f = f0 + u, i = f / (TN * 16), j = (f / 16) % TN, v = f % 16;
+        const int col = col_base + j * 32 + l32;
+        const int row = row_base + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+        off[u] = col < p.N ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
+      }
 #pragma unroll
-        for (int v0 = 0; v0 < 16; v0 += VB) {
-          const int col = col_base + j * 32 + l32;
-          const bool col_ok = col < p.N;
-          uint32_t off[VB];
-          float pw[VB], mw[VB], vw[VB];
+      for (int u = 0; u < VB; ++u) {
+        pw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rp, off[u], 0, kNonTemporal));
+        mw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off[u], 0, kNonTemporal));
+        vw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, off[u], 0, kNonTemporal));
+      }
 #pragma unroll
-          for (int u = 0; u < VB; ++u) {
-            const int v = v0 + u;
-            const int row = row_base + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-            off[u] = col_ok ? (uint32_t)(((int64_t)row * p.ldc + col) * 4) : 0xfffffff0u;
-          }
-#pragma unroll
-          for (int u = 0; u < VB; ++u) {
-            pw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rp, off[u], 0, kNonTemporal));
-            mw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rm, off[u], 0, kNonTemporal));
-            vw[u] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rv, off[u], 0, kNonTemporal));
-          }
-#pragma unroll
-          for (int u = 0; u < VB; ++u) {
-            const float g = acc[i][j][v0 + u];
-            adam_one(pw[u], g, mw[u], vw[u], p.adam.a);
-            if (p.adam.store_grad)
-              __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, g), rc, off[u], 0, kNonTemporal);
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, pw[u]), rp, off[u], 0, kNonTemporal);
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, mw[u]), rm, off[u], 0, kNonTemporal);
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, vw[u]), rv, off[u], 0, kNonTemporal);
-            const bf16 lo = (bf16)pw[u];
-            __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, lo), rl, col_ok ? off[u] >> 1 : 0xfffffff0u, 0,
-                                                  kNonTemporal);
-          }
-        }
+      for (int u = 0; u < VB; ++u) {
+        const int f = f0 + u;
+        const float g = acc[f / (TN * 16)][(f / 16) % TN][f % 16];
+        adam_one(pw[u], g, mw[u], vw[u], p.adam.a);
+        if (p.adam.store_grad)
+          __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, g), rc, off[u], 0, kNonTemporal);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, pw[u]), rp, off[u], 0, kNonTemporal);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, mw[u]), rm, off[u], 0, kNonTemporal);
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned int, vw[u]), rv, off[u], 0, kNonTemporal);
+        const bf16 lo = (bf16)pw[u];
+        __builtin_amdgcn_raw_buffer_store_b16(__builtin_bit_cast(unsigned short, lo), rl,
+                                              off[u] != 0xfffffff0u ? off[u] >> 1 : 0xfffffff0u, 0, kNonTemporal);
+      }
+    }
     return;
   }
   if constexpr (EPI != 0) {
@@ -656,6 +716,9 @@ template <int BM, int BN, int BK, int WGM, int WGN, int NP, bool A_KC, bool B_KC
 __global__ __launch_bounds__(64 * (WGM * WGN + NP), 3) void gemm_ldw_kernel(const MfmaGemmParams p_in) {
   extern __shared__ __align__(16) char lds[];
   MfmaGemmParams p = p_in;
+  if constexpr (EPI == 3) {
+    if (p_in.stagger_ticks > 0 && (int)blockIdx.x < p_in.stagger_blocks) stagger_by_unit(p_in.stagger_ticks, p_in.stagger_phases);
+  }
   if (gridDim.y > 1) {  // split reduction: this block row takes one part of K and writes its own result
     const int part = p.K / (int)gridDim.y, first = (int)blockIdx.y * part;
     const int64_t a_skip = A_KC ? (int64_t)first : (int64_t)first * p.lda;
@@ -677,6 +740,9 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP), 3) void gemm_ldw_kernel(cons
   static_assert(KS % 2 == 0, "fragment buffers alternate");
   constexpr int MF = TM * TN;
   constexpr int DSN = TM * (A_KC ? 1 : 2) + TN * (B_KC ? 1 : 2);
+  // EPI 3 with eight multiplying waves and four loaders: HAND accumulator tiles per multiplying wave are updated by the loaders
+  constexpr int HAND = 2;
+  constexpr bool HANDOFF = EPI == 3 && NC == 8 && NP == 4 && MF == 6 && NC * HAND * 16 * 64 * 4 <= 2 * (BM + BN) * BK * 2;
 
   int m0, n0;
   tile_of_block(p, BM, BN, m0, n0);
@@ -715,6 +781,23 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP), 3) void gemm_ldw_kernel(cons
       __syncthreads();  // the multiplying waves add their accumulators in between
       __syncthreads();
       epilogue_lds_copy<BM, BN, NC + NP>(p, lds, m0, n0, /*residual_in=*/false);
+    }
+    if constexpr (HANDOFF) {
+      // the update of a third of the tile: two of every multiplying wave's six accumulator tiles come through LDS, so
+      // that all twelve waves of the block stream optimizer state
+      __syncthreads();  // the stages are free
+      __syncthreads();  // the accumulator tiles are in LDS
+      const AdamRsrc r = adam_rsrc(p);
+      const float *h = reinterpret_cast<const float *>(lds);
+#pragma unroll
+      for (int q = 0; q < HAND * NC / NP; ++q) {
+        const int slot = lw * (HAND * NC / NP) + q, cw = slot / HAND, f = MF - HAND + slot % HAND;
+        const int i = f / TN, j = f % TN;
+        f32x16 gacc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) gacc[v] = h[(slot * 16 + v) * 64 + lane];
+        adam_tile(p, r, gacc, m0 + (cw / WGN) * WM + i * 32, n0 + (cw % WGN) * WN + j * 32 + (lane & 31), lane >> 5);
+      }
     }
     return;
   }
@@ -778,8 +861,23 @@ __global__ __launch_bounds__(64 * (WGM * WGN + NP), 3) void gemm_ldw_kernel(cons
     epilogue_lds_acc<BM, BN, TM, TN>(p, acc, lds, n0, wm * WM, wn * WN, lane);
     __syncthreads();
     epilogue_lds_copy<BM, BN, NC + NP>(p, lds, m0, n0, /*residual_in=*/false);
+  } else if constexpr (HANDOFF) {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __syncthreads();  // the loaders' last loads have landed and every fragment read is done: the stages are free
+    float *h = reinterpret_cast<float *>(lds);
+#pragma unroll
+    for (int t = 0; t < HAND; ++t) {
+      const int f = MF - HAND + t, slot = wave * HAND + t;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) h[(slot * 16 + v) * 64 + lane] = acc[f / TN][f % TN][v];
+    }
+    __syncthreads();
+    const AdamRsrc r = adam_rsrc(p);
+#pragma unroll
+    for (int f = 0; f < MF - HAND; ++f)
+      adam_tile(p, r, acc[f / TN][f % TN], m0 + wm * WM + (f / TN) * 32, n0 + wn * WN + (f % TN) * 32 + (lane & 31), lane >> 5);
   } else {
-    epilogue<TM, TN, EPI, 8>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
+    epilogue<TM, TN, EPI, TM_LDW_VB>(p, acc, m0 + wm * WM, n0 + wn * WN, lane & 31, lane >> 5);
   }
 }
 
@@ -1088,7 +1186,30 @@ template <bool A_KC, bool B_KC, int EPI> static MfmaGemmParams make_params(const
   p.b_bytes = (uint32_t)((B_KC ? g.N * g.b_rs : g.K * g.b_cs) * 2);
   p.c_bytes = (uint32_t)(g.M * g.ldc * (EPI == 0 ? 2 : 4));
   if (EPI == 3 && g.adam) p.adam = *g.adam;
+  p.stagger_ticks = p.stagger_phases = p.stagger_blocks = 0;
   return p;
+}
+// Start offsets for a fused-update product on one large block per compute unit (see stagger_by_unit): two groups of
+// units, the second one main loop late (a 256x192 tile at about 4.5 TFLOP/s a unit).  TM_GEMM_STAGGER_US overrides the
+// span (twice the delay of the second group; 0 switches the offsets off), TM_GEMM_STAGGER_PHASES the number of groups.
+static void stagger_of(MfmaGemmParams &p, int BM, int BN, int64_t nblk) {
+  static int cus = 0, khz = 0, phases = 2;
+  static double forced = -1.0;
+  if (!cus) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || cus <= 0 || khz <= 0)
+      cus = -1;
+    if (const char *e = getenv("TM_GEMM_STAGGER_US")) forced = atof(e);
+    if (const char *e = getenv("TM_GEMM_STAGGER_PHASES")) phases = atoi(e) > 1 ? atoi(e) : 2;
+  }
+  if (cus <= 0 || nblk < 2 * (int64_t)cus) return;
+  const double main_loop_us = 2.0 * BM * BN * (double)p.K / 4.5e6;
+  const double us = forced >= 0.0 ? forced : 2.0 * main_loop_us;
+  if (us <= 0.0) return;
+  p.stagger_ticks = (int)(us * khz * 1e-3);
+  p.stagger_phases = phases;
+  p.stagger_blocks = cus;
 }
 
 static std::string kernel_tag(const char *base, int bm, int bn, int wgm, int wgn, bool akc, bool bkc, int epi) {
@@ -1146,7 +1267,8 @@ static int launch_alt(const GemmArgs &g, hipStream_t s) {
 template <int BM, int BN, int WGM, int WGN, int NP, bool A_KC, bool B_KC, int EPI>
 static int launch_ldw(const GemmArgs &g, hipStream_t s) {
   constexpr int BK = GEMM_BK;
-  const MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, BM, BN);
+  MfmaGemmParams p = make_params<A_KC, B_KC, EPI>(g, BM, BN);
+  if (EPI == 3 && NP == 4) stagger_of(p, BM, BN, (int64_t)p.tiles_m * p.tiles_n);
   constexpr int lds_bytes = 2 * (BM + BN) * BK * 2 > BM * BN * 2 ? 2 * (BM + BN) * BK * 2 : BM * BN * 2;
   static_assert(lds_bytes <= 160 * 1024, "LDS");
   static bool attr_set = false;  // per instantiation
