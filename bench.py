@@ -40,8 +40,8 @@ def recorded_traffic(kernel: str):
     import re
     for path in glob.glob(os.path.join(ROOT, "profiles", "*traffic*.txt")):
         text = open(path).read()
-        m = re.search(r"^kernel:\s*(\S+)", text, re.M)
-        if not m or not kernel.startswith(m.group(1)):
+        m = re.search(r"^kernel:\s*(.+?)\s*$", text, re.M)
+        if not m or kernel != m.group(1):
             continue
         src = re.search(r"^source:\s*(\S+)\s+sha256:\s*([0-9a-f]+)", text, re.M)
         val = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", text, re.M)
