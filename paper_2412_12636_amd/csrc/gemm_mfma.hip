@@ -101,9 +101,10 @@ int gemm_mfma_force_config(int index) {
 }
 
 // Configurations found by gemm_mfma_tune(), keyed by (layout, M, N, K).  A weight-gradient product that also applies
-// the update (c_mode 3) spends most of its time in the epilogue, streaming the optimizer state; it is faster with
-// two small blocks per compute unit (one multiplies while the other streams) than with one large block, so it keeps
-// the best of the configurations that allow two blocks: layout key 3.
+// the update (c_mode 3) spends most of its time in the epilogue, streaming the optimizer state.  Where the large
+// staggered form does not apply (fused_on_large_tiles below) it is faster with two small blocks per compute unit than
+// with one large block whose units all stream at once, so it keeps the best of the configurations that allow two
+// blocks: layout key 3.
 typedef std::tuple<int, int64_t, int64_t, int64_t> TuneKey;
 static std::map<TuneKey, int> g_tuned;
 static std::mutex g_tuned_mutex;
