@@ -170,9 +170,15 @@ def test_tuning_changes_speed_only(env):
     st.close()
 
 
+# FC matrices of 4104 x 6152 and 6152 x 4104: 17 x 33 and 25 x 22 tiles of 256 x 192 with ragged last tiles, enough of
+# them for the update products' large staggered form; 64 tokens are a single reduction step, 192 are three
+WIDE_RAGGED = si.StageConfig(1, 6152, 2, 2, 128, 4104, 64, 1)
+
+
 @pytest.mark.parametrize("cfg", [SMALL_GPT.replace(n_layers=3), SMALL_GPT.replace(n_layers=3, seq=192),
-                                 SMALL_LLAMA.replace(n_layers=2, seq=256), TINY],
-                         ids=["ragged_tokens_flat_sweep", "fused_into_the_products", "fused_llama", "fp32_flat_sweep"])
+                                 SMALL_LLAMA.replace(n_layers=2, seq=256), TINY, WIDE_RAGGED, WIDE_RAGGED.replace(seq=192)],
+                         ids=["ragged_tokens_flat_sweep", "fused_into_the_products", "fused_llama", "fp32_flat_sweep",
+                              "fused_large_staggered_ragged_one_step", "fused_large_staggered_ragged_three_steps"])
 def test_backward_with_overlapped_optimizer_equals_the_two_calls(env, cfg):
     """tm_stage_bwd_adam = tm_stage_bwd then tm_adam_step, bit for bit: gradients, master weights, both moments, the
     bf16 copy, the input gradient; two iterations, so that the second forward pass sees updated weights.  With a
